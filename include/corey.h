@@ -1,0 +1,169 @@
+/*
+ * corey.h -- C ABI of libcorey: the COREY hot path on one AMD MI355X (gfx950).
+ *
+ * Three operations, named after the paper's statement of the problem (its inline scheduling hook runs
+ * them in this order on every Mamba layer: statistic of the post-convolution tensor u -> chunk -> scan
+ * with that chunk, "Active-Mode Overhead Budget", steps (2)-(4)):
+ *
+ *   corey_entropy_hist   fixed-bin histogram of a tensor, its Shannon entropy H (Eq. 1) and the
+ *                        normalised signal r = H / log K (Method, Preliminaries).
+ *   corey_select_chunk   the entropy-to-chunk rule (Eq. 2) and the scheduler family around it
+ *                        (sequence-length table, guarded fallback, static chunk).
+ *   selective_scan_fwd   the Mamba-1 selective-scan forward with a run-time chunk (the
+ *                        recurrence-preserving runtime-chunk scan of "End-to-End Routed Inference").
+ *
+ * Conventions common to all calls
+ *   - Plain C: no C++ types, no exceptions cross the boundary.  Every function returns a corey_status;
+ *     0 is success.  corey_last_error() gives a thread-local message for the last failure.
+ *   - Pointers marked DEVICE point to GPU global memory owned by the caller; HOST pointers to ordinary
+ *     memory.  The library never frees or keeps caller memory and allocates nothing itself.
+ *   - GPU work is enqueued on the HIP stream passed as `hip_stream` (a hipStream_t cast to void*; NULL is
+ *     the default stream) and the call returns without synchronising.  Argument errors are detected on
+ *     the host before anything is launched; outputs are then untouched.
+ *   - Tensors are dense and row-major with the last index contiguous.  Activation tensors (x, u, delta,
+ *     z, y) are [B, D, L] (batch, channel, time); Bm and Cm are [B, N, L]; A is [D, N].
+ *   - Calls are thread-safe; two calls that share an output or workspace buffer must be ordered by the
+ *     caller (same stream, or events).
+ */
+#ifndef COREY_H
+#define COREY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    COREY_F32 = 0,   /* IEEE binary32 storage                                 */
+    COREY_BF16 = 1   /* bfloat16 storage; all arithmetic and the state are fp32 */
+} corey_dtype;
+
+typedef enum {
+    COREY_OK = 0,
+    COREY_EINVAL = 1,       /* a size, flag or enum is out of range                          */
+    COREY_ENULL = 2,        /* a required pointer is NULL                                    */
+    COREY_ESHAPE = 3,       /* sizes are inconsistent or exceed what the kernels index       */
+    COREY_ENONFINITE = 4,   /* r is NaN (the statistic saw a non-finite range)               */
+    COREY_EUNSUPPORTED = 5, /* valid request the library does not implement                  */
+    COREY_EHIP = 6,         /* a HIP runtime call failed (message in corey_last_error)       */
+    COREY_EWORKSPACE = 7    /* workspace missing or smaller than the query call says         */
+} corey_status;
+
+/* Limits the kernels are written for. */
+#define COREY_MAX_BINS 4096      /* K                      */
+#define COREY_MAX_STATE 256      /* N (d_state)            */
+#define COREY_MIN_CHUNK 16
+#define COREY_MAX_CHUNK 2048
+
+/* -------------------------------------------------------------------------------------------------------
+ * corey_entropy_hist -- Eq. 1 and r = H / log K.
+ *
+ * For one histogram over a set S of values: lo = min S, hi = max S (binary32); K equal-width bins on
+ * [lo, hi], half open, the last closed; p_k = count_k / |S|; H = -sum_k p_k log(p_k + eps) in nats;
+ * r = clamp(H / log K, 0, 1).  Bin index of a value v, stated to the rounding because counts are integers:
+ *     scale = (float)(K / ((double)hi - (double)lo));  k = min((int)((v - lo) * scale), K - 1)
+ * with the subtraction and the multiplication each one binary32 operation (no fused multiply-add).
+ * hi == lo puts every sample in bin 0.  If S is empty or its range is not finite (NaN or infinity in the
+ * input) the counts are zero and H and r are NaN.  binary32 subnormal inputs are outside the contract.
+ *
+ *   x           DEVICE, [B, D, L] in `dt`.
+ *   seqlens     DEVICE int32[B] or NULL.  NULL: one histogram over all B*D*L values (nh = 1).  Otherwise one
+ *               histogram per sequence b over the positions t < seqlens[b] of its D channels (nh = B);
+ *               0 <= seqlens[b] <= L is the caller's responsibility (values are clamped to [0, L]).
+ *   K           number of bins, 2 <= K <= COREY_MAX_BINS.   eps >= 0 (the paper's hook uses 1e-8).
+ *   stride      >= 1.  Number the values of one histogram in memory order j = 0, 1, ...; value j is used
+ *               iff j % stride == 0.  1 is the exact statistic; 8 is the paper's sampled variant.
+ *   counts_out  DEVICE uint32[nh * K].   H_out, r_out: DEVICE double[nh].
+ *   range_out   DEVICE float[nh * 2] (lo, hi per histogram) or NULL.
+ *   workspace   DEVICE, at least corey_entropy_hist_workspace(B, K) bytes, 256-byte aligned; scratch only,
+ *               contents are undefined afterwards.
+ * The work is two sweeps over x (range, then counts) plus an O(K) reduction, as the paper's protocol
+ * states; H is summed in double.  Counts are exact integers; H and r agree with a sequential double
+ * evaluation to summation-order rounding (about 1e-15 relative).
+ * ----------------------------------------------------------------------------------------------------- */
+int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
+                       const int32_t* seqlens, int32_t K, double eps, int64_t stride,
+                       uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace corey_entropy_hist needs for batch B and K bins (0 if the arguments are invalid). */
+size_t corey_entropy_hist_workspace(int64_t B, int32_t K);
+
+/* -------------------------------------------------------------------------------------------------------
+ * corey_select_chunk -- Eq. 2:  C = clip(2^round(log2(c_min + r (c_max - c_min))), c_min, c_max).
+ *
+ * Pure host function (HOST pointers, no GPU work), evaluated in double; round(v) = floor(v + 0.5).
+ *   mode 0  entropy rule.
+ *   mode 1  sequence-length gate, then entropy rule: L <= short_len returns short_chunk.
+ *   mode 2  sequence-length table only: L <= short_len -> short_chunk, else long_chunk
+ *           (the paper's learned table: <= 50 tokens -> 128, otherwise 512).
+ *   mode 3  static_chunk.
+ *   mode 4  guarded entropy rule: the prediction is kept only if it is at least guard_buckets powers of
+ *           two away from safe_chunk, else safe_chunk (the paper's guard: 512, two buckets).
+ * r is first multiplied by h_ref_scale and clamped to [0, 1]: 1.0 is the calibrated reference
+ * H_ref = log K; log(K)/8 gives the legacy H_ref = 8 nats.
+ * Eq. 2's own result is finally capped at the smallest power of two >= L (never below c_min), since a
+ * larger tile cannot be filled; table and static values are returned as given.
+ * Errors: COREY_ENULL; COREY_EINVAL for L < 1, a chunk field that is not a power of two, c_min > c_max or
+ * an unknown mode; COREY_ENONFINITE if r is NaN in an entropy mode.
+ * ----------------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t mode;
+    int32_t c_min, c_max;        /* library default 64, 2048; Eq. 2 as printed uses 32, 512 */
+    double  h_ref_scale;
+    int32_t short_len, short_chunk, long_chunk;   /* 50, 128, 512 */
+    int32_t static_chunk;
+    int32_t safe_chunk, guard_buckets;            /* 512, 2 */
+} corey_policy;
+
+/* Fill *p with the defaults named above (mode 0). */
+int corey_policy_default(corey_policy* p);
+
+int corey_select_chunk(double r, int64_t L, const corey_policy* p, int32_t* chunk_out);
+
+/* -------------------------------------------------------------------------------------------------------
+ * selective_scan_fwd -- the recurrence h_t = A_t h_{t-1} + B_t x_t, y_t = C_t h_t + D_t x_t (Method,
+ * Preliminaries) in its Mamba-1 form, for every sequence b and channel d independently:
+ *
+ *     dl_t = delta[b,d,t] + delta_bias[d];   if delta_softplus: dl_t = log(1 + exp(dl_t))
+ *     h_t[n] = exp(dl_t * A[d,n]) * h_{t-1}[n] + dl_t * Bm[b,n,t] * u[b,d,t]          (h_{-1} = h0 or 0)
+ *     y[b,d,t] = sum_n Cm[b,n,t] * h_t[n] + Dv[d] * u[b,d,t];   if z: y *= z * sigmoid(z)
+ *
+ * The sequence is processed in tiles of `chunk` time steps per workgroup iteration with the fp32 state
+ * carried on chip from tile to tile; the result does not depend on `chunk` beyond floating-point
+ * reassociation (the paper's patched kernel is "recurrence-preserving").
+ *
+ *   u, delta, z, y   DEVICE [B, D, L] in `dt`; z may be NULL (no gate).
+ *   A                DEVICE float[D, N].     Bm, Cm: DEVICE [B, N, L] in `dt`.
+ *   Dv, delta_bias   DEVICE float[D] or NULL (treated as zeros).
+ *   h0               DEVICE float[B, D, N] or NULL (zero initial state).
+ *   seqlens          DEVICE int32[B] or NULL.  With seqlens, sequence b is scanned over t < seqlens[b];
+ *                    y is written as 0 for the padded positions and last_state is the state after the
+ *                    last valid step.
+ *   chunk            HOST value: power of two in [COREY_MIN_CHUNK, COREY_MAX_CHUNK].  chunk > L is legal.
+ *   chunks_dev       DEVICE int32[B] or NULL: per-sequence chunk (same constraints) that overrides `chunk`
+ *                    without a host round trip; out-of-range or non-power-of-two entries fall back to `chunk`.
+ *   last_state       DEVICE float[B, D, N], required.
+ *   1 <= N <= COREY_MAX_STATE;  B*D*L and B*N*L must fit in int64 and B*D in int32.
+ * y and last_state may not alias any input.  Accuracy against a double-precision evaluation of the same
+ * bits: about 1e-6 relative to the row's scale for fp32 storage; for bf16 storage y carries one bf16
+ * rounding (2^-9 relative) on top.
+ * ----------------------------------------------------------------------------------------------------- */
+int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
+                       const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
+                       const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
+                       void* y, float* last_state, corey_dtype dt,
+                       int64_t B, int64_t D, int64_t N, int64_t L, void* hip_stream);
+
+/* Message for the most recent failing call on this thread ("" if none).  Static storage; do not free. */
+const char* corey_last_error(void);
+
+/* Library version, "major.minor". */
+const char* corey_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COREY_H */

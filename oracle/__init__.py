@@ -1,0 +1,137 @@
+"""CPU oracle for the COREY hot path (test infrastructure only).
+
+Thin ctypes loader around ``corey_oracle.c``.  Only tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this package; the product package never does, and this package
+never imports the product.  All arithmetic lives in the C file; this module only marshals numpy
+arrays into it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "corey_oracle.c")
+_LIB = os.path.join(_HERE, "libcorey_oracle.so")
+
+OK, EINVAL, ENONFINITE = 0, 1, 4
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (double precision, no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fopenmp",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class Policy(ctypes.Structure):
+    """Mirror of ``oracle_policy`` (scheduler family around Eq. 2)."""
+    _fields_ = [("mode", ctypes.c_int32), ("c_min", ctypes.c_int32), ("c_max", ctypes.c_int32),
+                ("h_ref_scale", ctypes.c_double), ("short_len", ctypes.c_int32),
+                ("short_chunk", ctypes.c_int32), ("long_chunk", ctypes.c_int32),
+                ("static_chunk", ctypes.c_int32), ("safe_chunk", ctypes.c_int32),
+                ("guard_buckets", ctypes.c_int32)]
+
+
+def policy(mode=0, c_min=64, c_max=2048, h_ref_scale=1.0, short_len=50, short_chunk=128,
+           long_chunk=512, static_chunk=512, safe_chunk=512, guard_buckets=2) -> Policy:
+    return Policy(mode, c_min, c_max, h_ref_scale, short_len, short_chunk, long_chunk,
+                  static_chunk, safe_chunk, guard_buckets)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_entropy_hist.restype = ctypes.c_int
+        _lib.oracle_select_chunk.restype = ctypes.c_int
+        _lib.oracle_selective_scan.restype = ctypes.c_int
+        _lib.oracle_max_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _f32(a):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def entropy_hist(x, K, eps=1e-8, stride=1, seqlens=None):
+    """x: float array [B, D, L] (already widened).  Returns dict(status, counts, H, r, lo, hi)."""
+    x = np.asarray(x)
+    if x.ndim != 3:
+        raise ValueError("x must be [B, D, L]")
+    B, D, L = x.shape
+    xk, xp = _f32(x)
+    sk, sp = _i32(seqlens)
+    nh = B if seqlens is not None else 1
+    counts = np.zeros((nh, K), dtype=np.uint32)
+    H = np.zeros(nh, dtype=np.float64)
+    r = np.zeros(nh, dtype=np.float64)
+    lo = np.zeros(nh, dtype=np.float32)
+    hi = np.zeros(nh, dtype=np.float32)
+    st = lib().oracle_entropy_hist(
+        xp, ctypes.c_int64(B), ctypes.c_int64(D), ctypes.c_int64(L), sp, ctypes.c_int32(K),
+        ctypes.c_double(eps), ctypes.c_int64(stride),
+        counts.ctypes.data_as(ctypes.c_void_p), H.ctypes.data_as(ctypes.c_void_p),
+        r.ctypes.data_as(ctypes.c_void_p), lo.ctypes.data_as(ctypes.c_void_p),
+        hi.ctypes.data_as(ctypes.c_void_p))
+    return dict(status=st, counts=counts, H=H, r=r, lo=lo, hi=hi)
+
+
+def select_chunk(r, L, pol: Policy | None = None):
+    """Returns (status, chunk, margin)."""
+    pol = pol or policy()
+    chunk = ctypes.c_int32(0)
+    margin = ctypes.c_double(0.0)
+    st = lib().oracle_select_chunk(ctypes.c_double(r), ctypes.c_int64(L), ctypes.byref(pol),
+                                   ctypes.byref(chunk), ctypes.byref(margin))
+    return st, chunk.value, margin.value
+
+
+def selective_scan(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True,
+                   h0=None, seqlens=None, chunk=256, threads=1):
+    """All inputs float arrays (widened).  Returns (status, y float64 [B,D,L], last float64 [B,D,N])."""
+    u = np.asarray(u)
+    B, D, L = u.shape
+    A = np.asarray(A)
+    N = A.shape[1]
+    assert A.shape == (D, N)
+    assert np.asarray(Bm).shape == (B, N, L) and np.asarray(Cm).shape == (B, N, L)
+    keep = []
+    ptrs = []
+    for a in (u, delta, A, Bm, Cm, Dv, z, delta_bias):
+        k, p = _f32(a)
+        keep.append(k)
+        ptrs.append(p)
+    hk, hp = _f32(h0)
+    sk, sp = _i32(seqlens)
+    y = np.zeros((B, D, L), dtype=np.float64)
+    last = np.zeros((B, D, N), dtype=np.float64)
+    st = lib().oracle_selective_scan(
+        ptrs[0], ptrs[1], ptrs[2], ptrs[3], ptrs[4], ptrs[5], ptrs[6], ptrs[7],
+        ctypes.c_int(1 if delta_softplus else 0), hp, sp, ctypes.c_int64(chunk),
+        ctypes.c_int64(B), ctypes.c_int64(D), ctypes.c_int64(N), ctypes.c_int64(L),
+        y.ctypes.data_as(ctypes.c_void_p), last.ctypes.data_as(ctypes.c_void_p),
+        ctypes.c_int(threads))
+    return st, y, last
+
+
+def max_threads() -> int:
+    return lib().oracle_max_threads()
