@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the COREY hot path on one MI355X.
+
+One step = one pass of the whole path over one batch that already sits in HBM: corey_entropy_hist on u,
+a read of r, corey_select_chunk on the host, selective_scan_fwd with the routed chunk.  Prints ONE JSON line.
+
+  value      scan algorithmic bytes (u, delta, z in; y out; B, C, parameters, final state) per step time, GB/s
+  roofline   for the dominant kernel (the scan): algorithmic bytes / its own launch duration, measured with
+             events on the launch stream inside the timed region, against the 8 TB/s HBM peak; the `alu` block
+             beside it prices the same launches against the fp32 vector peak, which is the bound that binds
+  per_chunk  scan-only latency, GB/s and tokens/s for every chunk of the sweep
+  overhead   entropy + routing cost relative to the scan alone at the routed chunk
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload on this host's cores
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
+# HBM bytes per scan launch from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` (see profiles/); None until measured
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c4_mamba2p8b")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2604_10597_amd as corey
+    from paper_2604_10597_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    w = wl.make(cfg)
+
+    def dev(a):
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    d = {k: dev(v) for k, v in w.dev.items()}
+    seqlens = None if w.seqlens is None else torch.from_numpy(w.seqlens).cuda()
+    tokens = int(w.seqlens.sum()) if w.seqlens is not None else cfg.B * cfg.L
+    scan_bytes = wl.scan_bytes(cfg)
+    state_updates = cfg.D * cfg.N * tokens
+    # algorithmic flops per state update: 2 mul + 2 fma (6 flop) + 1 exp counted as one
+    scan_flop = 7.0 * state_updates
+
+    y = torch.empty_like(d["u"])
+    last = torch.empty((cfg.B, cfg.D, cfg.N), dtype=torch.float32, device="cuda")
+    ent = corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens)
+    pol = corey.policy_default()
+    r_pinned = torch.empty(ent["r"].shape, dtype=torch.float64).pin_memory()
+
+    def scan(chunk):
+        corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
+                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=chunk, y=y, last_state=last)
+
+    def route():
+        corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
+        r_pinned.copy_(ent["r"], non_blocking=True)
+        torch.cuda.current_stream().synchronize()              # the host needs r to pick the launch shape
+        Ls = w.seqlens if w.seqlens is not None else [cfg.L] * r_pinned.numel()
+        return max(corey.corey_select_chunk(float(r_pinned[i]), int(Ls[i]), pol) for i in range(r_pinned.numel()))
+
+    # ---- the timed region: K whole steps
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    for _ in range(args.warmup):
+        scan(route())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    chunk = None
+    for i in range(args.steps):
+        chunk = route()
+        ev0[i].record()
+        scan(chunk)
+        ev1[i].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    scan_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev0, ev1)]))
+
+    def time_scan(c, warm, reps):
+        for _ in range(warm):
+            scan(c)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            scan(c)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # ---- scan alone at the routed chunk (for the overhead figure) and the chunk sweep
+    scan_alone_ms = time_scan(chunk, 3, args.steps)
+    hist_a, hist_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    hist_a.record()
+    for _ in range(args.steps):
+        corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
+    hist_b.record()
+    torch.cuda.synchronize()
+    hist_ms = hist_a.elapsed_time(hist_b) / args.steps
+    per_chunk = {}
+    if not args.no_sweep:
+        for c in cfg.chunks:
+            ms = time_scan(c, 2, 10)
+            per_chunk[str(c)] = {"ms": round(ms, 4), "GBps": round(scan_bytes / ms * 1e-6, 1),
+                                 "tokens_per_s": round(tokens / ms * 1e3, 1),
+                                 "hbm_frac": round(scan_bytes / ms * 1e-6 / HBM_PEAK_GBPS, 4)}
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        cores = min(16, len(os.sched_getaffinity(0)))
+
+        def oracle_pass(nrows):
+            sel = np.linspace(0, cfg.D - 1, nrows).astype(np.int64)
+            p3 = lambda a: np.ascontiguousarray(a[:, sel, :])
+            t = time.perf_counter()
+            h = oracle.entropy_hist(p3(w.val["u"]), cfg.K, seqlens=w.seqlens)
+            Ls = w.seqlens if w.seqlens is not None else [cfg.L]
+            c = max(oracle.select_chunk(float(h["r"][i]), int(Ls[i]), oracle.policy())[1] for i in range(len(h["r"])))
+            oracle.selective_scan(p3(w.val["u"]), p3(w.val["delta"]), w.val["A"][sel], w.val["B"], w.val["C"],
+                                  Dv=w.val["D"][sel], z=p3(w.val["z"]), delta_bias=w.val["delta_bias"][sel],
+                                  seqlens=w.seqlens, chunk=c, threads=cores)
+            return time.perf_counter() - t
+
+        probe_rows = min(cfg.D, 2 * cores)
+        t_probe = oracle_pass(probe_rows)
+        nrows = int(min(cfg.D, max(probe_rows, probe_rows * args.cpu_seconds / max(t_probe, 1e-3))))
+        t_cpu = oracle_pass(nrows)
+        frac = nrows / cfg.D
+        cpu = {"value": round(scan_bytes * frac / t_cpu * 1e-9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+               "tokens_per_s": round(tokens * frac / t_cpu, 1), "seconds": round(t_cpu, 2),
+               "sample": f"{nrows} of {cfg.D} channels of {cfg.name} (all {tokens} tokens), histogram + chunk rule + scan, "
+                         f"double precision, OpenMP over channels"}
+
+    gbps = scan_bytes / scan_ms * 1e-6
+    out = {
+        "metric": "selective_scan_hbm_GBps", "value": round(scan_bytes / ms_step * 1e-6, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B{cfg.B} D{cfg.D} N{cfg.N} L{cfg.L}, {cfg.dtype} storage, fp32 state, "
+                               f"u {cfg.u_kind}, K={cfg.K}, routed chunk {chunk}",
+                   "scan_bytes": scan_bytes, "tokens": tokens},
+        "tokens_per_s": round(tokens / ms_step * 1e3, 1),
+        "routed_chunk": chunk, "r": [round(float(v), 6) for v in r_pinned],
+        "roofline": {"bound": "hbm", "kernel": "k_selective_scan", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": round(scan_ms, 4)},
+        "alu": {"achieved": round(scan_flop / scan_ms * 1e-9, 2), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(scan_flop / scan_ms * 1e-9 / FP32_VECTOR_PEAK_TFLOPS, 4),
+                "flop_per_state_update": 7, "state_updates": state_updates},
+        "overhead": {"entropy_routing_pct_of_scan": round((ms_step - scan_alone_ms) / scan_alone_ms * 100, 2),
+                     "hist_kernels_ms": round(hist_ms, 4), "scan_alone_ms": round(scan_alone_ms, 4),
+                     "hist_pct_of_scan": round(hist_ms / scan_alone_ms * 100, 2)},
+        "per_chunk": per_chunk,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

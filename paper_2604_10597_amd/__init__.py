@@ -1,0 +1,11 @@
+"""COREY hot path on AMD MI355X: entropy histogram, chunk rule and the Mamba-1 selective-scan forward.
+
+The work is done by hand-written HIP kernels in ``libcorey.so`` (sources under ``csrc/``, C ABI in
+``include/corey.h``); ``binding`` marshals torch GPU tensors into it.  Importing the package does not
+load the library; the first call does, and raises if it has not been built.
+"""
+from .binding import (CoreyError, Policy, corey_entropy_hist, corey_entropy_hist_workspace, corey_select_chunk,
+                      corey_version, policy_default, selective_scan_fwd)
+
+__all__ = ["CoreyError", "Policy", "corey_entropy_hist", "corey_entropy_hist_workspace", "corey_select_chunk",
+           "corey_version", "policy_default", "selective_scan_fwd"]

@@ -1,0 +1,161 @@
+"""ctypes binding of libcorey.so: argument marshalling only.
+
+Functions carry the names of the C entry points (include/corey.h).  Device buffers are torch tensors
+(torch is used for GPU memory and streams, nothing else); every step of the path runs in the library's
+HIP kernels.  There is no fallback: if the library is missing or fails to load, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcorey.so")
+
+COREY_F32, COREY_BF16 = 0, 1
+STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
+          5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
+EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
+           "selective_scan_fwd", "corey_last_error", "corey_version")
+
+
+class CoreyError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class Policy(ctypes.Structure):
+    """corey_policy"""
+    _fields_ = [("mode", ctypes.c_int32), ("c_min", ctypes.c_int32), ("c_max", ctypes.c_int32),
+                ("h_ref_scale", ctypes.c_double), ("short_len", ctypes.c_int32), ("short_chunk", ctypes.c_int32),
+                ("long_chunk", ctypes.c_int32), ("static_chunk", ctypes.c_int32), ("safe_chunk", ctypes.c_int32),
+                ("guard_buckets", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcorey.so (built in-tree by build.py); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, dbl = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_double
+        L.corey_entropy_hist.restype = ctypes.c_int
+        L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, vp, vp, vp, vp, vp,
+                                         ctypes.c_size_t, vp]
+        L.corey_entropy_hist_workspace.restype = ctypes.c_size_t
+        L.corey_entropy_hist_workspace.argtypes = [i64, i32]
+        L.corey_policy_default.restype = ctypes.c_int
+        L.corey_policy_default.argtypes = [ctypes.POINTER(Policy)]
+        L.corey_select_chunk.restype = ctypes.c_int
+        L.corey_select_chunk.argtypes = [dbl, i64, ctypes.POINTER(Policy), ctypes.POINTER(i32)]
+        L.selective_scan_fwd.restype = ctypes.c_int
+        L.selective_scan_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, vp, vp, vp,
+                                         ctypes.c_int, i64, i64, i64, i64, vp]
+        L.corey_last_error.restype = ctypes.c_char_p
+        L.corey_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise CoreyError(code, lib().corey_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return COREY_F32
+    if t.dtype == torch.bfloat16:
+        return COREY_BF16
+    raise TypeError(f"unsupported storage type {t.dtype}")
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, name):
+    if t is not None and (not t.is_cuda or not t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous GPU tensor")
+
+
+def policy_default() -> Policy:
+    p = Policy()
+    _check(lib().corey_policy_default(ctypes.byref(p)))
+    return p
+
+
+def corey_version() -> str:
+    return lib().corey_version().decode()
+
+
+def corey_entropy_hist_workspace(B: int, K: int) -> int:
+    return int(lib().corey_entropy_hist_workspace(B, K))
+
+
+def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int = 1, seqlens: torch.Tensor | None = None,
+                       out: dict | None = None, workspace: torch.Tensor | None = None):
+    """x: [B, D, L] GPU tensor (float32 or bfloat16).  Returns dict(counts, H, r, range) of GPU tensors;
+    nothing is copied to the host and the call does not synchronise."""
+    _dev(x, "x"), _dev(seqlens, "seqlens")
+    if x.dim() != 3:
+        raise ValueError("x must be [B, D, L]")
+    B, D, L = x.shape
+    nh = B if seqlens is not None else 1
+    if out is None:
+        out = dict(counts=torch.empty((nh, K), dtype=torch.int32, device=x.device),   # uint32 bit patterns
+                   H=torch.empty(nh, dtype=torch.float64, device=x.device),
+                   r=torch.empty(nh, dtype=torch.float64, device=x.device),
+                   range=torch.empty((nh, 2), dtype=torch.float32, device=x.device))
+    need = corey_entropy_hist_workspace(B, K)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    _check(lib().corey_entropy_hist(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride,
+                                    _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
+                                    _ptr(workspace), workspace.numel(), _stream()))
+    out["workspace"] = workspace
+    return out
+
+
+def corey_select_chunk(r: float, L: int, policy: Policy | None = None) -> int:
+    p = policy if policy is not None else policy_default()
+    c = ctypes.c_int32(0)
+    _check(lib().corey_select_chunk(float(r), int(L), ctypes.byref(p), ctypes.byref(c)))
+    return c.value
+
+
+def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True, h0=None,
+                       seqlens=None, chunk: int = 512, chunks_dev=None, y=None, last_state=None):
+    """Tensors as in include/corey.h.  Returns (y, last_state); enqueues on torch's current stream."""
+    for name, t in (("u", u), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dv", Dv), ("z", z),
+                    ("delta_bias", delta_bias), ("h0", h0), ("seqlens", seqlens), ("chunks_dev", chunks_dev)):
+        _dev(t, name)
+    B, D, L = u.shape
+    N = A.shape[1]
+    if A.shape != (D, N) or Bm.shape != (B, N, L) or Cm.shape != (B, N, L) or delta.shape != u.shape:
+        raise ValueError("inconsistent shapes")
+    for t in (delta, Bm, Cm, z):
+        if t is not None and t.dtype != u.dtype:
+            raise TypeError("u, delta, Bm, Cm, z must share one storage type")
+    for t in (A, Dv, delta_bias, h0):
+        if t is not None and t.dtype != torch.float32:
+            raise TypeError("A, Dv, delta_bias, h0 must be float32")
+    if y is None:
+        y = torch.empty_like(u)
+    if last_state is None:
+        last_state = torch.empty((B, D, N), dtype=torch.float32, device=u.device)
+    _check(lib().selective_scan_fwd(_ptr(u), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dv), _ptr(z),
+                                    _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(h0), _ptr(seqlens), int(chunk),
+                                    _ptr(chunks_dev), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L, _stream()))
+    return y, last_state

@@ -1,0 +1,91 @@
+"""Helpers for the GPU parity tests: upload a workload, run the oracle on it (or on sampled rows), compare."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2604_10597_amd import workloads as wl
+
+RTOL = {wl.F32: 1e-5, wl.BF16: 3e-3}
+
+
+def fp32_rtol(L: int) -> float:
+    """Tolerance on quantities kept in fp32 end to end (y for fp32 storage, the carried state always).
+
+    1e-5 is the bound stated for the fp32 configuration (L = 256).  Every step rounds the decay exp(dl A) and the
+    state update to binary32 (relative 2^-24 each); a state whose decay is close to 1 remembers up to L steps, so
+    these independent roundings add up like a random walk, ~ sqrt(L) * 6e-8 of the state's scale (1.5e-6 at
+    L = 256 typical, several times that in the tail of many thousand elements).  The bound therefore grows with
+    sqrt(L / 256) for sequences longer than the stated configuration.
+    """
+    return 1e-5 * max(1.0, (L / 256.0) ** 0.5)
+
+
+def y_rtol(cfg) -> float:
+    return fp32_rtol(cfg.L) if cfg.dtype == wl.F32 else RTOL[wl.BF16]
+
+
+def to_dev(arr, dtype):
+    """Storage array from workloads.store -> GPU tensor of that storage type."""
+    if arr is None:
+        return None
+    if arr.dtype == np.uint16:
+        return torch.from_numpy(arr.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def upload(w: wl.Workload):
+    d = {k: to_dev(v, w.cfg.dtype) for k, v in w.dev.items()}
+    d["seqlens"] = None if w.seqlens is None else torch.from_numpy(w.seqlens).cuda()
+    return d
+
+
+def y_to_f64(y: torch.Tensor) -> np.ndarray:
+    return y.to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def counts_u32(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+def oracle_scan(w: wl.Workload, rows=None, chunk=256, use_z=True, use_h0=True, threads=8):
+    """Oracle on all rows, or on the channel subset `rows` (same B, C and parameters)."""
+    v = w.val
+    sel = slice(None) if rows is None else np.asarray(rows)
+    pick3 = lambda a: None if a is None else np.ascontiguousarray(a[:, sel, :])
+    pick1 = lambda a: None if a is None else np.ascontiguousarray(a[sel])
+    st, y, last = oracle.selective_scan(
+        pick3(v["u"]), pick3(v["delta"]), pick1(v["A"]), v["B"], v["C"], Dv=pick1(v["D"]),
+        z=pick3(v["z"]) if use_z else None, delta_bias=pick1(v["delta_bias"]), delta_softplus=True,
+        h0=pick3(v["h0"]) if (use_h0 and v.get("h0") is not None) else None,
+        seqlens=w.seqlens, chunk=chunk, threads=threads)
+    assert st == oracle.OK
+    return y, last
+
+
+def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, what: str, stored_bf16: bool = False):
+    """|got - ref| <= rtol * (|ref| + rms of the reference row)  [+ half a bf16 ulp of ref if `stored_bf16`].
+
+    The first term is the tolerance on the fp32 computation, relative to the value and to the row's scale (a sum
+    over states that cancels is not held to a relative bound on its own tiny value).  When the result is stored
+    as bfloat16 the store itself rounds by up to half an ulp (2^-8 relative just above a power of two, i.e. more
+    than 3e-3), so that rounding is granted on top: the value before the store must lie within rtol.
+    """
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
+    bound = rtol * (np.abs(ref) + rms) + 1e-30
+    if stored_bf16:
+        with np.errstate(divide="ignore"):
+            e = np.floor(np.log2(np.abs(ref) + bound))
+        bound = bound + np.where(ref != 0, 2.0 ** (e - 8), 0.0)
+    err = np.abs(got - ref)
+    bad = err > bound
+    if bad.any():
+        i = np.unravel_index(np.argmax(err / bound), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} of {bad.size} outside tolerance {rtol}; worst at {i}: "
+                             f"got {got[i]!r} ref {ref[i]!r} err {err[i]:.3e} bound {bound[i]:.3e}")
+    return float((err / bound).max())

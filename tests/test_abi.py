@@ -1,0 +1,98 @@
+"""Host-side checks that need no GPU: the shared library loads, exports what include/corey.h declares,
+rejects bad arguments before launching anything, and its chunk rule agrees with the oracle's."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+import oracle
+from conftest import ROOT, read_golden
+from paper_2604_10597_amd import binding
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "corey.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(corey_\w+|selective_scan_fwd)\s*\(", hdr))
+    declared -= {"corey_dtype", "corey_status", "corey_policy"}
+    assert declared == set(binding.EXPORTS)
+    lib = binding.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert binding.corey_version() == "0.1"
+
+
+def _href(tok):
+    return math.log(int(tok.split(":")[1])) if tok.startswith("logK:") else float(tok)
+
+
+@pytest.mark.parametrize("row", read_golden("chunk_rule_pins.txt"), ids=lambda r: "-".join(r))
+def test_library_chunk_rule_on_the_papers_values(row):
+    H, href, cmin, cmax, expect = float(row[0]), _href(row[1]), int(row[2]), int(row[3]), int(row[4])
+    p = binding.policy_default()
+    p.c_min, p.c_max = cmin, cmax
+    assert binding.corey_select_chunk(min(H / href, 1.0), 4096, p) == expect
+
+
+def test_library_chunk_rule_matches_oracle_everywhere():
+    for mode in (0, 1, 2, 3, 4):
+        for cmin, cmax in ((64, 2048), (32, 512), (128, 128)):
+            p = binding.policy_default()
+            p.mode, p.c_min, p.c_max = mode, cmin, cmax
+            op = oracle.policy(mode=mode, c_min=cmin, c_max=cmax)
+            for scale in (1.0, math.log(256) / 8.0):
+                p.h_ref_scale = op.h_ref_scale = scale
+                for L in (1, 25, 50, 51, 256, 300, 4096, 16384):
+                    for i in range(0, 201):
+                        r = i / 200.0
+                        st, c, margin = oracle.select_chunk(r, L, op)
+                        assert st == oracle.OK
+                        assert binding.corey_select_chunk(r, L, p) == c, (mode, cmin, cmax, L, r, margin)
+
+
+def test_chunk_rule_errors():
+    p = binding.policy_default()
+    with pytest.raises(binding.CoreyError) as e:
+        binding.corey_select_chunk(float("nan"), 4096, p)
+    assert e.value.code == 4
+    with pytest.raises(binding.CoreyError) as e:
+        binding.corey_select_chunk(0.5, 0, p)
+    assert e.value.code == 1
+    p.c_min = 48
+    with pytest.raises(binding.CoreyError):
+        binding.corey_select_chunk(0.5, 64, p)
+    p = binding.policy_default()
+    p.mode = 9
+    with pytest.raises(binding.CoreyError):
+        binding.corey_select_chunk(0.5, 64, p)
+    assert binding.lib().corey_select_chunk(0.5, 64, None, None) == 2
+    assert b"NULL" in binding.lib().corey_last_error()
+
+
+def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
+    lib = binding.lib()
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: every call below fails validation first
+    none = ctypes.c_void_p(0)
+    eh = lambda **kw: lib.corey_entropy_hist(
+        kw.get("x", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("L", 8), none, kw.get("K", 16),
+        kw.get("eps", 1e-8), kw.get("stride", 1), kw.get("counts", fake), fake, fake, none, kw.get("ws", fake),
+        kw.get("wsb", 256), none)
+    assert eh(x=none) == 2 and eh(counts=none) == 2
+    assert eh(dt=7) == 1 and eh(K=1) == 1 and eh(K=5000) == 1 and eh(stride=0) == 1 and eh(eps=-1.0) == 1
+    assert eh(B=0) == 3 and eh(L=0) == 3
+    assert eh(ws=none) == 7 and eh(wsb=8) == 7
+    assert lib.corey_entropy_hist_workspace(0, 16) == 0 and lib.corey_entropy_hist_workspace(3, 1) == 0
+    assert lib.corey_entropy_hist_workspace(3, 256) >= 3 * 16
+
+    ss = lambda **kw: lib.selective_scan_fwd(
+        kw.get("u", fake), fake, fake, fake, fake, none, none, none, 1, none, none, kw.get("chunk", 256), none,
+        kw.get("y", fake), kw.get("last", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("N", 16),
+        kw.get("L", 64), none)
+    assert ss(u=none) == 2 and ss(y=none) == 2 and ss(last=none) == 2
+    assert ss(dt=3) == 1
+    for bad in (0, 8, 100, 4096, -64):
+        assert ss(chunk=bad) == 1
+    assert ss(N=0) == 3 and ss(N=257) == 3 and ss(B=0) == 3 and ss(L=0) == 3 and ss(B=70000) == 3
+    assert b"chunk" in lib.corey_last_error() or b"B" in lib.corey_last_error()

@@ -1,0 +1,179 @@
+"""GPU parity: selective_scan_fwd against the CPU oracle, element by element, plus the invariants of the method.
+
+Tolerance (written out in gpu_util.assert_close): |got - ref| <= rtol * (|ref| + rms(ref row)), with rtol = 1e-5 for
+fp32 storage at the stated configuration (growing with sqrt(L/256) for longer sequences, see gpu_util.fp32_rtol)
+and 3e-3 for bf16 storage with fp32 state, plus the bf16 store's own half ulp; the fp32 state is held to the fp32
+bound for both storage types.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_10597_amd as corey
+from gpu_util import assert_close, fp32_rtol, oracle_scan, upload, y_rtol, y_to_f64
+from paper_2604_10597_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+ALL_CHUNKS = (16, 32, 64, 128, 256, 512, 1024, 2048)
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def _run(d, chunk, use_z=True, use_h0=True, chunks_dev=None, softplus=True):
+    y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"] if use_z else None,
+                                       delta_bias=d["delta_bias"], delta_softplus=softplus,
+                                       h0=d.get("h0") if use_h0 else None, seqlens=d["seqlens"], chunk=chunk,
+                                       chunks_dev=chunks_dev)
+    torch.cuda.synchronize()
+    return y_to_f64(y), last.cpu().numpy().astype(np.float64)
+
+
+def _parity(cfg, chunks, a_kind="mamba", with_h0=False, use_z=True):
+    w = wl.make(cfg, a_kind=a_kind, with_h0=with_h0)
+    d = upload(w)
+    y_ref, s_ref = oracle_scan(w, use_z=use_z)
+    worst = 0.0
+    for chunk in chunks:
+        _say(f"scan {cfg.name} B{cfg.B} D{cfg.D} N{cfg.N} L{cfg.L} {cfg.dtype} A={a_kind} chunk={chunk} z={use_z} h0={with_h0}")
+        y, s = _run(d, chunk, use_z=use_z)
+        worst = max(worst, assert_close(y, y_ref, y_rtol(cfg), f"y chunk {chunk}", cfg.dtype == wl.BF16))
+        assert_close(s, s_ref, fp32_rtol(cfg.L), f"last_state chunk {chunk}")
+    return worst
+
+
+def test_config0_fp32_every_chunk():
+    _parity(wl.CONFIGS["c0_tiny_f32"], ALL_CHUNKS)
+    _parity(wl.CONFIGS["c0_tiny_f32"], (64, 128, 256), a_kind="random", with_h0=True)
+
+
+@pytest.mark.parametrize("name,D,L,seqlens", [
+    ("c1_mamba130m", 40, 2048, None),
+    ("c2_mamba370m", 24, 1280, None),
+    ("c3_mamba1p4b", 20, 2304, (2304, 700)),
+    ("c4_mamba2p8b", 200, 1100, None),
+])
+def test_configs_at_oracle_size_every_chunk(name, D, L, seqlens):
+    cfg = wl.scaled(wl.CONFIGS[name], D=D, L=L, seqlens=seqlens)
+    _parity(cfg, ALL_CHUNKS)
+
+
+def test_unstructured_A_initial_state_and_no_gate():
+    cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=36, L=777)
+    _parity(cfg, (64, 512, 2048), a_kind="random", with_h0=True)
+    _parity(cfg, (128, 1024), a_kind="random", use_z=False)
+    cfg32 = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=20, L=1500, dtype=wl.F32)
+    _parity(cfg32, (64, 256, 2048), a_kind="random", with_h0=True)
+
+
+@pytest.mark.parametrize("N", [1, 3, 16, 40, 64, 256])
+def test_state_sizes(N):
+    cfg = wl.scaled(wl.CONFIGS["c1_mamba130m"], D=12, L=300, N=N, B=2)
+    _parity(cfg, (64, 2048), a_kind="random", with_h0=True)
+
+
+@pytest.mark.parametrize("L", [1, 15, 16, 17, 63, 65, 1023, 2049])
+def test_ragged_lengths(L):
+    for dtype in (wl.F32, wl.BF16):
+        cfg = wl.scaled(wl.CONFIGS["c0_tiny_f32"], D=7, L=L, B=2, dtype=dtype)
+        _parity(cfg, (16, 64, 2048), a_kind="random")
+
+
+def test_padded_batches_and_empty_sequence():
+    for lens in ((512, 2048), (2048, 512), (1, 2048), (0, 100), (2048, 2048)):
+        cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], D=16, L=2048, seqlens=lens)
+        w = wl.make(cfg, with_h0=True)
+        d = upload(w)
+        y_ref, s_ref = oracle_scan(w)
+        for chunk in (64, 256, 2048):
+            _say(f"scan padded lens={lens} chunk={chunk}")
+            y, s = _run(d, chunk)
+            assert_close(y, y_ref, y_rtol(cfg), f"y lens {lens}", True)
+            assert_close(s, s_ref, fp32_rtol(cfg.L), f"state lens {lens}")
+            for b, n in enumerate(lens):
+                assert not y[b, :, n:].any()                 # padded positions are exactly zero
+        if lens[0] == 0:
+            assert np.array_equal(s[0], w.val["h0"][0].astype(np.float64))
+
+
+def test_per_sequence_device_chunks():
+    cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], D=24, L=1536, B=4, seqlens=(1536, 40, 900, 1536))
+    w = wl.make(cfg)
+    d = upload(w)
+    y_ref, s_ref = oracle_scan(w)
+    chunks = torch.tensor([2048, 64, 512, 100], dtype=torch.int32, device="cuda")   # 100 is invalid -> host value
+    _say("scan per-sequence device chunks")
+    y, s = _run(d, 256, chunks_dev=chunks)
+    assert_close(y, y_ref, y_rtol(cfg), "y device chunks", True)
+    # each sequence must equal a uniform launch with its own chunk, bit for bit
+    for b, c in enumerate((2048, 64, 512, 256)):
+        yb, sb = _run(d, c)
+        assert np.array_equal(yb[b], y[b]) and np.array_equal(sb[b], s[b])
+
+
+def test_invariants_on_the_gpu_path():
+    cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=32, L=1024)
+    w = wl.make(cfg, a_kind="random")
+    d = upload(w)
+    _say("scan invariants")
+    y1, s1 = _run(d, 256)
+    # linearity in u: scaling by a power of two scales y and the state exactly
+    d2 = dict(d)
+    d2["u"] = (d["u"].to(torch.float32) * 4).to(d["u"].dtype)
+    y4, s4 = _run(d2, 256)
+    assert np.array_equal(y4, 4 * y1) and np.array_equal(s4, 4 * s1)
+    # continuation: scanning the tail from the returned state reproduces the full scan
+    cut = 384
+    head = {k: (v[..., :cut].contiguous() if k in ("u", "delta", "z", "B", "C") else v) for k, v in d.items()}
+    tail = {k: (v[..., cut:].contiguous() if k in ("u", "delta", "z", "B", "C") else v) for k, v in d.items()}
+    yh, sh = _run(head, 128)
+    tail["h0"] = torch.from_numpy(sh.astype(np.float32)).cuda()
+    yt, st = _run(tail, 128)
+    assert_close(np.concatenate([yh, yt], axis=-1), y1, y_rtol(cfg), "split scan", True)
+    assert_close(st, s1, fp32_rtol(cfg.L), "split scan state")
+    # gate: z = 0 gives y = 0; no gate equals gated / silu
+    d0 = dict(d)
+    d0["z"] = torch.zeros_like(d["z"])
+    y0, _ = _run(d0, 256)
+    assert not y0.any()
+    # repeat runs are bit-identical
+    y1b, s1b = _run(d, 256)
+    assert np.array_equal(y1, y1b) and np.array_equal(s1, s1b)
+
+
+def test_closed_form_on_gpu_without_softplus():
+    # constant inputs: geometric series (decay strong enough that binary32 rounding of exp() stays below tolerance)
+    B, D, N, L = 1, 8, 16, 600
+    dl, uu, bb, cc = 0.25, 1.5, -0.75, 2.0
+    A = -np.broadcast_to(np.arange(1, N + 1, dtype=np.float32), (D, N)).copy()
+    full = lambda v, shape: torch.full(shape, v, dtype=torch.float32, device="cuda")
+    y, last = corey.selective_scan_fwd(full(uu, (B, D, L)), full(dl, (B, D, L)), torch.from_numpy(A).cuda(),
+                                       full(bb, (B, N, L)), full(cc, (B, N, L)), delta_softplus=False, chunk=128)
+    abar = np.exp(dl * A[0].astype(np.float64))
+    t = np.arange(1, L + 1)[:, None]
+    h = dl * bb * uu * (1 - abar ** t) / (1 - abar)
+    assert_close(y.cpu().numpy()[0, 0], cc * h.sum(1), fp32_rtol(L), "geometric series y")
+    assert_close(last.cpu().numpy()[0, 0], h[-1], fp32_rtol(L), "geometric series state")
+
+
+@pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b"])
+def test_full_size_sampled_rows(name):
+    """The benchmark's launch configuration at full size; the oracle recomputes sampled channels one by one."""
+    cfg = wl.CONFIGS[name]
+    w = wl.make(cfg)
+    d = upload(w)
+    rows = np.unique(np.concatenate([[0, 1, cfg.D // 2, cfg.D - 1], np.random.default_rng(3).integers(0, cfg.D, 12)]))
+    y_ref, s_ref = oracle_scan(w, rows=rows)
+    ent = corey.corey_entropy_hist(d["u"], cfg.K)
+    chunk = corey.corey_select_chunk(ent["r"].item(), cfg.L)
+    for c in sorted({chunk, 64, 2048}):
+        _say(f"scan full size {name} chunk={c} (routed={chunk})")
+        y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
+                                           delta_bias=d["delta_bias"], seqlens=d["seqlens"], chunk=c)
+        torch.cuda.synchronize()
+        ys = y[:, torch.from_numpy(rows).cuda(), :]
+        assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y chunk {c}", True)
+        assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state chunk {c}")
+        assert torch.isfinite(y.to(torch.float32)).all()
