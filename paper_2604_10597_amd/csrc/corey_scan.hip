@@ -2,12 +2,15 @@
 //
 // Mapping.  A workgroup of 256 lanes owns `rows` channels of one sequence and walks the time axis in
 // tiles of `chunk` steps.  Inside a tile a row is spread over chunk/16 consecutive lanes, each lane owning
-// 16 consecutive time steps, so loads of u/delta/z and the store of y are contiguous along L.  For every
-// state index n a lane
-//   1. discretises its 16 steps (a_i = exp(dl_i A), b_i = dl_i B_i u_i) and folds them, from a zero state,
-//      into the pair (P, h) that represents the affine map  x -> P x + h  of its sub-block;
-//   2. takes part in a segmented inclusive scan of those pairs over the lanes of its row (the pair
-//      operator is associative), crossing the wave boundary through LDS when a row needs 128 lanes;
+// 16 consecutive time steps, so loads of u/delta/z and the store of y are contiguous along L (16-byte
+// vectors per lane).  B and C of the tile are shared by every row of the workgroup: they are converted to
+// fp32 once, cooperatively, into LDS (a few states at a time when the chunk is long) in a layout that lets
+// consecutive lanes read consecutive 16-byte words.  For every state index n a lane
+//   1. discretises its 16 steps (a_i = exp2(dl_i A log2e), b_i = dl_i B_i u_i) and folds them, from a zero
+//      state, into the pair (P, h) that represents the affine map  x -> P x + h  of its sub-block
+//      (P itself comes from one exp2 of the summed dl);
+//   2. obtains the composition of all pairs to its left in the row by a DPP scan across lanes (the pair
+//      operator is associative); a row of 128 lanes crosses the wave boundary through LDS;
 //   3. replays its 16 steps from the true incoming state (prefix pair applied to the state carried from
 //      the previous tile) and accumulates y_i += C_i h_i.
 // The fp32 state carried from tile to tile lives in LDS; the last lane of a row refreshes it.
@@ -21,73 +24,190 @@ namespace {
 using corey::bf16_to_f32;
 using corey::f32_to_bf16;
 
-constexpr int kItems = 16;      // time steps per lane per tile
-constexpr int kBlock = 256;     // lanes per workgroup
+constexpr int kBlock = 256;       // lanes per workgroup
+constexpr int kWaves = kBlock / 64;
+constexpr int kTileElems = 4096;  // fp32 values of B (and of C) staged in LDS at a time
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
 
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// ------------------------------------------------------------------------------------------- storage types
+// A lane keeps its K consecutive stored values as raw 16-byte words (Raw) and widens them when needed.
 template <typename T> struct Io;
 template <> struct Io<float> {
+    static constexpr int kVec = 4;     // elements per 16-byte word
     static __device__ __forceinline__ float ld(const float* p) { return *p; }
     static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+    static __device__ __forceinline__ void unpack(const uint4v& q, float* out)
+    {
+        out[0] = __uint_as_float(q.x); out[1] = __uint_as_float(q.y);
+        out[2] = __uint_as_float(q.z); out[3] = __uint_as_float(q.w);
+    }
+    static __device__ __forceinline__ uint4v pack(const float* v)
+    {
+        uint4v q;
+        q.x = __float_as_uint(v[0]); q.y = __float_as_uint(v[1]); q.z = __float_as_uint(v[2]); q.w = __float_as_uint(v[3]);
+        return q;
+    }
 };
 template <> struct Io<uint16_t> {
+    static constexpr int kVec = 8;
     static __device__ __forceinline__ float ld(const uint16_t* p) { return bf16_to_f32(*p); }
     static __device__ __forceinline__ void st(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+    static __device__ __forceinline__ void unpack(const uint4v& q, float* out)
+    {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            out[2 * k] = __uint_as_float(w[k] << 16);
+            out[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+        }
+    }
+    // round to nearest even in hardware (v_cvt_pk_bf16_f32)
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        float2v f;
+        f.x = lo; f.y = hi;
+        const bf16x2 h = __builtin_convertvector(f, bf16x2);
+        uint32_t r;
+        __builtin_memcpy(&r, &h, 4);
+        return r;
+    }
+    static __device__ __forceinline__ uint4v pack(const float* v)
+    {
+        uint4v q;
+        q.x = pack2(v[0], v[1]); q.y = pack2(v[2], v[3]); q.z = pack2(v[4], v[5]); q.w = pack2(v[6], v[7]);
+        return q;
+    }
 };
 
-// Load kItems consecutive values starting at p (valid: the first nvalid), widened to fp32; the rest are 0.
-template <typename T>
-__device__ __forceinline__ void load_items(const T* p, int nvalid, bool vector_ok, float (&out)[kItems])
+template <typename T, int K> struct Raw {
+    static constexpr int kWords = K / Io<T>::kVec;
+    uint4v w[kWords];
+};
+
+// K consecutive stored values starting at p (the first nvalid exist); missing ones read as zero bits.
+template <typename T, int K>
+__device__ __forceinline__ Raw<T, K> load_raw(const T* p, int nvalid, bool vector_ok)
 {
-    if (vector_ok && nvalid == kItems) {
-        typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
-        constexpr int kVecs = kItems * (int)sizeof(T) / 16;
-        T raw[kItems];
-        const vec4* pv = reinterpret_cast<const vec4*>(p);
+    constexpr int V = Io<T>::kVec;
+    Raw<T, K> r;
+    if (vector_ok && nvalid == K) {
+        const uint4v* pv = reinterpret_cast<const uint4v*>(p);
 #pragma unroll
-        for (int v = 0; v < kVecs; ++v) {
-            const vec4 q = pv[v];
-            __builtin_memcpy(reinterpret_cast<char*>(raw) + 16 * v, &q, 16);
-        }
-#pragma unroll
-        for (int i = 0; i < kItems; ++i) out[i] = Io<T>::ld(&raw[i]);
+        for (int v = 0; v < Raw<T, K>::kWords; ++v) r.w[v] = pv[v];
     } else {
+        T tmp[K];
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) out[i] = (i < nvalid) ? Io<T>::ld(p + i) : 0.f;
+        for (int i = 0; i < K; ++i) tmp[i] = (i < nvalid) ? p[i] : T(0);
+#pragma unroll
+        for (int v = 0; v < Raw<T, K>::kWords; ++v) __builtin_memcpy(&r.w[v], &tmp[v * V], 16);
     }
+    return r;
 }
 
-template <typename T>
-__device__ __forceinline__ void store_items(T* p, int nstore, bool vector_ok, const float (&v)[kItems])
+template <typename T, int K>
+__device__ __forceinline__ void widen(const Raw<T, K>& r, float (&out)[K])
 {
-    if (vector_ok && nstore == kItems) {
-        typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
-        constexpr int kVecs = kItems * (int)sizeof(T) / 16;
-        T raw[kItems];
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) Io<T>::st(&raw[i], v[i]);
-        vec4* pv = reinterpret_cast<vec4*>(p);
+    for (int v = 0; v < Raw<T, K>::kWords; ++v) Io<T>::unpack(r.w[v], &out[v * Io<T>::kVec]);
+}
+
+template <typename T, int K>
+__device__ __forceinline__ void store_items(T* p, int nstore, bool vector_ok, const float (&v)[K])
+{
+    constexpr int V = Io<T>::kVec;
+    if (vector_ok && nstore == K) {
+        uint4v* pv = reinterpret_cast<uint4v*>(p);
 #pragma unroll
-        for (int k = 0; k < kVecs; ++k) {
-            vec4 q;
-            __builtin_memcpy(&q, reinterpret_cast<const char*>(raw) + 16 * k, 16);
-            pv[k] = q;
-        }
+        for (int k = 0; k < K / V; ++k) pv[k] = Io<T>::pack(&v[k * V]);
     } else {
 #pragma unroll
-        for (int i = 0; i < kItems; ++i)
+        for (int i = 0; i < K; ++i)
             if (i < nstore) Io<T>::st(p + i, v[i]);
     }
 }
 
-// log(1 + e^x) without losing the small tail: log1p on e^{-|x|}.
+// ------------------------------------------------------------------------------------------- elementwise maths
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// log(1 + e^x) = max(x, 0) + log1p(e^{-|x|}).  log1p(e) is taken as log(w), w = fl(1 + e), plus the repair
+// e - (w - 1) of the rounding in w (its 1/w factor lies in [1/2, 1] and the repair is below one ulp of w, so
+// dropping the factor costs < 3e-8 absolute): the small tail e << 1 stays accurate to binary32 relative precision.
 __device__ __forceinline__ float softplus(float x)
 {
-    return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
+    const float e = fast_exp2(-fabsf(x) * kLog2e);
+    const float w = 1.f + e;
+    const float fix = e - (w - 1.f);
+    return fmaxf(x, 0.f) + fmaf(__builtin_amdgcn_logf(w), kLn2, fix);
 }
 
-__device__ __forceinline__ float silu(float z) { return z / (1.f + expf(-z)); }
+// z * sigmoid(z)
+__device__ __forceinline__ float silu(float z)
+{
+    return z * __builtin_amdgcn_rcpf(1.f + fast_exp2(-z * kLog2e));
+}
 
+// ------------------------------------------------------------------------------------------- lane scan (DPP)
+// Exclusive prefix, over the `seg` consecutive lanes of a row inside one wave, of the per-lane affine maps
+// x -> P x + h: on return (P, h) is the composition of the maps of all lanes to the left (identity for the
+// first lane of a segment).  The pairs are first moved one lane to the right, then combined by a
+// Hillis-Steele scan whose steps are single DPP instructions:  h += h[lane - s] * P ;  P *= P[lane - s];
+// lanes without a source (DPP bound control off) keep their value, which is composing with the identity.
+// The instructions are written out because the hazard rules matter: a DPP operand written by the previous
+// VALU instruction needs two wait states (s_nop 1), and five after a VALU write of EXEC (s_nop 4 up front).
+#define COREY_DPP_STEP(ctrl)                                                               \
+    "s_nop 1\n\tv_fmac_f32_dpp %0, %0, %1 " ctrl " bank_mask:0xf\n\t"                      \
+    "s_nop 1\n\tv_mul_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t"
+#define COREY_ROW_STEPS                                                                    \
+    COREY_DPP_STEP("row_shr:1 row_mask:0xf") COREY_DPP_STEP("row_shr:2 row_mask:0xf")      \
+    COREY_DPP_STEP("row_shr:4 row_mask:0xf") COREY_DPP_STEP("row_shr:8 row_mask:0xf")
+
+__device__ __forceinline__ void exclusive_scan_pairs(int seg, int jseg, float& P, float& h)
+{
+    float hs = 0.f, Ps = 1.f;
+    asm volatile("s_nop 4\n\t"
+                 "v_mov_b32_dpp %0, %2 wave_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+                 "v_mov_b32_dpp %1, %3 wave_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+                 : "+v"(hs), "+v"(Ps)
+                 : "v"(h), "v"(P));
+    if (jseg == 0) { hs = 0.f; Ps = 1.f; }
+    h = hs;
+    P = Ps;
+    if (seg == 64) {
+        asm volatile("s_nop 4\n\t" COREY_ROW_STEPS COREY_DPP_STEP("row_bcast:15 row_mask:0xa")
+                     COREY_DPP_STEP("row_bcast:31 row_mask:0xc") : "+v"(h), "+v"(P));
+    } else if (seg == 32) {
+        asm volatile("s_nop 4\n\t" COREY_ROW_STEPS COREY_DPP_STEP("row_bcast:15 row_mask:0xa") : "+v"(h), "+v"(P));
+    } else if (seg == 16) {
+        asm volatile("s_nop 4\n\t" COREY_ROW_STEPS : "+v"(h), "+v"(P));
+    } else if (seg > 1) {
+        // segments shorter than a DPP row: the shifted-in partner must come from the same segment
+        for (int off = 1; off < seg; off <<= 1) {
+            float ho = 0.f, Po = 1.f;
+            if (off == 1)
+                asm volatile("s_nop 4\n\tv_mov_b32_dpp %0, %2 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+                             "v_mov_b32_dpp %1, %3 row_shr:1 row_mask:0xf bank_mask:0xf\n\t" : "+v"(ho), "+v"(Po) : "v"(h), "v"(P));
+            else if (off == 2)
+                asm volatile("s_nop 4\n\tv_mov_b32_dpp %0, %2 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+                             "v_mov_b32_dpp %1, %3 row_shr:2 row_mask:0xf bank_mask:0xf\n\t" : "+v"(ho), "+v"(Po) : "v"(h), "v"(P));
+            else
+                asm volatile("s_nop 4\n\tv_mov_b32_dpp %0, %2 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+                             "v_mov_b32_dpp %1, %3 row_shr:4 row_mask:0xf bank_mask:0xf\n\t" : "+v"(ho), "+v"(Po) : "v"(h), "v"(P));
+            const bool take = jseg >= off;
+            ho = take ? ho : 0.f;
+            Po = take ? Po : 1.f;
+            h = fmaf(P, ho, h);
+            P = P * Po;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------- kernel
 struct ScanArgs {
     const void* u;
     const void* delta;
@@ -106,11 +226,46 @@ struct ScanArgs {
     int32_t D, N;
     int32_t chunk;          // host chunk (also the fallback for invalid device entries)
     int32_t rows_cap;       // most rows a workgroup may hold (LDS budget for the carried state)
+    int32_t rows_alloc;     // rows the LDS arrays are sized for
     int32_t softplus;
     int32_t vector_ok;      // rows of the [.., L] tensors are 16-byte aligned
 };
 
-template <typename T>
+// Convert the tile [n0, n0+ns) x [tile, tile+chunk) of one [N, L] operand to fp32 in LDS.
+// LDS layout: value (n, t) at ((n*(K/4) + (t%K)/4) * lpr + t/K) * 4 + t%4, so that for a fixed quarter of a
+// lane's K steps consecutive lanes read consecutive 16-byte words.
+template <typename T, int K>
+__device__ __forceinline__ void stage_operand(const T* __restrict__ src_seq, float* __restrict__ dst, int n0, int ns,
+                                              int64_t tile, int chunk, int lpr, int64_t len, int64_t L, bool vector_ok)
+{
+    constexpr int V = Io<T>::kVec;
+    const int per_row = chunk / V;
+    const int units = ns * per_row;
+    for (int k = threadIdx.x; k < units; k += kBlock) {
+        const int nl = k / per_row;
+        const int tv = (k - nl * per_row) * V;                 // first step of this unit inside the tile
+        const int64_t t = tile + tv;
+        const T* p = src_seq + (int64_t)(n0 + nl) * L + t;
+        float v[V];
+        const int nvalid = (t >= len) ? 0 : (len - t < V ? (int)(len - t) : V);
+        if (vector_ok && nvalid == V) {
+            Io<T>::unpack(*reinterpret_cast<const uint4v*>(p), v);
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[e] = (e < nvalid) ? Io<T>::ld(p + e) : 0.f;
+        }
+        const int j = tv / K;
+        const int q = (tv % K) / 4;
+#pragma unroll
+        for (int g = 0; g < V / 4; ++g) {
+            float4v w;
+            w.x = v[4 * g]; w.y = v[4 * g + 1]; w.z = v[4 * g + 2]; w.w = v[4 * g + 3];
+            *reinterpret_cast<float4v*>(dst + ((size_t)((nl * (K / 4) + q + g) * lpr + j) * 4)) = w;
+        }
+    }
+}
+
+template <typename T, int K>
 __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
@@ -120,8 +275,8 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
         const int c = a.chunks_dev[b];
         if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
     }
-    const int lpr = chunk / kItems;                         // lanes per row (1 .. 128)
-    int rows = kBlock / lpr;                                // rows per workgroup
+    const int lpr = chunk / K;                              // lanes per row
+    int rows = lpr >= kBlock ? 1 : kBlock / lpr;            // rows per workgroup
     if (rows > a.rows_cap) rows = a.rows_cap;
     const int d0 = blockIdx.x * rows;
     if (d0 >= a.D) return;                                  // whole workgroup leaves together
@@ -131,6 +286,7 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
     const int j = tid - row_local * lpr;                    // sub-block of this lane inside the tile
     const int d = d0 + row_local;
     const bool active = row_local < rows && d < a.D;
+    const int rl = active ? row_local : 0;                  // safe LDS row for idle lanes
     const int N = a.N;
     const int64_t L = a.L;
     int64_t len = L;
@@ -140,15 +296,19 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
     }
 
     float* s_carry = s_mem;                                 // [rows][N] state carried tile to tile
-    float* s_xchg = s_mem + (size_t)a.rows_cap * N;         // [waves][2] wave totals when a row spans two waves
-    const int64_t row = (int64_t)b * a.D + (active ? d : d0);
+    float* s_A2 = s_carry + (size_t)a.rows_alloc * N;       // [rows][N] A * log2(e)
+    float* s_xchg = s_A2 + (size_t)a.rows_alloc * N;        // [waves][2] wave totals when a row spans several waves
+    float* s_B = s_xchg + 2 * kWaves;                       // staged B tile (fp32)
+    float* s_C = s_B + kTileElems;                          // staged C tile (fp32)
     for (int i = tid; i < rows * N; i += kBlock) {
-        const int rl = i / N, n = i - rl * N;
-        const int dd = d0 + rl;
-        s_carry[i] = (a.h0 && dd < a.D) ? a.h0[((int64_t)b * a.D + dd) * N + n] : 0.f;
+        const int r = i / N, n = i - r * N;
+        const int dd = d0 + r;
+        const bool ok = dd < a.D;
+        s_carry[i] = (a.h0 && ok) ? a.h0[((int64_t)b * a.D + dd) * N + n] : 0.f;
+        s_A2[i] = ok ? a.A[(int64_t)dd * N + n] * kLog2e : 0.f;
     }
-    __syncthreads();
 
+    const int64_t row = (int64_t)b * a.D + (active ? d : d0);
     const T* u_row = static_cast<const T*>(a.u) + row * L;
     const T* dl_row = static_cast<const T*>(a.delta) + row * L;
     const T* z_row = a.z ? static_cast<const T*>(a.z) + row * L : nullptr;
@@ -161,106 +321,123 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int seg = lpr < 64 ? lpr : 64;                    // scan segment inside a wave
+    const int jseg = lane & (seg - 1);
+    const int wpr = lpr > 64 ? lpr / 64 : 1;                // waves per row
+    const int wpos = wave & (wpr - 1);                      // this wave's position inside its row
+    int nsub = kTileElems / chunk;                          // states staged per group
+    if (nsub > N) nsub = N;
 
     for (int64_t tile = 0; tile < L; tile += chunk) {
-        const int64_t t0 = tile + (int64_t)j * kItems;
+        const int64_t t0 = tile + (int64_t)j * K;
         // valid steps of this lane (within the sequence) and steps that get a y written (within L)
         int nvalid = 0, nstore = 0;
         if (active) {
-            nvalid = (t0 >= len) ? 0 : (len - t0 < kItems ? (int)(len - t0) : kItems);
-            nstore = (t0 >= L) ? 0 : (L - t0 < kItems ? (int)(L - t0) : kItems);
+            nvalid = (t0 >= len) ? 0 : (len - t0 < K ? (int)(len - t0) : K);
+            nstore = (t0 >= L) ? 0 : (L - t0 < K ? (int)(L - t0) : K);
         }
-        float dl[kItems], du[kItems], uu[kItems], yv[kItems];
-        if (tile < len || nstore > 0) {
-            load_items<T>(u_row + t0, nvalid, vec, uu);
-            load_items<T>(dl_row + t0, nvalid, vec, dl);
+        const Raw<T, K> u_raw = load_raw<T, K>(u_row + t0, nvalid, vec);
+        float dl[K], du[K], yv[K];
+        {
+            const Raw<T, K> d_raw = load_raw<T, K>(dl_row + t0, nvalid, vec);
+            widen<T, K>(d_raw, dl);
+            widen<T, K>(u_raw, du);
         }
         float S = 0.f;
 #pragma unroll
-        for (int i = 0; i < kItems; ++i) {
-            float v = 0.f;
-            if (i < nvalid) {
-                v = dl[i] + bias;
-                if (a.softplus) v = softplus(v);
-            }
-            dl[i] = v;                                      // padded steps: dl = 0 -> a = 1, b = 0 (identity)
-            du[i] = v * uu[i];
+        for (int i = 0; i < K; ++i) {
+            float v = dl[i] + bias;
+            if (a.softplus) v = softplus(v);
+            v = (i < nvalid) ? v : 0.f;                     // padded steps: dl = 0 -> a = 1, b = 0 (identity)
+            dl[i] = v;
+            du[i] = v * du[i];
             S += v;
             yv[i] = 0.f;
         }
 
         if (tile < len) {                                   // uniform over the workgroup
-            for (int n = 0; n < N; ++n) {
-                const float A2 = active ? a.A[(int64_t)d * N + n] * kLog2e : 0.f;
-                float Bv[kItems], Cv[kItems];
-                load_items<T>(B_seq + (int64_t)n * L + t0, nvalid, vec, Bv);
-                load_items<T>(C_seq + (int64_t)n * L + t0, nvalid, vec, Cv);
-                const float carry = active ? s_carry[row_local * N + n] : 0.f;
+            for (int n0 = 0; n0 < N; n0 += nsub) {
+                const int ns = (N - n0 < nsub) ? N - n0 : nsub;
+                __syncthreads();                            // previous group's readers are done (and s_carry/s_A2 are set)
+                stage_operand<T, K>(B_seq, s_B, n0, ns, tile, chunk, lpr, len, L, vec);
+                stage_operand<T, K>(C_seq, s_C, n0, ns, tile, chunk, lpr, len, L, vec);
+                __syncthreads();
+                for (int nl = 0; nl < ns; ++nl) {
+                    const int n = n0 + nl;
+                    const float A2 = s_A2[rl * N + n];
+                    const float carry = s_carry[rl * N + n];
+                    const float4v* bq = reinterpret_cast<const float4v*>(s_B) + (size_t)(nl * (K / 4)) * lpr + j;
+                    const float4v* cq = reinterpret_cast<const float4v*>(s_C) + (size_t)(nl * (K / 4)) * lpr + j;
 
-                float av[kItems], bv[kItems];
-                float h = 0.f;
+                    float av[K], bv[K];
+                    float h = 0.f;
 #pragma unroll
-                for (int i = 0; i < kItems; ++i) {
-                    av[i] = __builtin_amdgcn_exp2f(dl[i] * A2);
-                    bv[i] = du[i] * Bv[i];
-                    h = fmaf(av[i], h, bv[i]);
-                }
-                float P = __builtin_amdgcn_exp2f(S * A2);
-
-                // segmented inclusive scan of (P, h) over the lanes of the row inside this wave
-                for (int off = 1; off < seg; off <<= 1) {
-                    const float Po = __shfl_up(P, off, seg);
-                    const float ho = __shfl_up(h, off, seg);
-                    if ((lane & (seg - 1)) >= off) {
-                        h = fmaf(P, ho, h);
-                        P = P * Po;
+                    for (int q = 0; q < K / 4; ++q) {
+                        const float4v b4 = bq[q * lpr];
+                        const float be[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = 4 * q + e;
+                            av[i] = fast_exp2(dl[i] * A2);
+                            bv[i] = du[i] * be[e];
+                            h = fmaf(av[i], h, bv[i]);
+                        }
                     }
-                }
-                // exclusive prefix = inclusive value of the lane to the left
-                float Pex = __shfl_up(P, 1, seg);
-                float hex = __shfl_up(h, 1, seg);
-                if ((lane & (seg - 1)) == 0) { Pex = 1.f; hex = 0.f; }
-                if (lpr > 64) {                              // a row spans two waves: second wave adds the first's total
-                    if (lane == 63) { s_xchg[2 * wave] = P; s_xchg[2 * wave + 1] = h; }
-                    __syncthreads();
-                    if (wave & 1) {
-                        const float Pw = s_xchg[2 * (wave - 1)], hw = s_xchg[2 * (wave - 1) + 1];
+                    const float P = fast_exp2(S * A2);
+                    float Pex = P, hex = h;
+                    exclusive_scan_pairs(seg, jseg, Pex, hex);
+                    if (wpr > 1) {                           // a row spans several waves: add the totals of the waves before
+                        if (lane == 63) { s_xchg[2 * wave] = P * Pex; s_xchg[2 * wave + 1] = fmaf(P, hex, h); }
+                        __syncthreads();
+                        float Pw = 1.f, hw = 0.f;            // composition of the row's earlier waves, oldest first
+                        for (int w = 0; w < wpos; ++w) {
+                            const float Pi = s_xchg[2 * (wave - wpos + w)], hi = s_xchg[2 * (wave - wpos + w) + 1];
+                            hw = fmaf(Pi, hw, hi);
+                            Pw = Pw * Pi;
+                        }
                         hex = fmaf(Pex, hw, hex);
                         Pex = Pex * Pw;
                     }
-                }
-                float hh = fmaf(Pex, carry, hex);            // true state entering this lane's sub-block
+                    float hh = fmaf(Pex, carry, hex);        // true state entering this lane's sub-block
 #pragma unroll
-                for (int i = 0; i < kItems; ++i) {
-                    hh = fmaf(av[i], hh, bv[i]);
-                    yv[i] = fmaf(Cv[i], hh, yv[i]);
+                    for (int q = 0; q < K / 4; ++q) {
+                        const float4v c4 = cq[q * lpr];
+                        const float ce[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = 4 * q + e;
+                            hh = fmaf(av[i], hh, bv[i]);
+                            yv[i] = fmaf(ce[e], hh, yv[i]);
+                        }
+                    }
+                    if (wpr > 1) __syncthreads();            // exchange slots are reused by the next state
+                    if (active && j == lpr - 1) s_carry[rl * N + n] = hh;
                 }
-                if (lpr > 64) __syncthreads();               // exchange slots are reused by the next state
-                if (active && j == lpr - 1) s_carry[row_local * N + n] = hh;
             }
         }
 
         if (nstore > 0) {
+            float uu[K];
+            widen<T, K>(u_raw, uu);
             if (nvalid > 0 && z_row) {
-                float zz[kItems];
-                load_items<T>(z_row + t0, nvalid, vec, zz);
+                float zz[K];
+                widen<T, K>(load_raw<T, K>(z_row + t0, nvalid, vec), zz);
 #pragma unroll
-                for (int i = 0; i < kItems; ++i) yv[i] = (yv[i] + Dd * uu[i]) * silu(zz[i]);
+                for (int i = 0; i < K; ++i) yv[i] = fmaf(Dd, uu[i], yv[i]) * silu(zz[i]);
             } else {
 #pragma unroll
-                for (int i = 0; i < kItems; ++i) yv[i] = yv[i] + Dd * uu[i];
+                for (int i = 0; i < K; ++i) yv[i] = fmaf(Dd, uu[i], yv[i]);
             }
 #pragma unroll
-            for (int i = 0; i < kItems; ++i)
+            for (int i = 0; i < K; ++i)
                 if (i >= nvalid) yv[i] = 0.f;                // padded positions are written as zero
-            store_items<T>(y_row + t0, nstore, vec, yv);
+            store_items<T, K>(y_row + t0, nstore, vec, yv);
         }
-        __syncthreads();                                     // carried state visible to every lane of the row
     }
+    __syncthreads();                                         // last writes of the carried state are visible
 
     for (int i = tid; i < rows * N; i += kBlock) {
-        const int rl = i / N, n = i - rl * N;
-        const int dd = d0 + rl;
+        const int r = i / N, n = i - r * N;
+        const int dd = d0 + r;
         if (dd < a.D) a.last_state[((int64_t)b * a.D + dd) * N + n] = s_carry[i];
     }
 }
@@ -296,25 +473,31 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.seqlens = seqlens; a.chunks_dev = chunks_dev; a.y = y; a.last_state = last_state;
     a.L = L; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
-    // LDS budget for the carried state: rows * N floats, at most 32 KiB
-    int rows_cap = (int)(8192 / N);
+    // LDS budget for the per-row arrays (carried state and A): rows * N floats each, at most 16 KiB each
+    int rows_cap = (int)(4096 / N);
     if (rows_cap < 1) rows_cap = 1;
     if (rows_cap > kBlock) rows_cap = kBlock;
     a.rows_cap = rows_cap;
 
-    // Rows per workgroup follow from the chunk; with per-sequence device chunks the grid is sized for the
-    // fewest rows any legal chunk gives, and surplus workgroups leave at once.
-    const int lpr_host = (chunks_dev ? COREY_MAX_CHUNK : chunk) / kItems;
-    int rows_min = kBlock / lpr_host;
+    // Time steps per lane: 16 (fewer scan steps per value) unless the chunk is too short for that.
+    const int items = 16;
+    // Rows per workgroup follow from the chunk.  With per-sequence device chunks the grid is sized for the
+    // fewest rows any legal chunk gives (surplus workgroups leave at once) and LDS for the most.
+    const int lpr_grid = (chunks_dev ? COREY_MAX_CHUNK : chunk) / items;
+    const int lpr_lds = (chunks_dev ? COREY_MIN_CHUNK : chunk) / items;
+    int rows_min = lpr_grid >= kBlock ? 1 : kBlock / lpr_grid;
     if (rows_min > rows_cap) rows_min = rows_cap;
+    int rows_alloc = lpr_lds >= kBlock ? 1 : kBlock / lpr_lds;
+    if (rows_alloc > rows_cap) rows_alloc = rows_cap;
+    a.rows_alloc = rows_alloc;
     const int64_t gx = (D + rows_min - 1) / rows_min;
-    const size_t lds = ((size_t)rows_cap * N + 2 * (kBlock / 64)) * sizeof(float);
+    const size_t lds = ((size_t)2 * rows_alloc * N + 2 * kWaves + 2 * kTileElems) * sizeof(float);
     const dim3 grid((unsigned)gx, (unsigned)B);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (dt == COREY_F32)
-        k_selective_scan<float><<<grid, dim3(kBlock), lds, stream>>>(a);
+        k_selective_scan<float, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
     else
-        k_selective_scan<uint16_t><<<grid, dim3(kBlock), lds, stream>>>(a);
+        k_selective_scan<uint16_t, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "selective_scan_fwd launch");
     return COREY_OK;
