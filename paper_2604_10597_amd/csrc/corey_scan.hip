@@ -239,11 +239,11 @@ __device__ __forceinline__ void stage_operand(const T* __restrict__ src_seq, flo
                                               int64_t tile, int chunk, int lpr, int64_t len, int64_t L, bool vector_ok)
 {
     constexpr int V = Io<T>::kVec;
-    const int per_row = chunk / V;
-    const int units = ns * per_row;
+    const int per_row_log2 = __ffs(chunk / V) - 1;           // chunk and V are powers of two
+    const int units = ns << per_row_log2;
     for (int k = threadIdx.x; k < units; k += kBlock) {
-        const int nl = k / per_row;
-        const int tv = (k - nl * per_row) * V;                 // first step of this unit inside the tile
+        const int nl = k >> per_row_log2;
+        const int tv = (k - (nl << per_row_log2)) * V;         // first step of this unit inside the tile
         const int64_t t = tile + tv;
         const T* p = src_seq + (int64_t)(n0 + nl) * L + t;
         float v[V];
@@ -480,7 +480,10 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.rows_cap = rows_cap;
 
     // Time steps per lane: 16 (fewer scan steps per value) unless the chunk is too short for that.
-    const int items = 16;
+    // Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes, which pays when
+    // 16 would leave the chip short of waves (fewer than two per SIMD: 256 CUs x 4 SIMDs x 64 lanes x 2).
+    const int64_t chunk_for_plan = chunks_dev ? COREY_MAX_CHUNK : chunk;
+    const int items = (B * D * (chunk_for_plan / 16) < 131072) ? 8 : 16;
     // Rows per workgroup follow from the chunk.  With per-sequence device chunks the grid is sized for the
     // fewest rows any legal chunk gives (surplus workgroups leave at once) and LDS for the most.
     const int lpr_grid = (chunks_dev ? COREY_MAX_CHUNK : chunk) / items;
@@ -494,10 +497,13 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     const size_t lds = ((size_t)2 * rows_alloc * N + 2 * kWaves + 2 * kTileElems) * sizeof(float);
     const dim3 grid((unsigned)gx, (unsigned)B);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (dt == COREY_F32)
-        k_selective_scan<float, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
-    else
-        k_selective_scan<uint16_t, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
+    if (dt == COREY_F32) {
+        if (items == 8) k_selective_scan<float, 8><<<grid, dim3(kBlock), lds, stream>>>(a);
+        else k_selective_scan<float, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
+    } else {
+        if (items == 8) k_selective_scan<uint16_t, 8><<<grid, dim3(kBlock), lds, stream>>>(a);
+        else k_selective_scan<uint16_t, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "selective_scan_fwd launch");
     return COREY_OK;
