@@ -233,10 +233,11 @@ struct ScanArgs {
 
 // Convert the tile [n0, n0+ns) x [tile, tile+chunk) of one [N, L] operand to fp32 in LDS.
 // LDS layout: value (n, t) at ((n*(K/4) + (t%K)/4) * lpr + t/K) * 4 + t%4, so that for a fixed quarter of a
-// lane's K steps consecutive lanes read consecutive 16-byte words.
-template <typename T, int K>
-__device__ __forceinline__ void stage_operand(const T* __restrict__ src_seq, float* __restrict__ dst, int n0, int ns,
-                                              int64_t tile, int chunk, int lpr, int64_t len, int64_t L, bool vector_ok)
+// lane's K steps consecutive lanes read consecutive 16-byte words.  FULL: the whole tile lies inside the
+// sequence and rows are 16-byte aligned, so every unit is one vector load.
+template <typename T, int K, bool FULL>
+__device__ __forceinline__ void stage_operand(const T* __restrict__ src_tile, float* __restrict__ dst, int ns,
+                                              int chunk, int lpr, int64_t remaining, int64_t L)
 {
     constexpr int V = Io<T>::kVec;
     const int per_row_log2 = __ffs(chunk / V) - 1;           // chunk and V are powers of two
@@ -244,15 +245,14 @@ __device__ __forceinline__ void stage_operand(const T* __restrict__ src_seq, flo
     for (int k = threadIdx.x; k < units; k += kBlock) {
         const int nl = k >> per_row_log2;
         const int tv = (k - (nl << per_row_log2)) * V;         // first step of this unit inside the tile
-        const int64_t t = tile + tv;
-        const T* p = src_seq + (int64_t)(n0 + nl) * L + t;
+        const T* p = src_tile + (int64_t)nl * L + tv;
         float v[V];
-        const int nvalid = (t >= len) ? 0 : (len - t < V ? (int)(len - t) : V);
-        if (vector_ok && nvalid == V) {
+        if (FULL) {
             Io<T>::unpack(*reinterpret_cast<const uint4v*>(p), v);
         } else {
+            const int64_t left = remaining - tv;               // valid steps from this unit on
 #pragma unroll
-            for (int e = 0; e < V; ++e) v[e] = (e < nvalid) ? Io<T>::ld(p + e) : 0.f;
+            for (int e = 0; e < V; ++e) v[e] = (e < left) ? Io<T>::ld(p + e) : 0.f;
         }
         const int j = tv / K;
         const int q = (tv % K) / 4;
@@ -265,8 +265,9 @@ __device__ __forceinline__ void stage_operand(const T* __restrict__ src_seq, flo
     }
 }
 
-template <typename T, int K>
-__global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
+// At least three waves per SIMD: the register allocator must stay within 168 VGPRs (K = 16 sits at that edge).
+template <typename T, int K, bool SOFTPLUS>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) void k_selective_scan(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
     const int b = blockIdx.y;
@@ -329,11 +330,16 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
 
     for (int64_t tile = 0; tile < L; tile += chunk) {
         const int64_t t0 = tile + (int64_t)j * K;
-        // valid steps of this lane (within the sequence) and steps that get a y written (within L)
-        int nvalid = 0, nstore = 0;
-        if (active) {
-            nvalid = (t0 >= len) ? 0 : (len - t0 < K ? (int)(len - t0) : K);
-            nstore = (t0 >= L) ? 0 : (L - t0 < K ? (int)(L - t0) : K);
+        // A full tile lies inside the sequence with aligned rows: no masks anywhere (idle lanes read row d0).
+        const bool full = vec && tile + chunk <= len;       // uniform over the workgroup
+        // otherwise: valid steps of this lane (within the sequence) and steps that get a y written (within L)
+        int nvalid = K, nstore = K;
+        if (!full) {
+            nvalid = nstore = 0;
+            if (active) {
+                nvalid = (t0 >= len) ? 0 : (len - t0 < K ? (int)(len - t0) : K);
+                nstore = (t0 >= L) ? 0 : (L - t0 < K ? (int)(L - t0) : K);
+            }
         }
         const Raw<T, K> u_raw = load_raw<T, K>(u_row + t0, nvalid, vec);
         float dl[K], du[K], yv[K];
@@ -346,8 +352,8 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
 #pragma unroll
         for (int i = 0; i < K; ++i) {
             float v = dl[i] + bias;
-            if (a.softplus) v = softplus(v);
-            v = (i < nvalid) ? v : 0.f;                     // padded steps: dl = 0 -> a = 1, b = 0 (identity)
+            if (SOFTPLUS) v = softplus(v);
+            if (!full) v = (i < nvalid) ? v : 0.f;          // padded steps: dl = 0 -> a = 1, b = 0 (identity)
             dl[i] = v;
             du[i] = v * du[i];
             S += v;
@@ -357,9 +363,16 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
         if (tile < len) {                                   // uniform over the workgroup
             for (int n0 = 0; n0 < N; n0 += nsub) {
                 const int ns = (N - n0 < nsub) ? N - n0 : nsub;
+                const T* B_tile = B_seq + (int64_t)n0 * L + tile;
+                const T* C_tile = C_seq + (int64_t)n0 * L + tile;
                 __syncthreads();                            // previous group's readers are done (and s_carry/s_A2 are set)
-                stage_operand<T, K>(B_seq, s_B, n0, ns, tile, chunk, lpr, len, L, vec);
-                stage_operand<T, K>(C_seq, s_C, n0, ns, tile, chunk, lpr, len, L, vec);
+                if (full) {
+                    stage_operand<T, K, true>(B_tile, s_B, ns, chunk, lpr, 0, L);
+                    stage_operand<T, K, true>(C_tile, s_C, ns, chunk, lpr, 0, L);
+                } else {
+                    stage_operand<T, K, false>(B_tile, s_B, ns, chunk, lpr, len - tile, L);
+                    stage_operand<T, K, false>(C_tile, s_C, ns, chunk, lpr, len - tile, L);
+                }
                 __syncthreads();
                 for (int nl = 0; nl < ns; ++nl) {
                     const int n = n0 + nl;
@@ -415,7 +428,20 @@ __global__ __launch_bounds__(kBlock) void k_selective_scan(const ScanArgs a)
             }
         }
 
-        if (nstore > 0) {
+        if (full) {
+            float uu[K];
+            widen<T, K>(u_raw, uu);
+            if (z_row) {
+                float zz[K];
+                widen<T, K>(load_raw<T, K>(z_row + t0, K, true), zz);
+#pragma unroll
+                for (int i = 0; i < K; ++i) yv[i] = fmaf(Dd, uu[i], yv[i]) * silu(zz[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < K; ++i) yv[i] = fmaf(Dd, uu[i], yv[i]);
+            }
+            if (active) store_items<T, K>(y_row + t0, K, true, yv);
+        } else if (nstore > 0) {
             float uu[K];
             widen<T, K>(u_raw, uu);
             if (nvalid > 0 && z_row) {
@@ -497,13 +523,16 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     const size_t lds = ((size_t)2 * rows_alloc * N + 2 * kWaves + 2 * kTileElems) * sizeof(float);
     const dim3 grid((unsigned)gx, (unsigned)B);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const dim3 block(kBlock);
+#define COREY_LAUNCH(T, K, SP) k_selective_scan<T, K, SP><<<grid, block, lds, stream>>>(a)
+#define COREY_LAUNCH_SP(T, K) do { if (a.softplus) COREY_LAUNCH(T, K, true); else COREY_LAUNCH(T, K, false); } while (0)
     if (dt == COREY_F32) {
-        if (items == 8) k_selective_scan<float, 8><<<grid, dim3(kBlock), lds, stream>>>(a);
-        else k_selective_scan<float, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
+        if (items == 8) COREY_LAUNCH_SP(float, 8); else COREY_LAUNCH_SP(float, 16);
     } else {
-        if (items == 8) k_selective_scan<uint16_t, 8><<<grid, dim3(kBlock), lds, stream>>>(a);
-        else k_selective_scan<uint16_t, 16><<<grid, dim3(kBlock), lds, stream>>>(a);
+        if (items == 8) COREY_LAUNCH_SP(uint16_t, 8); else COREY_LAUNCH_SP(uint16_t, 16);
     }
+#undef COREY_LAUNCH_SP
+#undef COREY_LAUNCH
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "selective_scan_fwd launch");
     return COREY_OK;
