@@ -2,13 +2,17 @@
 //
 // Three sweeps, as the paper's estimation protocol states them (a min/max pass, a bin-count pass, an
 // O(K) reduction):
-//   k_entropy_init      clears counts and the range keys (a kernel, not a memset, so a caller may capture it)
+//   k_entropy_init      clears the partial counts and the range keys (a kernel, not a memset, so a caller may
+//                       capture it)
 //   k_entropy_range     lo/hi per histogram: 16-byte loads, wave + workgroup reduction, one pair of integer
 //                       atomics per workgroup on order-preserving keys
 //   k_entropy_count     bin index per value in binary32 (subtract, multiply, truncate: the ABI's definition),
-//                       counts privatised in LDS (one copy per wave) and merged with integer atomics, so the
+//                       counts privatised in LDS (several copies per workgroup) and merged with integer atomics, so the
 //                       result is exact and independent of scheduling
-//   k_entropy_finalise  p_k, H = -sum p log(p + eps) and r in double, one workgroup per histogram
+//                       (merged into kParts partial histograms in the workspace, so that the merging atomics
+//                       of many workgroups do not all queue on the same few cache lines)
+//   k_entropy_finalise  sums the partial histograms into counts, then p_k, H = -sum p log(p + eps) and r in
+//                       double, one workgroup per histogram
 // All of it is bandwidth work: no matrix instructions.
 #include <hip/hip_runtime.h>
 
@@ -22,6 +26,8 @@ using corey::bf16_to_f32;
 
 constexpr int kThreads = 256;
 constexpr int kVecBytes = 16;
+constexpr int kParts = 16;     // partial histograms per histogram in the workspace
+constexpr int kMaxBlocks = 1024;  // workgroups per sweep (four per compute unit)
 
 struct RangeSlot {        // one per histogram, in the caller's workspace
     uint32_t lo_key;      // order-preserving image of the minimum (0xffffffff: nothing seen)
@@ -74,50 +80,67 @@ __device__ __forceinline__ Geometry geometry(int h, int64_t B, int64_t D, int64_
     return g;
 }
 
+constexpr int kUnroll = 4;   // 16-byte loads a thread keeps in flight
+
 // Visit every sampled value of histogram `h` once: f(value).  A workgroup takes (row, segment) units
-// grid-stride; inside a unit every thread owns one 16-byte vector.  `vector_ok` says rows are 16-byte
-// aligned (pointer and L), otherwise values are fetched one by one.
+// grid-stride; inside a unit every thread owns kUnroll 16-byte vectors, kThreads vectors apart, all loaded
+// before any is consumed so that enough bytes are in flight to cover HBM latency.  `vector_ok` says rows are
+// 16-byte aligned (pointer and L); otherwise, and in the ragged last segment of a row, values are fetched
+// one by one.
 template <typename T, typename F>
 __device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, int64_t stride, bool vector_ok, F&& f)
 {
     constexpr int V = Elem<T>::kVec;
-    constexpr int64_t kSeg = (int64_t)kThreads * V;
+    constexpr int64_t kSeg = (int64_t)kThreads * V * kUnroll;
+    typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
     if (g.len == 0) return;
     const int64_t nseg = (g.len + kSeg - 1) / kSeg;
     const int64_t units = g.rows * nseg;
     for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
         const int64_t r = unit / nseg;
-        const int64_t t0 = (unit - r * nseg) * kSeg + (int64_t)threadIdx.x * V;
-        if (t0 >= g.len) continue;
-        const T* p = x + g.base + r * g.row_stride + t0;
-        const int nvalid = (g.len - t0 < V) ? (int)(g.len - t0) : V;
-        T v[V];
-        if (vector_ok && nvalid == V) {
-            typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
-            const vec4 raw = *reinterpret_cast<const vec4*>(p);
-            __builtin_memcpy(v, &raw, kVecBytes);
-        } else {
-            for (int e = 0; e < V; ++e) v[e] = (e < nvalid) ? p[e] : T(0);
-        }
-        if (stride == 1) {
+        const int64_t seg0 = (unit - r * nseg) * kSeg;
+        const T* row = x + g.base + r * g.row_stride;
+        if (vector_ok && seg0 + kSeg <= g.len) {               // uniform: the whole unit is in range
+            vec4 raw[kUnroll];
 #pragma unroll
-            for (int e = 0; e < V; ++e)
-                if (e < nvalid) f(Elem<T>::widen(v[e]));
-        } else {
-            int64_t phase = (r * g.len + t0) % stride;   // index of v[0] in memory order, modulo stride
+            for (int k = 0; k < kUnroll; ++k)
+                raw[k] = *reinterpret_cast<const vec4*>(row + seg0 + ((int64_t)k * kThreads + threadIdx.x) * V);
 #pragma unroll
-            for (int e = 0; e < V; ++e) {
-                if (e < nvalid && phase == 0) f(Elem<T>::widen(v[e]));
-                if (++phase == stride) phase = 0;
+            for (int k = 0; k < kUnroll; ++k) {
+                T v[V];
+                __builtin_memcpy(v, &raw[k], kVecBytes);
+                if (stride == 1) {
+#pragma unroll
+                    for (int e = 0; e < V; ++e) f(Elem<T>::widen(v[e]));
+                } else {
+                    const int64_t t0 = seg0 + ((int64_t)k * kThreads + threadIdx.x) * V;
+                    int64_t phase = (r * g.len + t0) % stride;     // index of v[0] in memory order, modulo stride
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        if (phase == 0) f(Elem<T>::widen(v[e]));
+                        if (++phase == stride) phase = 0;
+                    }
+                }
+            }
+        } else {
+            for (int k = 0; k < kUnroll; ++k) {
+                const int64_t t0 = seg0 + ((int64_t)k * kThreads + threadIdx.x) * V;
+                if (t0 >= g.len) break;
+                const int nvalid = (g.len - t0 < V) ? (int)(g.len - t0) : V;
+                int64_t phase = (stride == 1) ? 0 : (r * g.len + t0) % stride;
+                for (int e = 0; e < nvalid; ++e) {
+                    if (phase == 0) f(Elem<T>::widen(row[t0 + e]));
+                    if (stride != 1 && ++phase == stride) phase = 0;
+                }
             }
         }
     }
 }
 
-__global__ void k_entropy_init(uint32_t* counts, int64_t ncounts, RangeSlot* slots, int nh)
+__global__ void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots, int nh)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < ncounts) counts[i] = 0u;
+    if (i < nparts) parts[i] = 0u;
     if (i < nh) {
         slots[i].lo_key = 0xffffffffu;
         slots[i].hi_key = 0u;
@@ -126,20 +149,11 @@ __global__ void k_entropy_init(uint32_t* counts, int64_t ncounts, RangeSlot* slo
     }
 }
 
-template <typename T>
-__global__ __launch_bounds__(kThreads) void k_entropy_range(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
-                                                            const int32_t* __restrict__ seqlens, int64_t stride,
-                                                            int vector_ok, RangeSlot* slots)
+// Workgroup reduction of (lo, hi, nan flag) and the integer atomics that publish it.  The slot is read
+// first and an atomic is issued only if it would change it: extremes only move one way, so a stale read can
+// cost a redundant atomic but never lose an update, and almost all workgroups skip the contended atomics.
+__device__ __forceinline__ void publish_range(float lo, float hi, bool nan, RangeSlot* slot)
 {
-    const int h = blockIdx.y;
-    const Geometry g = geometry(h, B, D, L, seqlens);
-    float lo = INFINITY, hi = -INFINITY;
-    bool nan = false;
-    for_each_value(x, g, stride, vector_ok != 0, [&](float v) {
-        nan |= (v != v);
-        lo = fminf(lo, v);       // fminf/fmaxf drop a NaN operand; NaNs are flagged separately
-        hi = fmaxf(hi, v);
-    });
     uint32_t klo = (lo <= hi) ? order_key(lo) : 0xffffffffu;
     uint32_t khi = (lo <= hi) ? order_key(hi) : 0u;
     uint32_t knan = nan ? 1u : 0u;
@@ -158,10 +172,94 @@ __global__ __launch_bounds__(kThreads) void k_entropy_range(const T* __restrict_
             khi = max(khi, s_hi[w]);
             knan |= s_nan[w];
         }
-        if (klo != 0xffffffffu) atomicMin(&slots[h].lo_key, klo);
-        if (khi != 0u) atomicMax(&slots[h].hi_key, khi);
-        if (knan) atomicOr(&slots[h].saw_nan, 1u);
+        if (klo < __atomic_load_n(&slot->lo_key, __ATOMIC_RELAXED)) atomicMin(&slot->lo_key, klo);
+        if (khi > __atomic_load_n(&slot->hi_key, __ATOMIC_RELAXED)) atomicMax(&slot->hi_key, khi);
+        if (knan) atomicOr(&slot->saw_nan, 1u);
     }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_entropy_range(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
+                                                            const int32_t* __restrict__ seqlens, int64_t stride,
+                                                            int vector_ok, RangeSlot* slots)
+{
+    const int h = blockIdx.y;
+    const Geometry g = geometry(h, B, D, L, seqlens);
+    float lo = INFINITY, hi = -INFINITY;
+    bool nan = false;
+    for_each_value(x, g, stride, vector_ok != 0, [&](float v) {
+        nan |= (v != v);
+        lo = fminf(lo, v);       // fminf/fmaxf drop a NaN operand; NaNs are flagged separately
+        hi = fmaxf(hi, v);
+    });
+    publish_range(lo, hi, nan, &slots[h]);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Fast path for the common call: one histogram over the whole tensor, every value used, 16-byte aligned.
+// The tensor is then a flat array of 16-byte words; a workgroup walks it grid-stride with kUnroll loads in
+// flight per lane and nothing but straight-line code in between.
+
+// min/max that ignore a NaN operand (hardware behaviour of v_min3/v_max3 in IEEE mode), two values per
+// instruction; written as instructions so that no canonicalising v_max(x, x) is added per operand.
+__device__ __forceinline__ void minmax3(float& lo, float& hi, float a, float b)
+{
+    asm("v_min3_f32 %0, %0, %1, %2" : "+v"(lo) : "v"(a), "v"(b));
+    asm("v_max3_f32 %0, %0, %1, %2" : "+v"(hi) : "v"(a), "v"(b));
+}
+
+typedef uint32_t word4 __attribute__((ext_vector_type(4)));
+
+// Fold one 16-byte word into the running range.  `mag` tracks the largest magnitude bit pattern seen
+// (per 16-bit half for bf16), from which NaN (pattern above infinity's) is read off at the end.
+template <typename T> struct RangeFold;
+template <> struct RangeFold<uint16_t> {
+    typedef uint16_t half2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void fold(const word4& q, float& lo, float& hi, uint32_t& mag)
+    {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            minmax3(lo, hi, __uint_as_float(w[k] << 16), __uint_as_float(w[k] & 0xffff0000u));
+            half2 m, c;
+            const uint32_t a = w[k] & 0x7fff7fffu;
+            __builtin_memcpy(&m, &mag, 4);
+            __builtin_memcpy(&c, &a, 4);
+            m = __builtin_elementwise_max(m, c);
+            __builtin_memcpy(&mag, &m, 4);
+        }
+    }
+    static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return (mag & 0xffffu) > 0x7f80u || (mag >> 16) > 0x7f80u; }
+};
+template <> struct RangeFold<float> {
+    static __device__ __forceinline__ void fold(const word4& q, float& lo, float& hi, uint32_t& mag)
+    {
+        minmax3(lo, hi, __uint_as_float(q.x), __uint_as_float(q.y));
+        minmax3(lo, hi, __uint_as_float(q.z), __uint_as_float(q.w));
+        mag = max(max(mag, q.x & 0x7fffffffu), max(q.y & 0x7fffffffu, max(q.z & 0x7fffffffu, q.w & 0x7fffffffu)));
+    }
+    static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return mag > 0x7f800000u; }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_entropy_range_flat(const word4* __restrict__ x, int64_t nwords, RangeSlot* slots)
+{
+    float lo = INFINITY, hi = -INFINITY;
+    uint32_t mag = 0u;
+    const int64_t step = (int64_t)gridDim.x * kThreads * kUnroll;
+    int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll;
+    for (; base + kThreads * kUnroll <= nwords; base += step) {
+        word4 q[kUnroll];
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) q[k] = x[base + k * kThreads + threadIdx.x];
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) RangeFold<T>::fold(q[k], lo, hi, mag);
+    }
+    for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) {     // ragged end: at most one workgroup gets here
+        const word4 q = x[i];
+        RangeFold<T>::fold(q, lo, hi, mag);
+    }
+    publish_range(lo, hi, RangeFold<T>::saw_nan(mag), &slots[0]);
 }
 
 __device__ __forceinline__ bool usable_range(const RangeSlot& s, float* lo, float* hi)
@@ -172,24 +270,26 @@ __device__ __forceinline__ bool usable_range(const RangeSlot& s, float* lo, floa
     return isfinite(*lo) && isfinite(*hi);
 }
 
-constexpr int kMaxLdsBins = 4096;
+constexpr int kMaxLdsBins = 8192;   // uint32 counters in LDS (32 KiB)
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
                                                             const int32_t* __restrict__ seqlens, int64_t stride,
                                                             int vector_ok, int K, const RangeSlot* __restrict__ slots,
-                                                            uint32_t* counts)
+                                                            uint32_t* parts)
 {
     __shared__ uint32_t s_bins[kMaxLdsBins];
     const int h = blockIdx.y;
     float lo, hi;
     if (!usable_range(slots[h], &lo, &hi)) return;            // counts stay zero, H and r become NaN
     const Geometry g = geometry(h, B, D, L, seqlens);
-    // one private copy per wave while they fit, to spread same-bin collisions
-    const int copies = (K * (kThreads / 64) <= kMaxLdsBins) ? kThreads / 64 : 1;
+    // as many private copies as fit (up to one per pair of lanes of a wave): lanes of a wave that hit the same
+    // bin then mostly land on different addresses, which is what serialises LDS atomics
+    int copies = kMaxLdsBins / K;
+    copies = copies > 32 ? 32 : (copies < 1 ? 1 : copies);
     for (int i = threadIdx.x; i < K * copies; i += kThreads) s_bins[i] = 0u;
     __syncthreads();
-    uint32_t* mine = s_bins + ((copies > 1) ? (threadIdx.x >> 6) * K : 0);
+    uint32_t* mine = s_bins + (threadIdx.x % copies) * K;
 
     if (hi == lo) {
         uint32_t n = 0;
@@ -206,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict_
         });
     }
     __syncthreads();
-    uint32_t* out = counts + (int64_t)h * K;
+    uint32_t* out = parts + ((int64_t)h * kParts + blockIdx.x % kParts) * K;
     for (int k = threadIdx.x; k < K; k += kThreads) {
         uint32_t c = 0;
         for (int w = 0; w < copies; ++w) c += s_bins[w * K + k];
@@ -214,12 +314,69 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict_
     }
 }
 
-__global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* __restrict__ counts, int K, double eps,
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __restrict__ x, int64_t nwords, int K,
+                                                                 const RangeSlot* __restrict__ slots, uint32_t* parts)
+{
+    __shared__ uint32_t s_bins[kMaxLdsBins];
+    float lo, hi;
+    if (!usable_range(slots[0], &lo, &hi)) return;            // counts stay zero, H and r become NaN
+    int copies = kMaxLdsBins / K;
+    copies = copies > 32 ? 32 : (copies < 1 ? 1 : copies);
+    for (int i = threadIdx.x; i < K * copies; i += kThreads) s_bins[i] = 0u;
+    __syncthreads();
+    uint32_t* mine = s_bins + (threadIdx.x % copies) * K;
+    const bool flat = hi == lo;                               // degenerate range: everything in bin 0
+    const float scale = flat ? 0.f : (float)((double)K / ((double)hi - (double)lo));
+    const int top = K - 1;
+    auto bin = [&](float v) {
+        const float q = __fmul_rn(__fsub_rn(v, lo), scale);    // two separate binary32 roundings
+        int k = (int)q;                                        // truncation; q >= 0
+        k = flat ? 0 : (k > top ? top : k);
+        atomicAdd(&mine[k], 1u);
+    };
+    auto fold = [&](const word4& q) {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if constexpr (sizeof(T) == 2) {
+                bin(__uint_as_float(w[k] << 16));
+                bin(__uint_as_float(w[k] & 0xffff0000u));
+            } else {
+                bin(__uint_as_float(w[k]));
+            }
+        }
+    };
+    const int64_t step = (int64_t)gridDim.x * kThreads * kUnroll;
+    int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll;
+    for (; base + kThreads * kUnroll <= nwords; base += step) {
+        word4 q[kUnroll];
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) q[k] = x[base + k * kThreads + threadIdx.x];
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) fold(q[k]);
+    }
+    for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) fold(x[i]);
+    __syncthreads();
+    for (int k = threadIdx.x; k < K; k += kThreads) {
+        uint32_t c = 0;
+        for (int w = 0; w < copies; ++w) c += s_bins[w * K + k];
+        if (c) atomicAdd(&parts[(size_t)(blockIdx.x % kParts) * K + k], c);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* __restrict__ parts, uint32_t* counts, int K, double eps,
                                                                const RangeSlot* __restrict__ slots, double* H_out,
                                                                double* r_out, float* range_out)
 {
     const int h = blockIdx.x;
-    const uint32_t* c = counts + (int64_t)h * K;
+    uint32_t* c = counts + (int64_t)h * K;
+    const uint32_t* ph = parts + (int64_t)h * kParts * K;
+    for (int k = threadIdx.x; k < K; k += kThreads) {           // each thread later re-reads only what it wrote
+        uint32_t sum = 0;
+        for (int q = 0; q < kParts; ++q) sum += ph[(size_t)q * K + k];
+        c[k] = sum;
+    }
     float lo = 0.f, hi = 0.f;
     const bool ok = usable_range(slots[h], &lo, &hi);
     __shared__ double s_red[kThreads];
@@ -263,35 +420,46 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
     }
 }
 
-size_t workspace_bytes(int64_t nh)
+size_t slots_bytes(int64_t nh)
 {
     const size_t raw = (size_t)nh * sizeof(RangeSlot);
     return (raw + 255) / 256 * 256;
 }
+
+size_t workspace_bytes(int64_t nh, int32_t K) { return slots_bytes(nh) + (size_t)nh * kParts * K * sizeof(uint32_t); }
 
 template <typename T>
 int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K, double eps, int64_t stride,
            uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream)
 {
     const int nh = seqlens ? (int)B : 1;
-    const int64_t ncounts = (int64_t)nh * K;
-    const int64_t init_items = ncounts > nh ? ncounts : nh;
-    k_entropy_init<<<dim3((unsigned)((init_items + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(
-        counts, ncounts, slots, nh);
+    uint32_t* parts = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(slots) + slots_bytes(B));
+    const int64_t nparts = (int64_t)nh * kParts * K;
+    k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
 
     constexpr int V = Elem<T>::kVec;
-    const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
-    const int64_t rows = seqlens ? D : B * D;
-    const int64_t units = rows * ((L + (int64_t)kThreads * V - 1) / ((int64_t)kThreads * V));
-    int64_t blocks = units < 1 ? 1 : units;
-    const int64_t cap = 256 * 8;                       // a few workgroups per compute unit
-    if (blocks > cap) blocks = cap;
-    const dim3 grid((unsigned)blocks, (unsigned)nh);
-    k_entropy_range<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride,
-                                                           vector_ok ? 1 : 0, slots);
-    k_entropy_count<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride,
-                                                           vector_ok ? 1 : 0, K, slots, counts);
-    k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(counts, K, eps, slots, H_out, r_out, range_out);
+    const int64_t E = B * D * L;
+    if (!seqlens && stride == 1 && reinterpret_cast<uintptr_t>(x) % kVecBytes == 0 && E % V == 0) {
+        // whole tensor, every value, aligned: flat sweeps
+        const int64_t nwords = E / V;
+        int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
+        blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
+        k_entropy_range_flat<T><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(static_cast<const word4*>(x), nwords, slots);
+        k_entropy_count_flat<T><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(static_cast<const word4*>(x), nwords, K, slots, parts);
+    } else {
+        const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
+        const int64_t rows = seqlens ? D : B * D;
+        const int64_t seg = (int64_t)kThreads * V * kUnroll;
+        const int64_t units = rows * ((L + seg - 1) / seg);
+        int64_t blocks = units < 1 ? 1 : units;
+        if (blocks > kMaxBlocks) blocks = kMaxBlocks;
+        const dim3 grid((unsigned)blocks, (unsigned)nh);
+        k_entropy_range<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride,
+                                                               vector_ok ? 1 : 0, slots);
+        k_entropy_count<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride,
+                                                               vector_ok ? 1 : 0, K, slots, parts);
+    }
+    k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, slots, H_out, r_out, range_out);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "corey_entropy_hist launch");
     return COREY_OK;
@@ -302,7 +470,7 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
 extern "C" size_t corey_entropy_hist_workspace(int64_t B, int32_t K)
 {
     if (B < 1 || K < 2 || K > COREY_MAX_BINS) return 0;
-    return workspace_bytes(B);
+    return workspace_bytes(B, K);
 }
 
 extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
@@ -320,7 +488,7 @@ extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int6
     if (K < 2 || K > COREY_MAX_BINS) return fail(COREY_EINVAL, "corey_entropy_hist: K = %d outside [2, %d]", K, COREY_MAX_BINS);
     if (!(eps >= 0.0)) return fail(COREY_EINVAL, "corey_entropy_hist: eps must be >= 0");
     if (stride < 1) return fail(COREY_EINVAL, "corey_entropy_hist: stride must be >= 1");
-    const size_t need = workspace_bytes(B);
+    const size_t need = workspace_bytes(B, K);
     if (!workspace || workspace_bytes_given < need)
         return fail(COREY_EWORKSPACE, "corey_entropy_hist: workspace of %zu bytes required", need);
     if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "corey_entropy_hist: workspace must be 16-byte aligned");
