@@ -2,7 +2,8 @@
 """Benchmark of the COREY hot path on one MI355X.
 
 One step = one pass of the whole path over one batch that already sits in HBM: corey_entropy_hist on u,
-a read of r, corey_select_chunk on the host, selective_scan_fwd with the routed chunk.  Prints ONE JSON line.
+corey_select_chunk_device on r, selective_scan_fwd reading the routed chunk from device memory (no host round
+trip inside a step).  Prints ONE JSON line.
 
   value      scan algorithmic bytes (u, delta, z in; y out; B, C, parameters, final state) per step time, GB/s
   roofline   for the dominant kernel (the scan): algorithmic bytes / its own launch duration, measured with
@@ -83,7 +84,17 @@ def main() -> int:
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
                                  delta_bias=d["delta_bias"], seqlens=seqlens, chunk=chunk, y=y, last_state=last)
 
-    def route():
+    chunks_dev = torch.empty(ent["r"].numel(), dtype=torch.int32, device="cuda")
+
+    def scan_routed():
+        """The whole path with no host round trip: statistic -> chunk rule on the GPU -> scan that reads the chunk."""
+        corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
+        corey.corey_select_chunk_device(ent["r"], cfg.L, pol, seqlens=seqlens, out=chunks_dev)
+        corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
+                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=512, chunks_dev=chunks_dev,
+                                 y=y, last_state=last)
+
+    def route_on_host():
         corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
         r_pinned.copy_(ent["r"], non_blocking=True)
         torch.cuda.current_stream().synchronize()              # the host needs r to pick the launch shape
@@ -94,19 +105,32 @@ def main() -> int:
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     for _ in range(args.warmup):
-        scan(route())
+        scan_routed()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    chunk = None
     for i in range(args.steps):
-        chunk = route()
+        corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
+        corey.corey_select_chunk_device(ent["r"], cfg.L, pol, seqlens=seqlens, out=chunks_dev)
         ev0[i].record()
-        scan(chunk)
+        corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
+                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=512, chunks_dev=chunks_dev,
+                                 y=y, last_state=last)
         ev1[i].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / args.steps
     scan_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev0, ev1)]))
+    chunk = int(chunks_dev.max().item())
+
+    # the same step with the chunk rule on the host (one 8-byte read of r and a synchronisation per step)
+    for _ in range(2):
+        scan(route_on_host())
+    torch.cuda.synchronize()
+    t0h = time.perf_counter()
+    for i in range(args.steps):
+        scan(route_on_host())
+    torch.cuda.synchronize()
+    ms_step_host = (time.perf_counter() - t0h) * 1e3 / args.steps
 
     def time_scan(c, warm, reps):
         for _ in range(warm):
@@ -182,6 +206,8 @@ def main() -> int:
                 "frac": round(scan_flop / scan_ms * 1e-9 / FP32_VECTOR_PEAK_TFLOPS, 4),
                 "flop_per_state_update": 7, "state_updates": state_updates},
         "overhead": {"entropy_routing_pct_of_scan": round((ms_step - scan_alone_ms) / scan_alone_ms * 100, 2),
+                     "host_routed_ms_per_step": round(ms_step_host, 4),
+                     "host_routed_pct_of_scan": round((ms_step_host - scan_alone_ms) / scan_alone_ms * 100, 2),
                      "hist_kernels_ms": round(hist_ms, 4), "scan_alone_ms": round(scan_alone_ms, 4),
                      "hist_pct_of_scan": round(hist_ms / scan_alone_ms * 100, 2)},
         "per_chunk": per_chunk,

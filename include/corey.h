@@ -124,6 +124,24 @@ int corey_policy_default(corey_policy* p);
 int corey_select_chunk(double r, int64_t L, const corey_policy* p, int32_t* chunk_out);
 
 /* -------------------------------------------------------------------------------------------------------
+ * corey_select_chunk_device -- the same rule, evaluated on the GPU for nh values of r that are still in
+ * device memory, so that a routed scan needs no host round trip (the paper names the synchronisation around
+ * runtime feature collection as one of the costs of routing).
+ *
+ *   r_dev        DEVICE double[nh]   (r_out of corey_entropy_hist).
+ *   seqlens      DEVICE int32[nh] or NULL: the sequence length each decision is taken for; NULL uses L for all.
+ *   p            HOST policy (copied at call time).
+ *   chunks_out   DEVICE int32[nh]: the chunk per histogram, directly usable as `chunks_dev` of selective_scan_fwd.
+ *                An entry whose r is NaN in an entropy mode is written as 0, which selective_scan_fwd treats as
+ *                "use the host chunk".
+ * Same arithmetic as corey_select_chunk (double precision, round = floor(v + 0.5)); the device log2 can differ
+ * from the host's in the last bit, which matters only within ~1e-15 of a rounding tie of Eq. 2.
+ * Errors (host side, before the launch): COREY_ENULL, COREY_EINVAL as for corey_select_chunk, nh < 1.
+ * ----------------------------------------------------------------------------------------------------- */
+int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64_t L, int32_t nh,
+                              const corey_policy* p, int32_t* chunks_out, void* hip_stream);
+
+/* -------------------------------------------------------------------------------------------------------
  * selective_scan_fwd -- the recurrence h_t = A_t h_{t-1} + B_t x_t, y_t = C_t h_t + D_t x_t (Method,
  * Preliminaries) in its Mamba-1 form, for every sequence b and channel d independently:
  *

@@ -18,6 +18,7 @@ COREY_F32, COREY_BF16 = 0, 1
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
+           "corey_select_chunk_device",
            "selective_scan_fwd", "corey_last_error", "corey_version")
 
 
@@ -55,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.corey_policy_default.argtypes = [ctypes.POINTER(Policy)]
         L.corey_select_chunk.restype = ctypes.c_int
         L.corey_select_chunk.argtypes = [dbl, i64, ctypes.POINTER(Policy), ctypes.POINTER(i32)]
+        L.corey_select_chunk_device.restype = ctypes.c_int
+        L.corey_select_chunk_device.argtypes = [vp, vp, i64, i32, ctypes.POINTER(Policy), vp, vp]
         L.selective_scan_fwd.restype = ctypes.c_int
         L.selective_scan_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, vp, vp, vp,
                                          ctypes.c_int, i64, i64, i64, i64, vp]
@@ -133,6 +136,20 @@ def corey_select_chunk(r: float, L: int, policy: Policy | None = None) -> int:
     c = ctypes.c_int32(0)
     _check(lib().corey_select_chunk(float(r), int(L), ctypes.byref(p), ctypes.byref(c)))
     return c.value
+
+
+def corey_select_chunk_device(r_dev: torch.Tensor, L: int, policy: Policy | None = None, seqlens: torch.Tensor | None = None,
+                              out: torch.Tensor | None = None) -> torch.Tensor:
+    """r_dev: float64 GPU tensor [nh].  Returns an int32 GPU tensor [nh] of chunks (no synchronisation)."""
+    _dev(r_dev, "r_dev"), _dev(seqlens, "seqlens")
+    if r_dev.dtype != torch.float64:
+        raise TypeError("r_dev must be float64")
+    p = policy if policy is not None else policy_default()
+    nh = r_dev.numel()
+    if out is None:
+        out = torch.empty(nh, dtype=torch.int32, device=r_dev.device)
+    _check(lib().corey_select_chunk_device(_ptr(r_dev), _ptr(seqlens), int(L), nh, ctypes.byref(p), _ptr(out), _stream()))
+    return out
 
 
 def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True, h0=None,

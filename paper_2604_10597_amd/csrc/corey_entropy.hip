@@ -420,6 +420,44 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
     }
 }
 
+// Eq. 2 and the scheduler family around it, one thread per histogram (see corey_select_chunk for the rule).
+__global__ void k_select_chunk(const double* __restrict__ r, const int32_t* __restrict__ seqlens, int64_t L_all, int nh,
+                               corey_policy p, int32_t* __restrict__ chunks)
+{
+    const int h = blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= nh) return;
+    int64_t L = seqlens ? (int64_t)seqlens[h] : L_all;
+    if (L < 1) L = 1;
+    const bool short_seq = L <= p.short_len;
+    int64_t c;
+    if (p.mode == 3) {
+        c = p.static_chunk;
+    } else if (p.mode == 2) {
+        c = short_seq ? p.short_chunk : p.long_chunk;
+    } else if (p.mode == 1 && short_seq) {
+        c = p.short_chunk;
+    } else {
+        const double rv = r[h];
+        if (rv != rv) { chunks[h] = 0; return; }
+        double re = rv * p.h_ref_scale;
+        re = re < 0.0 ? 0.0 : (re > 1.0 ? 1.0 : re);
+        const double target = (double)p.c_min + re * (double)(p.c_max - p.c_min);
+        const double k = floor(log2(target) + 0.5);
+        c = (int64_t)1 << (int)k;
+        c = c < p.c_min ? p.c_min : (c > p.c_max ? p.c_max : c);
+        if (p.mode == 4) {
+            int away = (63 - __clzll((long long)c)) - (63 - __clzll((long long)p.safe_chunk));
+            away = away < 0 ? -away : away;
+            if (away < p.guard_buckets) c = p.safe_chunk;
+        }
+        int64_t cap = 1;
+        while (cap < L) cap <<= 1;
+        if (cap < p.c_min) cap = p.c_min;
+        if (c > cap) c = cap;
+    }
+    chunks[h] = (int32_t)c;
+}
+
 size_t slots_bytes(int64_t nh)
 {
     const size_t raw = (size_t)nh * sizeof(RangeSlot);
@@ -466,6 +504,25 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
 }
 
 }  // namespace
+
+extern "C" int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64_t L, int32_t nh,
+                                         const corey_policy* p, int32_t* chunks_out, void* hip_stream)
+{
+    using corey::fail;
+    using corey::is_pow2;
+    if (!r_dev || !p || !chunks_out) return fail(COREY_ENULL, "corey_select_chunk_device: r_dev, p and chunks_out are required");
+    if (nh < 1) return fail(COREY_EINVAL, "corey_select_chunk_device: nh = %d < 1", nh);
+    if (!seqlens && L < 1) return fail(COREY_EINVAL, "corey_select_chunk_device: L = %lld < 1", (long long)L);
+    // validate the policy on the host with the host rule (r = 0.5 is a placeholder that no mode rejects)
+    int32_t probe = 0;
+    const int st = corey_select_chunk(0.5, L < 1 ? 1 : L, p, &probe);
+    if (st != COREY_OK) return st;
+    if (p->mode == 1 && !is_pow2(p->short_chunk)) return fail(COREY_EINVAL, "corey_select_chunk_device: short_chunk = %d", p->short_chunk);
+    k_select_chunk<<<dim3((unsigned)((nh + 63) / 64)), dim3(64), 0, static_cast<hipStream_t>(hip_stream)>>>(r_dev, seqlens, L, nh, *p, chunks_out);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return corey::hip_fail(e, "corey_select_chunk_device launch");
+    return COREY_OK;
+}
 
 extern "C" size_t corey_entropy_hist_workspace(int64_t B, int32_t K)
 {

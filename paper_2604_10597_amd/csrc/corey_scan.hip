@@ -499,10 +499,11 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.seqlens = seqlens; a.chunks_dev = chunks_dev; a.y = y; a.last_state = last_state;
     a.L = L; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
-    // LDS budget for the per-row arrays (carried state and A): rows * N floats each, at most 16 KiB each
+    // LDS budget for the per-row arrays (carried state and A): at most 64 rows and 16 KiB each.  64 rows fill
+    // the workgroup for every chunk >= 64; shorter chunks run with idle lanes.
     int rows_cap = (int)(4096 / N);
     if (rows_cap < 1) rows_cap = 1;
-    if (rows_cap > kBlock) rows_cap = kBlock;
+    if (rows_cap > 64) rows_cap = 64;
     a.rows_cap = rows_cap;
 
     // Time steps per lane: 16 (fewer scan steps per value) unless the chunk is too short for that.

@@ -113,6 +113,55 @@ def test_per_sequence_device_chunks():
         assert np.array_equal(yb[b], y[b]) and np.array_equal(sb[b], s[b])
 
 
+def test_device_side_routing_matches_the_oracle_rule():
+    import math
+    import oracle
+    _say("device chunk rule")
+    rs = np.concatenate([np.linspace(0.0, 1.0, 801), [float("nan"), -0.5, 1.5]])
+    r_dev = torch.from_numpy(rs).cuda()
+    for mode in (0, 1, 2, 3, 4):
+        for cmin, cmax in ((64, 2048), (32, 512)):
+            for scale in (1.0, math.log(256) / 8.0):
+                for L in (25, 50, 51, 300, 16384):
+                    pol, opol = corey.policy_default(), oracle.policy(mode=mode, c_min=cmin, c_max=cmax, h_ref_scale=scale)
+                    pol.mode, pol.c_min, pol.c_max, pol.h_ref_scale = mode, cmin, cmax, scale
+                    got = corey.corey_select_chunk_device(r_dev, L, pol).cpu().numpy()
+                    for r, g in zip(rs, got):
+                        st, c, margin = oracle.select_chunk(float(r), L, opol)
+                        if st == oracle.ENONFINITE:
+                            assert g == 0
+                        elif margin < 0 or margin > 1e-12:          # away from a rounding tie of Eq. 2
+                            assert g == c, (mode, cmin, cmax, scale, L, r, g, c)
+    # per-sequence lengths
+    lens = torch.tensor([25, 50, 51, 4096], dtype=torch.int32, device="cuda")
+    pol = corey.policy_default()
+    pol.mode = 2
+    got = corey.corey_select_chunk_device(torch.zeros(4, dtype=torch.float64, device="cuda"), 1, pol, seqlens=lens)
+    assert got.cpu().tolist() == [128, 128, 512, 512]
+
+
+def test_routed_scan_without_host_round_trip():
+    cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], D=32, L=2048, B=3, seqlens=(2048, 40, 700))
+    w = wl.make(cfg)
+    d = upload(w)
+    _say("scan routed on device")
+    ent = corey.corey_entropy_hist(d["u"], cfg.K, seqlens=d["seqlens"])
+    pol = corey.policy_default()
+    pol.mode = 1                                              # sequence-length gate, then the entropy rule
+    chunks = corey.corey_select_chunk_device(ent["r"], cfg.L, pol, seqlens=d["seqlens"])
+    y, s = _run(d, 512, chunks_dev=chunks)                    # no synchronisation between the three calls
+    import oracle
+    ref = oracle.entropy_hist(w.val["u"], cfg.K, seqlens=w.seqlens)
+    expect = [oracle.select_chunk(float(ref["r"][b]), int(w.seqlens[b]), oracle.policy(mode=1))[1] for b in range(3)]
+    assert chunks.cpu().tolist() == expect and expect[1] == 128
+    y_ref, s_ref = oracle_scan(w)
+    assert_close(y, y_ref, y_rtol(cfg), "routed y", True)
+    assert_close(s, s_ref, fp32_rtol(cfg.L), "routed state")
+    for b, c in enumerate(expect):                            # each sequence ran with its own chunk
+        yb, _ = _run(d, c)
+        assert np.array_equal(yb[b], y[b])
+
+
 def test_invariants_on_the_gpu_path():
     cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=32, L=1024)
     w = wl.make(cfg, a_kind="random")
