@@ -74,6 +74,7 @@ def main() -> int:
     # algorithmic flops per state update: 2 mul + 2 fma (6 flop) + 1 exp counted as one
     scan_flop = 7.0 * state_updates
 
+    scan_ws = torch.empty(corey.selective_scan_fwd_workspace(cfg.B, cfg.N, cfg.L), dtype=torch.uint8, device="cuda")
     y = torch.empty_like(d["u"])
     last = torch.empty((cfg.B, cfg.D, cfg.N), dtype=torch.float32, device="cuda")
     ent = corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens)
@@ -82,7 +83,7 @@ def main() -> int:
 
     def scan(chunk):
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
-                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=chunk, y=y, last_state=last)
+                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=chunk, y=y, last_state=last, workspace=scan_ws)
 
     chunks_dev = torch.empty(ent["r"].numel(), dtype=torch.int32, device="cuda")
 
@@ -92,7 +93,7 @@ def main() -> int:
         corey.corey_select_chunk_device(ent["r"], cfg.L, pol, seqlens=seqlens, out=chunks_dev)
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
                                  delta_bias=d["delta_bias"], seqlens=seqlens, chunk=512, chunks_dev=chunks_dev,
-                                 y=y, last_state=last)
+                                 y=y, last_state=last, workspace=scan_ws)
 
     def route_on_host():
         corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
@@ -114,7 +115,7 @@ def main() -> int:
         ev0[i].record()
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
                                  delta_bias=d["delta_bias"], seqlens=seqlens, chunk=512, chunks_dev=chunks_dev,
-                                 y=y, last_state=last)
+                                 y=y, last_state=last, workspace=scan_ws)
         ev1[i].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()

@@ -164,6 +164,8 @@ int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64
  *   chunks_dev       DEVICE int32[B] or NULL: per-sequence chunk (same constraints) that overrides `chunk`
  *                    without a host round trip; out-of-range or non-power-of-two entries fall back to `chunk`.
  *   last_state       DEVICE float[B, D, N], required.
+ *   workspace        DEVICE, at least selective_scan_fwd_workspace(B, N, L) bytes, 16-byte aligned; scratch only
+ *                    (the call first rewrites B and C there as fp32 in the order the scan reads them).
  *   1 <= N <= COREY_MAX_STATE;  B*D*L and B*N*L must fit in int64 and B*D in int32.
  * y and last_state may not alias any input.  Accuracy against a double-precision evaluation of the same
  * bits: about 1e-6 relative to the row's scale for fp32 storage; for bf16 storage y carries one bf16
@@ -173,7 +175,12 @@ int selective_scan_fwd(const void* u, const void* delta, const float* A, const v
                        const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
                        const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
                        void* y, float* last_state, corey_dtype dt,
-                       int64_t B, int64_t D, int64_t N, int64_t L, void* hip_stream);
+                       int64_t B, int64_t D, int64_t N, int64_t L,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace selective_scan_fwd needs (0 if the arguments are invalid): room for B and C as fp32,
+ * padded along L to whole tiles, 2 * B * N * (L + 2048 rounded up to 4) * 4. */
+size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L);
 
 /* Message for the most recent failing call on this thread ("" if none).  Static storage; do not free. */
 const char* corey_last_error(void);

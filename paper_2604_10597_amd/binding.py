@@ -19,7 +19,7 @@ STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
            "corey_select_chunk_device",
-           "selective_scan_fwd", "corey_last_error", "corey_version")
+           "selective_scan_fwd", "selective_scan_fwd_workspace", "corey_last_error", "corey_version")
 
 
 class CoreyError(RuntimeError):
@@ -60,7 +60,9 @@ def lib() -> ctypes.CDLL:
         L.corey_select_chunk_device.argtypes = [vp, vp, i64, i32, ctypes.POINTER(Policy), vp, vp]
         L.selective_scan_fwd.restype = ctypes.c_int
         L.selective_scan_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, vp, vp, vp,
-                                         ctypes.c_int, i64, i64, i64, i64, vp]
+                                         ctypes.c_int, i64, i64, i64, i64, vp, ctypes.c_size_t, vp]
+        L.selective_scan_fwd_workspace.restype = ctypes.c_size_t
+        L.selective_scan_fwd_workspace.argtypes = [i64, i64, i64]
         L.corey_last_error.restype = ctypes.c_char_p
         L.corey_version.restype = ctypes.c_char_p
         _lib = L
@@ -152,9 +154,14 @@ def corey_select_chunk_device(r_dev: torch.Tensor, L: int, policy: Policy | None
     return out
 
 
+def selective_scan_fwd_workspace(B: int, N: int, L: int) -> int:
+    return int(lib().selective_scan_fwd_workspace(B, N, L))
+
+
 def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True, h0=None,
-                       seqlens=None, chunk: int = 512, chunks_dev=None, y=None, last_state=None):
-    """Tensors as in include/corey.h.  Returns (y, last_state); enqueues on torch's current stream."""
+                       seqlens=None, chunk: int = 512, chunks_dev=None, y=None, last_state=None, workspace=None):
+    """Tensors as in include/corey.h.  Returns (y, last_state); enqueues on torch's current stream.
+    `workspace`: uint8 GPU tensor of selective_scan_fwd_workspace(B, N, L) bytes (allocated here if omitted)."""
     for name, t in (("u", u), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dv", Dv), ("z", z),
                     ("delta_bias", delta_bias), ("h0", h0), ("seqlens", seqlens), ("chunks_dev", chunks_dev)):
         _dev(t, name)
@@ -172,7 +179,10 @@ def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, de
         y = torch.empty_like(u)
     if last_state is None:
         last_state = torch.empty((B, D, N), dtype=torch.float32, device=u.device)
+    if workspace is None:
+        workspace = torch.empty(selective_scan_fwd_workspace(B, N, L), dtype=torch.uint8, device=u.device)
     _check(lib().selective_scan_fwd(_ptr(u), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dv), _ptr(z),
                                     _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(h0), _ptr(seqlens), int(chunk),
-                                    _ptr(chunks_dev), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L, _stream()))
+                                    _ptr(chunks_dev), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L,
+                                    _ptr(workspace), workspace.numel(), _stream()))
     return y, last_state

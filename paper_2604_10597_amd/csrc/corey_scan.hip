@@ -1,17 +1,25 @@
 // selective_scan_fwd: Mamba-1 selective-scan forward with a run-time chunk on gfx950.
 //
-// Mapping.  A workgroup of 256 lanes owns `rows` channels of one sequence and walks the time axis in
-// tiles of `chunk` steps.  Inside a tile a row is spread over chunk/16 consecutive lanes, each lane owning
-// 16 consecutive time steps, so loads of u/delta/z and the store of y are contiguous along L (16-byte
-// vectors per lane).  B and C of the tile are shared by every row of the workgroup: they are converted to
-// fp32 once, cooperatively, into LDS (a few states at a time when the chunk is long) in a layout that lets
-// consecutive lanes read consecutive 16-byte words.  For every state index n a lane
-//   1. discretises its 16 steps (a_i = exp2(dl_i A log2e), b_i = dl_i B_i u_i) and folds them, from a zero
+// Two kernels per call.
+//
+// k_relayout_bc   converts B and C ([B, N, L], bf16 or fp32) once to fp32 in the caller's workspace, tile by
+//                 tile, in exactly the order the scan's lanes read them.  B and C are shared by every channel of
+//                 a sequence, so doing this once per call instead of once per workgroup removes all conversion
+//                 work from the scan (a few MB of traffic against the scan's hundreds).
+//
+// k_selective_scan   A workgroup of 256 lanes owns `rows` channels of one sequence and walks the time axis in
+//                 tiles of `chunk` steps.  Inside a tile a row is spread over chunk/K consecutive lanes, each lane
+//                 owning K (16 or 8) consecutive time steps, so loads of u/delta/z and the store of y are
+//                 contiguous along L (16-byte vectors per lane).  The fp32 B/C values of a few states at a time
+//                 are copied from the workspace straight into LDS (global_load_lds, no registers), double
+//                 buffered: the copy for the next group of states is in flight while the current one is
+//                 computed.  For every state index n a lane
+//   1. discretises its K steps (a_i = exp2(dl_i A log2e), b_i = dl_i B_i u_i) and folds them, from a zero
 //      state, into the pair (P, h) that represents the affine map  x -> P x + h  of its sub-block
 //      (P itself comes from one exp2 of the summed dl);
 //   2. obtains the composition of all pairs to its left in the row by a DPP scan across lanes (the pair
-//      operator is associative); a row of 128 lanes crosses the wave boundary through LDS;
-//   3. replays its 16 steps from the true incoming state (prefix pair applied to the state carried from
+//      operator is associative); rows wider than a wave cross the wave boundary through LDS;
+//   3. replays its K steps from the true incoming state (prefix pair applied to the state carried from
 //      the previous tile) and accumulates y_i += C_i h_i.
 // The fp32 state carried from tile to tile lives in LDS; the last lane of a row refreshes it.
 // The work is a recurrence plus elementwise maths: no matrix instructions.
@@ -26,7 +34,8 @@ using corey::f32_to_bf16;
 
 constexpr int kBlock = 256;       // lanes per workgroup
 constexpr int kWaves = kBlock / 64;
-constexpr int kTileElems = 4096;  // fp32 values of B (and of C) staged in LDS at a time
+constexpr int kStageElems = 2048; // fp32 values of B (and of C) per LDS staging buffer (two buffers)
+constexpr int kPad = COREY_MAX_CHUNK;  // the relaid-out time axis is padded to whole tiles
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -158,11 +167,12 @@ __device__ __forceinline__ float silu(float z)
 // first lane of a segment).  The pairs are first moved one lane to the right, then combined by a
 // Hillis-Steele scan whose steps are single DPP instructions:  h += h[lane - s] * P ;  P *= P[lane - s];
 // lanes without a source (DPP bound control off) keep their value, which is composing with the identity.
-// The instructions are written out because the hazard rules matter: a DPP operand written by the previous
-// VALU instruction needs two wait states (s_nop 1), and five after a VALU write of EXEC (s_nop 4 up front).
+// The instructions are written out because the hazard rules matter: a DPP source register needs two wait
+// states after the VALU write that produced it (here: one other instruction plus s_nop 0), and five after a
+// VALU write of EXEC (s_nop 4 up front).
 #define COREY_DPP_STEP(ctrl)                                                               \
-    "s_nop 1\n\tv_fmac_f32_dpp %0, %0, %1 " ctrl " bank_mask:0xf\n\t"                      \
-    "s_nop 1\n\tv_mul_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t"
+    "s_nop 0\n\tv_fmac_f32_dpp %0, %0, %1 " ctrl " bank_mask:0xf\n\t"                      \
+    "s_nop 0\n\tv_mul_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t"
 #define COREY_ROW_STEPS                                                                    \
     COREY_DPP_STEP("row_shr:1 row_mask:0xf") COREY_DPP_STEP("row_shr:2 row_mask:0xf")      \
     COREY_DPP_STEP("row_shr:4 row_mask:0xf") COREY_DPP_STEP("row_shr:8 row_mask:0xf")
@@ -222,7 +232,9 @@ struct ScanArgs {
     const int32_t* chunks_dev;
     void* y;
     float* last_state;
-    int64_t L;
+    float* ws_B;            // relaid-out fp32 B, [B][N * Lpad]
+    float* ws_C;
+    int64_t L, Lpad;
     int32_t D, N;
     int32_t chunk;          // host chunk (also the fallback for invalid device entries)
     int32_t rows_cap;       // most rows a workgroup may hold (LDS budget for the carried state)
@@ -231,36 +243,68 @@ struct ScanArgs {
     int32_t vector_ok;      // rows of the [.., L] tensors are 16-byte aligned
 };
 
-// Convert the tile [n0, n0+ns) x [tile, tile+chunk) of one [N, L] operand to fp32 in LDS.
-// LDS layout: value (n, t) at ((n*(K/4) + (t%K)/4) * lpr + t/K) * 4 + t%4, so that for a fixed quarter of a
-// lane's K steps consecutive lanes read consecutive 16-byte words.  FULL: the whole tile lies inside the
-// sequence and rows are 16-byte aligned, so every unit is one vector load.
-template <typename T, int K, bool FULL>
-__device__ __forceinline__ void stage_operand(const T* __restrict__ src_tile, float* __restrict__ dst, int ns,
-                                              int chunk, int lpr, int64_t remaining, int64_t L)
+// Workspace layout of one operand for sequence b, chunk c (lpr = c / K lanes per row): value (n, t) of tile
+// tau = t / c lives at   b*N*Lpad + tau*N*c + ((n*(K/4) + q) * lpr + j) * 4 + e,   t - tau*c = j*K + q*4 + e.
+// For a fixed quarter q of a lane's K steps consecutive lanes j read consecutive 16-byte words, the values
+// of one state are c consecutive floats and a group of states of one tile is one contiguous block, so a
+// workgroup stages it with straight 16-byte copies.  Steps at or beyond the sequence length are written as 0.
+template <typename T, int K>
+__global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, const T* __restrict__ Cm, float* __restrict__ ws_B,
+                                                     float* __restrict__ ws_C, const int32_t* __restrict__ seqlens,
+                                                     const int32_t* __restrict__ chunks_dev, int chunk_host, int N, int64_t L,
+                                                     int64_t Lpad)
 {
-    constexpr int V = Io<T>::kVec;
-    const int per_row_log2 = __ffs(chunk / V) - 1;           // chunk and V are powers of two
-    const int units = ns << per_row_log2;
-    for (int k = threadIdx.x; k < units; k += kBlock) {
-        const int nl = k >> per_row_log2;
-        const int tv = (k - (nl << per_row_log2)) * V;         // first step of this unit inside the tile
-        const T* p = src_tile + (int64_t)nl * L + tv;
-        float v[V];
-        if (FULL) {
-            Io<T>::unpack(*reinterpret_cast<const uint4v*>(p), v);
-        } else {
-            const int64_t left = remaining - tv;               // valid steps from this unit on
-#pragma unroll
-            for (int e = 0; e < V; ++e) v[e] = (e < left) ? Io<T>::ld(p + e) : 0.f;
-        }
-        const int j = tv / K;
-        const int q = (tv % K) / 4;
-#pragma unroll
-        for (int g = 0; g < V / 4; ++g) {
-            float4v w;
-            w.x = v[4 * g]; w.y = v[4 * g + 1]; w.z = v[4 * g + 2]; w.w = v[4 * g + 3];
-            *reinterpret_cast<float4v*>(dst + ((size_t)((nl * (K / 4) + q + g) * lpr + j) * 4)) = w;
+    const int b = blockIdx.y;
+    int chunk = chunk_host;
+    if (chunks_dev) {
+        const int c = chunks_dev[b];
+        if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
+    }
+    int64_t len = L;
+    if (seqlens) {
+        const int64_t sl = seqlens[b];
+        len = sl < 0 ? 0 : (sl > L ? L : sl);
+    }
+    const int lpr = chunk / K;
+    const int slots_log2 = __ffs(chunk / 4) - 1;                 // 16-byte slots per (tile, state)
+    const int lpr_log2 = __ffs(lpr) - 1;
+    const int64_t ntiles = (len + chunk - 1) / chunk;            // tiles the scan will actually visit
+    const int64_t total = (ntiles * N) << slots_log2;
+    const T* Bs = Bm + (int64_t)b * N * L;
+    const T* Cs = Cm + (int64_t)b * N * L;
+    float4v* oB = reinterpret_cast<float4v*>(ws_B + (int64_t)b * N * Lpad);
+    float4v* oC = reinterpret_cast<float4v*>(ws_C + (int64_t)b * N * Lpad);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int slot = (int)(i & ((1 << slots_log2) - 1));
+        const int64_t tn = i >> slots_log2;                      // tau * N + n
+        const int64_t tau = tn / N;
+        const int n = (int)(tn - tau * N);
+        const int j = slot & (lpr - 1);
+        const int q = slot >> lpr_log2;
+        const int64_t t = tau * chunk + (int64_t)j * K + q * 4;
+        const T* pb = Bs + (int64_t)n * L + t;
+        const T* pc = Cs + (int64_t)n * L + t;
+        float4v vb, vc;
+        vb.x = (t + 0 < len) ? Io<T>::ld(pb + 0) : 0.f; vb.y = (t + 1 < len) ? Io<T>::ld(pb + 1) : 0.f;
+        vb.z = (t + 2 < len) ? Io<T>::ld(pb + 2) : 0.f; vb.w = (t + 3 < len) ? Io<T>::ld(pb + 3) : 0.f;
+        vc.x = (t + 0 < len) ? Io<T>::ld(pc + 0) : 0.f; vc.y = (t + 1 < len) ? Io<T>::ld(pc + 1) : 0.f;
+        vc.z = (t + 2 < len) ? Io<T>::ld(pc + 2) : 0.f; vc.w = (t + 3 < len) ? Io<T>::ld(pc + 3) : 0.f;
+        oB[i] = vb;
+        oC[i] = vc;
+    }
+}
+
+// Start the copy of `nfloat` consecutive floats (a multiple of 4) of each operand from the workspace into an
+// LDS staging buffer.  Every wave copies 64 sixteen-byte words per instruction; the words go from global
+// memory to LDS without passing through registers and are complete when the wave's vmcnt reaches zero.
+__device__ __forceinline__ void stage_async(const float* __restrict__ srcB, const float* __restrict__ srcC, float* dstB,
+                                            float* dstC, int nfloat, int wave, int lane)
+{
+    const int slots = nfloat >> 2;
+    for (int s0 = wave * 64; s0 < slots; s0 += kBlock) {
+        if (s0 + lane < slots) {
+            __builtin_amdgcn_global_load_lds(srcB + (size_t)(s0 + lane) * 4, dstB + (size_t)s0 * 4, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(srcC + (size_t)(s0 + lane) * 4, dstC + (size_t)s0 * 4, 16, 0, 0);
         }
     }
 }
@@ -296,11 +340,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
         len = s < 0 ? 0 : (s > L ? L : s);
     }
 
-    float* s_carry = s_mem;                                 // [rows][N] state carried tile to tile
+    float* s_stage = s_mem;                                 // [2 buffers][B, C][kStageElems] staged fp32 operands
+    float* s_carry = s_stage + 4 * kStageElems;             // [rows][N] state carried tile to tile
     float* s_A2 = s_carry + (size_t)a.rows_alloc * N;       // [rows][N] A * log2(e)
     float* s_xchg = s_A2 + (size_t)a.rows_alloc * N;        // [waves][2] wave totals when a row spans several waves
-    float* s_B = s_xchg + 2 * kWaves;                       // staged B tile (fp32)
-    float* s_C = s_B + kTileElems;                          // staged C tile (fp32)
     for (int i = tid; i < rows * N; i += kBlock) {
         const int r = i / N, n = i - r * N;
         const int dd = d0 + r;
@@ -314,8 +357,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
     const T* dl_row = static_cast<const T*>(a.delta) + row * L;
     const T* z_row = a.z ? static_cast<const T*>(a.z) + row * L : nullptr;
     T* y_row = static_cast<T*>(a.y) + row * L;
-    const T* B_seq = static_cast<const T*>(a.Bm) + (int64_t)b * N * L;
-    const T* C_seq = static_cast<const T*>(a.Cm) + (int64_t)b * N * L;
+    const float* wsB = a.ws_B + (int64_t)b * N * a.Lpad;
+    const float* wsC = a.ws_C + (int64_t)b * N * a.Lpad;
     const float bias = (a.dbias && active) ? a.dbias[d] : 0.f;
     const float Dd = (a.Dv && active) ? a.Dv[d] : 0.f;
     const bool vec = a.vector_ok != 0;
@@ -325,8 +368,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
     const int jseg = lane & (seg - 1);
     const int wpr = lpr > 64 ? lpr / 64 : 1;                // waves per row
     const int wpos = wave & (wpr - 1);                      // this wave's position inside its row
-    int nsub = kTileElems / chunk;                          // states staged per group
-    if (nsub > N) nsub = N;
+    int nsub = kStageElems / chunk;                         // states staged per group
+    nsub = nsub < 1 ? 1 : (nsub > N ? N : nsub);
+    int buf = 0;                                            // staging buffer holding the group about to be used
+    if (len > 0) {                                          // first group of the first tile
+        const int ns0 = N < nsub ? N : nsub;
+        stage_async(wsB, wsC, s_stage, s_stage + kStageElems, ns0 * chunk, wave, lane);
+    }
 
     for (int64_t tile = 0; tile < L; tile += chunk) {
         const int64_t t0 = tile + (int64_t)j * K;
@@ -363,17 +411,23 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
         if (tile < len) {                                   // uniform over the workgroup
             for (int n0 = 0; n0 < N; n0 += nsub) {
                 const int ns = (N - n0 < nsub) ? N - n0 : nsub;
-                const T* B_tile = B_seq + (int64_t)n0 * L + tile;
-                const T* C_tile = C_seq + (int64_t)n0 * L + tile;
-                __syncthreads();                            // previous group's readers are done (and s_carry/s_A2 are set)
-                if (full) {
-                    stage_operand<T, K, true>(B_tile, s_B, ns, chunk, lpr, 0, L);
-                    stage_operand<T, K, true>(C_tile, s_C, ns, chunk, lpr, 0, L);
-                } else {
-                    stage_operand<T, K, false>(B_tile, s_B, ns, chunk, lpr, len - tile, L);
-                    stage_operand<T, K, false>(C_tile, s_C, ns, chunk, lpr, len - tile, L);
-                }
+                float* s_B = s_stage + buf * 2 * kStageElems;
+                float* s_C = s_B + kStageElems;
+                // this group's copy (started one group earlier) has landed; every wave is past the previous group
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
+                {   // start the copy of the next group: same tile, or the first group of the next tile
+                    int nn0 = n0 + nsub;
+                    int64_t ntile = tile;
+                    if (nn0 >= N) { nn0 = 0; ntile = tile + chunk; }
+                    if (ntile < len) {
+                        const int nns = (N - nn0 < nsub) ? N - nn0 : nsub;
+                        const int64_t off = (ntile / chunk * N + nn0) * chunk;
+                        float* d_B = s_stage + (buf ^ 1) * 2 * kStageElems;
+                        stage_async(wsB + off, wsC + off, d_B, d_B + kStageElems, nns * chunk, wave, lane);
+                    }
+                }
+                buf ^= 1;
                 for (int nl = 0; nl < ns; ++nl) {
                     const int n = n0 + nl;
                     const float A2 = s_A2[rl * N + n];
@@ -468,13 +522,21 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
     }
 }
 
+int64_t padded_len(int64_t L) { return (L + kPad + 3) / 4 * 4; }
+
 }  // namespace
+
+extern "C" size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L)
+{
+    if (B < 1 || N < 1 || N > COREY_MAX_STATE || L < 1) return 0;
+    return (size_t)2 * B * N * padded_len(L) * sizeof(float);
+}
 
 extern "C" int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
                                   const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
                                   const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
                                   void* y, float* last_state, corey_dtype dt, int64_t B, int64_t D, int64_t N, int64_t L,
-                                  void* hip_stream)
+                                  void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     using corey::fail;
     if (!u || !delta || !A || !Bm || !Cm || !y || !last_state)
@@ -489,6 +551,11 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     if (chunk < COREY_MIN_CHUNK || chunk > COREY_MAX_CHUNK || !corey::is_pow2(chunk))
         return fail(COREY_EINVAL, "selective_scan_fwd: chunk = %d must be a power of two in [%d, %d]", chunk, COREY_MIN_CHUNK, COREY_MAX_CHUNK);
 
+    const size_t need = selective_scan_fwd_workspace(B, N, L);
+    if (!workspace || workspace_bytes < need)
+        return fail(COREY_EWORKSPACE, "selective_scan_fwd: workspace of %zu bytes required", need);
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "selective_scan_fwd: workspace must be 16-byte aligned");
+
     const size_t esz = dt == COREY_F32 ? 4 : 2;
     bool vector_ok = (L * (int64_t)esz) % 16 == 0;
     for (const void* p : {u, delta, Bm, Cm, z, (const void*)y})
@@ -497,6 +564,9 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     ScanArgs a;
     a.u = u; a.delta = delta; a.A = A; a.Bm = Bm; a.Cm = Cm; a.Dv = Dv; a.z = z; a.dbias = delta_bias; a.h0 = h0;
     a.seqlens = seqlens; a.chunks_dev = chunks_dev; a.y = y; a.last_state = last_state;
+    a.Lpad = padded_len(L);
+    a.ws_B = static_cast<float*>(workspace);
+    a.ws_C = a.ws_B + (size_t)B * N * a.Lpad;
     a.L = L; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
     // LDS budget for the per-row arrays (carried state and A): at most 64 rows and 16 KiB each.  64 rows fill
@@ -506,7 +576,6 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     if (rows_cap > 64) rows_cap = 64;
     a.rows_cap = rows_cap;
 
-    // Time steps per lane: 16 (fewer scan steps per value) unless the chunk is too short for that.
     // Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes, which pays when
     // 16 would leave the chip short of waves (fewer than two per SIMD: 256 CUs x 4 SIMDs x 64 lanes x 2).
     const int64_t chunk_for_plan = chunks_dev ? COREY_MAX_CHUNK : chunk;
@@ -521,11 +590,20 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     if (rows_alloc > rows_cap) rows_alloc = rows_cap;
     a.rows_alloc = rows_alloc;
     const int64_t gx = (D + rows_min - 1) / rows_min;
-    const size_t lds = ((size_t)2 * rows_alloc * N + 2 * kWaves + 2 * kTileElems) * sizeof(float);
+    const size_t lds = ((size_t)4 * kStageElems + (size_t)2 * rows_alloc * N + 2 * kWaves) * sizeof(float);
     const dim3 grid((unsigned)gx, (unsigned)B);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const dim3 block(kBlock);
-#define COREY_LAUNCH(T, K, SP) k_selective_scan<T, K, SP><<<grid, block, lds, stream>>>(a)
+    // relayout of B and C: one 16-byte word per lane, enough workgroups to cover the operand a few times over
+    int64_t rb = (N * a.Lpad / 4 + 255) / 256;
+    rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
+    const dim3 rgrid((unsigned)rb, (unsigned)B);
+#define COREY_LAUNCH(T, K, SP)                                                                                       \
+    do {                                                                                                             \
+        k_relayout_bc<T, K><<<rgrid, block, 0, stream>>>(static_cast<const T*>(Bm), static_cast<const T*>(Cm), a.ws_B, \
+                                                         a.ws_C, seqlens, chunks_dev, chunk, (int)N, L, a.Lpad);     \
+        k_selective_scan<T, K, SP><<<grid, block, lds, stream>>>(a);                                                 \
+    } while (0)
 #define COREY_LAUNCH_SP(T, K) do { if (a.softplus) COREY_LAUNCH(T, K, true); else COREY_LAUNCH(T, K, false); } while (0)
     if (dt == COREY_F32) {
         if (items == 8) COREY_LAUNCH_SP(float, 8); else COREY_LAUNCH_SP(float, 16);

@@ -15,7 +15,7 @@ from paper_2604_10597_amd import binding
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "corey.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(corey_\w+|selective_scan_fwd)\s*\(", hdr))
+    declared = set(re.findall(r"\b(corey_\w+|selective_scan_fwd\w*)\s*\(", hdr))
     declared -= {"corey_dtype", "corey_status", "corey_policy"}
     assert declared == set(binding.EXPORTS)
     lib = binding.lib()
@@ -89,10 +89,12 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     ss = lambda **kw: lib.selective_scan_fwd(
         kw.get("u", fake), fake, fake, fake, fake, none, none, none, 1, none, none, kw.get("chunk", 256), none,
         kw.get("y", fake), kw.get("last", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("N", 16),
-        kw.get("L", 64), none)
+        kw.get("L", 64), kw.get("ws", fake), kw.get("wsb", 1 << 30), none)
     assert ss(u=none) == 2 and ss(y=none) == 2 and ss(last=none) == 2
     assert ss(dt=3) == 1
     for bad in (0, 8, 100, 4096, -64):
         assert ss(chunk=bad) == 1
     assert ss(N=0) == 3 and ss(N=257) == 3 and ss(B=0) == 3 and ss(L=0) == 3 and ss(B=70000) == 3
-    assert b"chunk" in lib.corey_last_error() or b"B" in lib.corey_last_error()
+    assert ss(ws=none) == 7 and ss(wsb=64) == 7
+    assert lib.selective_scan_fwd_workspace(1, 16, 64) == 2 * 16 * (64 + 2048) * 4
+    assert lib.selective_scan_fwd_workspace(0, 16, 64) == 0 and lib.selective_scan_fwd_workspace(1, 300, 64) == 0
