@@ -32,9 +32,13 @@ namespace {
 using corey::bf16_to_f32;
 using corey::f32_to_bf16;
 
-constexpr int kBlock = 256;       // lanes per workgroup
-constexpr int kWaves = kBlock / 64;
+constexpr int kMaxBlock = 256;    // lanes per workgroup: four waves, one per SIMD of a compute unit (workgroups whose
+                                  // wave count is not a multiple of four were measured to place badly)
+constexpr int kMaxWaves = kMaxBlock / 64;
 constexpr int kStageElems = 2048; // fp32 values of B (and of C) per LDS staging buffer (two buffers)
+// waves per SIMD the register allocation must leave room for: K = 16 needs about 156 VGPRs, K = 8 about 95
+// (a four-wave target for K = 16 was measured: it spills a little and is slower at the routed chunk)
+template <int K> constexpr int min_waves() { return K == 8 ? 5 : 3; }
 constexpr int kPad = COREY_MAX_CHUNK;  // the relaid-out time axis is padded to whole tiles
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -301,7 +305,7 @@ __device__ __forceinline__ void stage_async(const float* __restrict__ srcB, cons
                                             float* dstC, int nfloat, int wave, int lane)
 {
     const int slots = nfloat >> 2;
-    for (int s0 = wave * 64; s0 < slots; s0 += kBlock) {
+    for (int s0 = wave * 64; s0 < slots; s0 += (int)blockDim.x) {
         if (s0 + lane < slots) {
             __builtin_amdgcn_global_load_lds(srcB + (size_t)(s0 + lane) * 4, dstB + (size_t)s0 * 4, 16, 0, 0);
             __builtin_amdgcn_global_load_lds(srcC + (size_t)(s0 + lane) * 4, dstC + (size_t)s0 * 4, 16, 0, 0);
@@ -309,9 +313,8 @@ __device__ __forceinline__ void stage_async(const float* __restrict__ srcB, cons
     }
 }
 
-// At least three waves per SIMD: the register allocator must stay within 168 VGPRs (K = 16 sits at that edge).
 template <typename T, int K, bool SOFTPLUS>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) void k_selective_scan(const ScanArgs a)
+__global__ __launch_bounds__(kMaxBlock) __attribute__((amdgpu_waves_per_eu(min_waves<K>()))) void k_selective_scan(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
     const int b = blockIdx.y;
@@ -321,7 +324,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
         if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
     }
     const int lpr = chunk / K;                              // lanes per row
-    int rows = lpr >= kBlock ? 1 : kBlock / lpr;            // rows per workgroup
+    const int nthreads = blockDim.x;                        // whole waves; a multiple of lpr when lpr > 64
+    int rows = lpr >= nthreads ? 1 : nthreads / lpr;        // rows per workgroup
     if (rows > a.rows_cap) rows = a.rows_cap;
     const int d0 = blockIdx.x * rows;
     if (d0 >= a.D) return;                                  // whole workgroup leaves together
@@ -343,8 +347,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
     float* s_stage = s_mem;                                 // [2 buffers][B, C][kStageElems] staged fp32 operands
     float* s_carry = s_stage + 4 * kStageElems;             // [rows][N] state carried tile to tile
     float* s_A2 = s_carry + (size_t)a.rows_alloc * N;       // [rows][N] A * log2(e)
-    float* s_xchg = s_A2 + (size_t)a.rows_alloc * N;        // [waves][2] wave totals when a row spans several waves
-    for (int i = tid; i < rows * N; i += kBlock) {
+    float* s_xchg = s_A2 + (size_t)a.rows_alloc * N;        // [kMaxWaves][2] wave totals when a row spans several waves
+    for (int i = tid; i < rows * N; i += nthreads) {
         const int r = i / N, n = i - r * N;
         const int dd = d0 + r;
         const bool ok = dd < a.D;
@@ -515,7 +519,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3))) voi
     }
     __syncthreads();                                         // last writes of the carried state are visible
 
-    for (int i = tid; i < rows * N; i += kBlock) {
+    for (int i = tid; i < rows * N; i += nthreads) {
         const int r = i / N, n = i - r * N;
         const int dd = d0 + r;
         if (dd < a.D) a.last_state[((int64_t)b * a.D + dd) * N + n] = s_carry[i];
@@ -576,31 +580,33 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     if (rows_cap > 64) rows_cap = 64;
     a.rows_cap = rows_cap;
 
-    // Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes, which pays when
-    // 16 would leave the chip short of waves (fewer than two per SIMD: 256 CUs x 4 SIMDs x 64 lanes x 2).
+    // Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes and needs fewer registers,
+    // which pays only when 16 would leave the chip short of waves (fewer than two per SIMD: 256 CUs x 4 SIMDs x
+    // 64 lanes x 2).  Measured on the 2.8B-shaped layer: 8 wins for chunks up to 256, 16 from 512 on.
     const int64_t chunk_for_plan = chunks_dev ? COREY_MAX_CHUNK : chunk;
     const int items = (B * D * (chunk_for_plan / 16) < 131072) ? 8 : 16;
+    const int nthreads = kMaxBlock;
     // Rows per workgroup follow from the chunk.  With per-sequence device chunks the grid is sized for the
     // fewest rows any legal chunk gives (surplus workgroups leave at once) and LDS for the most.
     const int lpr_grid = (chunks_dev ? COREY_MAX_CHUNK : chunk) / items;
     const int lpr_lds = (chunks_dev ? COREY_MIN_CHUNK : chunk) / items;
-    int rows_min = lpr_grid >= kBlock ? 1 : kBlock / lpr_grid;
+    int rows_min = lpr_grid >= nthreads ? 1 : nthreads / lpr_grid;
     if (rows_min > rows_cap) rows_min = rows_cap;
-    int rows_alloc = lpr_lds >= kBlock ? 1 : kBlock / lpr_lds;
+    int rows_alloc = lpr_lds >= nthreads ? 1 : nthreads / lpr_lds;
     if (rows_alloc > rows_cap) rows_alloc = rows_cap;
     a.rows_alloc = rows_alloc;
     const int64_t gx = (D + rows_min - 1) / rows_min;
-    const size_t lds = ((size_t)4 * kStageElems + (size_t)2 * rows_alloc * N + 2 * kWaves) * sizeof(float);
+    const size_t lds = ((size_t)4 * kStageElems + (size_t)2 * rows_alloc * N + 2 * kMaxWaves) * sizeof(float);
     const dim3 grid((unsigned)gx, (unsigned)B);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const dim3 block(kBlock);
+    const dim3 block((unsigned)nthreads);
     // relayout of B and C: one 16-byte word per lane, enough workgroups to cover the operand a few times over
     int64_t rb = (N * a.Lpad / 4 + 255) / 256;
     rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
     const dim3 rgrid((unsigned)rb, (unsigned)B);
 #define COREY_LAUNCH(T, K, SP)                                                                                       \
     do {                                                                                                             \
-        k_relayout_bc<T, K><<<rgrid, block, 0, stream>>>(static_cast<const T*>(Bm), static_cast<const T*>(Cm), a.ws_B, \
+        k_relayout_bc<T, K><<<rgrid, dim3(256), 0, stream>>>(static_cast<const T*>(Bm), static_cast<const T*>(Cm), a.ws_B, \
                                                          a.ws_C, seqlens, chunks_dev, chunk, (int)N, L, a.Lpad);     \
         k_selective_scan<T, K, SP><<<grid, block, lds, stream>>>(a);                                                 \
     } while (0)
