@@ -27,8 +27,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
-# HBM bytes per scan launch from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` (see profiles/); None until measured
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per scan launch measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`, scaled by what the same counters
+# read for a 256 MiB device copy (profiles/hot_path_c4_mamba2p8b_counters.txt); not re-measured by this script
+MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 713_100_000}
 
 
 def main() -> int:
@@ -40,6 +41,9 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 256 MiB device-to-device copy a few times: a dispatch of known traffic against which "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
@@ -101,6 +105,14 @@ def main() -> int:
         torch.cuda.current_stream().synchronize()              # the host needs r to pick the launch shape
         Ls = w.seqlens if w.seqlens is not None else [cfg.L] * r_pinned.numel()
         return max(corey.corey_select_chunk(float(r_pinned[i]), int(Ls[i]), pol) for i in range(r_pinned.numel()))
+
+    if args.calibrate_copy:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: K whole steps
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
