@@ -68,7 +68,7 @@ def main() -> int:
             return None
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()          # float32 and float16 upload as they are
 
     d = {k: dev(v) for k, v in w.dev.items()}
     seqlens = None if w.seqlens is None else torch.from_numpy(w.seqlens).cuda()
@@ -174,6 +174,39 @@ def main() -> int:
                                  "tokens_per_s": round(tokens / ms * 1e3, 1),
                                  "hbm_frac": round(scan_bytes / ms * 1e-6 / HBM_PEAK_GBPS, 4)}
 
+    # ---- the paper's own kernel-benchmark shape (batch 1, d 1024, L 4096, d_state 16, FP16), for context only
+    paper_shape = None
+    if not args.no_sweep:
+        pc = wl.CONFIGS["paper_w1_fp16"]
+        pw = wl.make(pc)
+        pd = {k: dev(v) for k, v in pw.dev.items()}
+        p_ws = torch.empty(corey.selective_scan_fwd_workspace(pc.B, pc.N, pc.L), dtype=torch.uint8, device="cuda")
+        p_y, p_last = torch.empty_like(pd["u"]), torch.empty((pc.B, pc.D, pc.N), dtype=torch.float32, device="cuda")
+        p_ent = corey.corey_entropy_hist(pd["u"], pc.K)
+        p_chunk = corey.corey_select_chunk(p_ent["r"].item(), pc.L, pol)
+
+        def p_scan(c):
+            corey.selective_scan_fwd(pd["u"], pd["delta"], pd["A"], pd["B"], pd["C"], Dv=pd["D"], z=pd["z"],
+                                     delta_bias=pd["delta_bias"], chunk=c, y=p_y, last_state=p_last, workspace=p_ws)
+
+        def p_time(c):
+            for _ in range(5):
+                p_scan(c)
+            a0, b0 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a0.record()
+            for _ in range(30):
+                p_scan(c)
+            b0.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(b0) / 30
+
+        paper_shape = {"workload": "B1 D1024 N16 L4096 fp16 (the paper's kernel-level benchmark shape), 5 warm-up + 30 timed",
+                       "r": round(p_ent["r"].item(), 4), "routed_chunk": p_chunk,
+                       "scan_ms": {str(c): round(p_time(c), 4) for c in (64, 256, 512, 2048)},
+                       "scan_bytes": wl.scan_bytes(pc)}
+        del pd, pw, p_ws, p_y
+
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not a target)
     cpu = None
     if not args.no_cpu:
@@ -224,6 +257,7 @@ def main() -> int:
                      "hist_kernels_ms": round(hist_ms, 4), "scan_alone_ms": round(scan_alone_ms, 4),
                      "hist_pct_of_scan": round(hist_ms / scan_alone_ms * 100, 2)},
         "per_chunk": per_chunk,
+        "paper_shape": paper_shape,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -37,7 +37,8 @@ extern "C" {
 
 typedef enum {
     COREY_F32 = 0,   /* IEEE binary32 storage                                 */
-    COREY_BF16 = 1   /* bfloat16 storage; all arithmetic and the state are fp32 */
+    COREY_BF16 = 1,  /* bfloat16 storage; all arithmetic and the state are fp32 */
+    COREY_F16 = 2    /* IEEE binary16 storage (the paper's kernel-level benchmarks run in FP16); arithmetic and state fp32 */
 } corey_dtype;
 
 typedef enum {

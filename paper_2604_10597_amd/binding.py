@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcorey.so")
 
-COREY_F32, COREY_BF16 = 0, 1
+COREY_F32, COREY_BF16, COREY_F16 = 0, 1, 2
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
@@ -83,6 +83,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return COREY_F32
     if t.dtype == torch.bfloat16:
         return COREY_BF16
+    if t.dtype == torch.float16:
+        return COREY_F16
     raise TypeError(f"unsupported storage type {t.dtype}")
 
 

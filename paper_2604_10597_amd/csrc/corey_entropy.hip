@@ -52,9 +52,26 @@ template <> struct Elem<float> {
     static constexpr int kVec = 4;
     static __device__ __forceinline__ float widen(float v) { return v; }
 };
-template <> struct Elem<uint16_t> {
+template <> struct Elem<uint16_t> {                       // bfloat16 bit patterns
     static constexpr int kVec = 8;
     static __device__ __forceinline__ float widen(uint16_t v) { return bf16_to_f32(v); }
+    static __device__ __forceinline__ void widen2(uint32_t w, float& a, float& b)
+    {
+        a = __uint_as_float(w << 16);
+        b = __uint_as_float(w & 0xffff0000u);
+    }
+};
+template <> struct Elem<_Float16> {                       // IEEE binary16
+    static constexpr int kVec = 8;
+    static __device__ __forceinline__ float widen(_Float16 v) { return (float)v; }
+    static __device__ __forceinline__ void widen2(uint32_t w, float& a, float& b)
+    {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        h2 h;
+        __builtin_memcpy(&h, &w, 4);
+        a = (float)h.x;
+        b = (float)h.y;
+    }
 };
 
 // Geometry of one histogram: `rows` rows of `len` valid values, `row_stride` apart, starting at `base`.
@@ -231,6 +248,20 @@ template <> struct RangeFold<uint16_t> {
     }
     static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return (mag & 0xffffu) > 0x7f80u || (mag >> 16) > 0x7f80u; }
 };
+template <> struct RangeFold<_Float16> {
+    static __device__ __forceinline__ void fold(const word4& q, float& lo, float& hi, uint32_t& mag)
+    {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float a, b;
+            Elem<_Float16>::widen2(w[k], a, b);
+            minmax3(lo, hi, a, b);
+            mag = max(mag, max(__float_as_uint(a) & 0x7fffffffu, __float_as_uint(b) & 0x7fffffffu));
+        }
+    }
+    static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return mag > 0x7f800000u; }
+};
 template <> struct RangeFold<float> {
     static __device__ __forceinline__ void fold(const word4& q, float& lo, float& hi, uint32_t& mag)
     {
@@ -340,8 +371,10 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if constexpr (sizeof(T) == 2) {
-                bin(__uint_as_float(w[k] << 16));
-                bin(__uint_as_float(w[k] & 0xffff0000u));
+                float a, b;
+                Elem<T>::widen2(w[k], a, b);
+                bin(a);
+                bin(b);
             } else {
                 bin(__uint_as_float(w[k]));
             }
@@ -536,7 +569,7 @@ extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int6
 {
     using corey::fail;
     if (!x || !counts_out || !H_out || !r_out) return fail(COREY_ENULL, "corey_entropy_hist: x, counts_out, H_out and r_out are required");
-    if (dt != COREY_F32 && dt != COREY_BF16) return fail(COREY_EINVAL, "corey_entropy_hist: unknown dtype %d", (int)dt);
+    if (dt != COREY_F32 && dt != COREY_BF16 && dt != COREY_F16) return fail(COREY_EINVAL, "corey_entropy_hist: unknown dtype %d", (int)dt);
     if (B < 1 || D < 1 || L < 1) return fail(COREY_ESHAPE, "corey_entropy_hist: B, D, L must be >= 1");
     if (B > 65535) return fail(COREY_ESHAPE, "corey_entropy_hist: B = %lld exceeds 65535", (long long)B);
     if ((double)B * (double)D * (double)L >= 9.0e18) return fail(COREY_ESHAPE, "corey_entropy_hist: B*D*L overflows");
@@ -553,5 +586,7 @@ extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int6
     RangeSlot* slots = static_cast<RangeSlot*>(workspace);
     if (dt == COREY_F32)
         return launch<float>(x, B, D, L, seqlens, K, eps, stride, counts_out, H_out, r_out, range_out, slots, stream);
+    if (dt == COREY_F16)
+        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, counts_out, H_out, r_out, range_out, slots, stream);
     return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, counts_out, H_out, r_out, range_out, slots, stream);
 }

@@ -98,6 +98,39 @@ template <> struct Io<uint16_t> {
     }
 };
 
+template <> struct Io<_Float16> {                         // IEEE binary16 storage
+    static constexpr int kVec = 8;
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ float ld(const _Float16* p) { return (float)*p; }
+    static __device__ __forceinline__ void st(_Float16* p, float v) { *p = (_Float16)v; }
+    static __device__ __forceinline__ void unpack(const uint4v& q, float* out)
+    {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            h2 h;
+            __builtin_memcpy(&h, &w[k], 4);
+            out[2 * k] = (float)h.x;
+            out[2 * k + 1] = (float)h.y;
+        }
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)    // round to nearest even
+    {
+        float2v f;
+        f.x = lo; f.y = hi;
+        const h2 h = __builtin_convertvector(f, h2);
+        uint32_t r;
+        __builtin_memcpy(&r, &h, 4);
+        return r;
+    }
+    static __device__ __forceinline__ uint4v pack(const float* v)
+    {
+        uint4v q;
+        q.x = pack2(v[0], v[1]); q.y = pack2(v[2], v[3]); q.z = pack2(v[4], v[5]); q.w = pack2(v[6], v[7]);
+        return q;
+    }
+};
+
 template <typename T, int K> struct Raw {
     static constexpr int kWords = K / Io<T>::kVec;
     uint4v w[kWords];
@@ -545,7 +578,7 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     using corey::fail;
     if (!u || !delta || !A || !Bm || !Cm || !y || !last_state)
         return fail(COREY_ENULL, "selective_scan_fwd: u, delta, A, Bm, Cm, y and last_state are required");
-    if (dt != COREY_F32 && dt != COREY_BF16) return fail(COREY_EINVAL, "selective_scan_fwd: unknown dtype %d", (int)dt);
+    if (dt != COREY_F32 && dt != COREY_BF16 && dt != COREY_F16) return fail(COREY_EINVAL, "selective_scan_fwd: unknown dtype %d", (int)dt);
     if (B < 1 || D < 1 || L < 1) return fail(COREY_ESHAPE, "selective_scan_fwd: B, D, L must be >= 1");
     if (N < 1 || N > COREY_MAX_STATE) return fail(COREY_ESHAPE, "selective_scan_fwd: N = %lld outside [1, %d]", (long long)N, COREY_MAX_STATE);
     if (B > 65535) return fail(COREY_ESHAPE, "selective_scan_fwd: B = %lld exceeds 65535", (long long)B);
@@ -613,6 +646,8 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
 #define COREY_LAUNCH_SP(T, K) do { if (a.softplus) COREY_LAUNCH(T, K, true); else COREY_LAUNCH(T, K, false); } while (0)
     if (dt == COREY_F32) {
         if (items == 8) COREY_LAUNCH_SP(float, 8); else COREY_LAUNCH_SP(float, 16);
+    } else if (dt == COREY_F16) {
+        if (items == 8) COREY_LAUNCH_SP(_Float16, 8); else COREY_LAUNCH_SP(_Float16, 16);
     } else {
         if (items == 8) COREY_LAUNCH_SP(uint16_t, 8); else COREY_LAUNCH_SP(uint16_t, 16);
     }

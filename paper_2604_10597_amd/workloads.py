@@ -19,6 +19,7 @@ import numpy as np
 
 F32 = "f32"
 BF16 = "bf16"
+F16 = "f16"
 
 
 # ----------------------------------------------------------------------------- storage helpers
@@ -42,6 +43,9 @@ def store(a: np.ndarray, dtype: str):
     a = np.ascontiguousarray(a, dtype=np.float32)
     if dtype == F32:
         return a, a
+    if dtype == F16:
+        h = a.astype(np.float16)                  # IEEE round to nearest even
+        return h, h.astype(np.float32)
     bits = f32_to_bf16_bits(a)
     return bits, bf16_bits_to_f32(bits)
 
@@ -72,6 +76,9 @@ CONFIGS = {
                            seed=1003),
     "c4_mamba2p8b": Config("c4_mamba2p8b", 1, 5120, 16, 16384, BF16, 256, _SWEEP, "outlier_channels",
                            seed=1004),
+    # the shape of the paper's own kernel-level benchmark (batch 1, d 1024, L 4096, d_state 16, FP16 standard-normal
+    # activations, K = 256): reported beside the build's configurations for context
+    "paper_w1_fp16": Config("paper_w1_fp16", 1, 1024, 16, 4096, F16, 256, _SWEEP, seed=1005),
 }
 # The mixed-regime configuration lists three lengths for a batch of two: these are the pairs it is run on.
 C3_LENGTH_PAIRS = ((8192, 512), (8192, 2048), (2048, 512), (8192, 8192))

@@ -23,7 +23,14 @@ def fp32_rtol(L: int) -> float:
 
 
 def y_rtol(cfg) -> float:
-    return fp32_rtol(cfg.L) if cfg.dtype == wl.F32 else RTOL[wl.BF16]
+    """fp32 and fp16 storage: the fp32 computation bound (the fp16 store's half ulp is granted separately);
+    bf16 storage: the stated 3e-3."""
+    return RTOL[wl.BF16] if cfg.dtype == wl.BF16 else fp32_rtol(cfg.L)
+
+
+def store_bits(cfg) -> int:
+    """Significand bits of the storage type of y (0: fp32, no store rounding to grant)."""
+    return {wl.F32: 0, wl.BF16: 8, wl.F16: 11}[cfg.dtype]
 
 
 def to_dev(arr, dtype):
@@ -32,6 +39,8 @@ def to_dev(arr, dtype):
         return None
     if arr.dtype == np.uint16:
         return torch.from_numpy(arr.view(np.int16)).cuda().view(torch.bfloat16)
+    if arr.dtype == np.float16:
+        return torch.from_numpy(arr).cuda()
     return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
 
 
@@ -64,8 +73,10 @@ def oracle_scan(w: wl.Workload, rows=None, chunk=256, use_z=True, use_h0=True, t
     return y, last
 
 
-def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, what: str, stored_bf16: bool = False):
-    """|got - ref| <= rtol * (|ref| + rms of the reference row)  [+ half a bf16 ulp of ref if `stored_bf16`].
+def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, what: str, stored_bf16=False):
+    """|got - ref| <= rtol * (|ref| + rms of the reference row)  [+ half an ulp of the storage type of y].
+
+    `stored_bf16`: False / 0 (fp32 result), True / 8 (bfloat16: 8 significand bits) or 11 (binary16).
 
     The first term is the tolerance on the fp32 computation, relative to the value and to the row's scale (a sum
     over states that cancels is not held to a relative bound on its own tiny value).  When the result is stored
@@ -78,10 +89,12 @@ def assert_close(got: np.ndarray, ref: np.ndarray, rtol: float, what: str, store
     assert np.isfinite(got).all(), f"{what}: non-finite output"
     rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
     bound = rtol * (np.abs(ref) + rms) + 1e-30
-    if stored_bf16:
+    bits = 8 if stored_bf16 is True else int(stored_bf16)
+    if bits:
         with np.errstate(divide="ignore"):
             e = np.floor(np.log2(np.abs(ref) + bound))
-        bound = bound + np.where(ref != 0, 2.0 ** (e - 8), 0.0)
+        e = np.maximum(e, -14.0) if bits == 11 else e           # binary16 spacing stops shrinking below 2^-14
+        bound = bound + np.where(ref != 0, 2.0 ** (e - bits), 0.0)
     err = np.abs(got - ref)
     bad = err > bound
     if bad.any():

@@ -50,7 +50,7 @@ def test_configs_at_oracle_size(name, D, L):
         _check(w.dev["u"], w.val["u"], cfg.dtype, cfg.K)
 
 
-@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16, wl.F16])
 @pytest.mark.parametrize("shape", [(1, 1, 1), (1, 3, 7), (2, 5, 37), (3, 4, 2049), (1, 2, 4104)])
 def test_ragged_shapes_and_unaligned_rows(dtype, shape):
     _say(f"entropy ragged {shape} {dtype}")
@@ -121,7 +121,19 @@ def test_repeat_runs_are_identical_and_outputs_reusable():
     assert np.array_equal(counts_u32(out["counts"]), first[0]) and out["H"].item() == first[1]
 
 
-@pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b"])
+def test_fp16_whole_tensor_fast_path_and_nan():
+    _say("entropy fp16")
+    rng = np.random.default_rng(4)
+    store, val = wl.store(rng.standard_normal((2, 96, 2048)).astype(np.float32) * 3, wl.F16)
+    _check(store, val, wl.F16, 256)
+    _check(store, val, wl.F16, 256, stride=8)
+    bad = store.copy()
+    bad[1, 5, 100] = np.float16(np.nan)
+    out, ref = _check(bad, bad.astype(np.float32), wl.F16, 64)
+    assert ref["status"] == oracle.ENONFINITE
+
+
+@pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b", "paper_w1_fp16"])
 def test_full_size_counts_and_routed_chunk(name):
     cfg = wl.CONFIGS[name]
     _say(f"entropy full size {name}")

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import paper_2604_10597_amd as corey
-from gpu_util import assert_close, fp32_rtol, oracle_scan, upload, y_rtol, y_to_f64
+from gpu_util import assert_close, fp32_rtol, oracle_scan, store_bits, upload, y_rtol, y_to_f64
 from paper_2604_10597_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -39,7 +39,7 @@ def _parity(cfg, chunks, a_kind="mamba", with_h0=False, use_z=True):
     for chunk in chunks:
         _say(f"scan {cfg.name} B{cfg.B} D{cfg.D} N{cfg.N} L{cfg.L} {cfg.dtype} A={a_kind} chunk={chunk} z={use_z} h0={with_h0}")
         y, s = _run(d, chunk, use_z=use_z)
-        worst = max(worst, assert_close(y, y_ref, y_rtol(cfg), f"y chunk {chunk}", cfg.dtype == wl.BF16))
+        worst = max(worst, assert_close(y, y_ref, y_rtol(cfg), f"y chunk {chunk}", store_bits(cfg)))
         assert_close(s, s_ref, fp32_rtol(cfg.L), f"last_state chunk {chunk}")
     return worst
 
@@ -60,6 +60,14 @@ def test_configs_at_oracle_size_every_chunk(name, D, L, seqlens):
     _parity(cfg, ALL_CHUNKS)
 
 
+@pytest.mark.parametrize("name,D,L", [("paper_w1_fp16", 48, 2048), ("c2_mamba370m", 24, 1100)])
+def test_fp16_storage(name, D, L):
+    """IEEE binary16 storage (the paper's kernel-level precision): fp32 computation bound plus the fp16 store."""
+    cfg = wl.scaled(wl.CONFIGS[name], D=D, L=L, dtype=wl.F16)
+    _parity(cfg, (64, 256, 512, 2048))
+    _parity(wl.scaled(cfg, L=333), (64, 512), a_kind="random", with_h0=True)
+
+
 def test_unstructured_A_initial_state_and_no_gate():
     cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=36, L=777)
     _parity(cfg, (64, 512, 2048), a_kind="random", with_h0=True)
@@ -76,7 +84,7 @@ def test_state_sizes(N):
 
 @pytest.mark.parametrize("L", [1, 15, 16, 17, 63, 65, 1023, 2049])
 def test_ragged_lengths(L):
-    for dtype in (wl.F32, wl.BF16):
+    for dtype in (wl.F32, wl.BF16, wl.F16):
         cfg = wl.scaled(wl.CONFIGS["c0_tiny_f32"], D=7, L=L, B=2, dtype=dtype)
         _parity(cfg, (16, 64, 2048), a_kind="random")
 
@@ -207,7 +215,7 @@ def test_closed_form_on_gpu_without_softplus():
     assert_close(last.cpu().numpy()[0, 0], h[-1], fp32_rtol(L), "geometric series state")
 
 
-@pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b"])
+@pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b", "paper_w1_fp16"])
 def test_full_size_sampled_rows(name):
     """The benchmark's launch configuration at full size; the oracle recomputes sampled channels one by one."""
     cfg = wl.CONFIGS[name]
@@ -223,6 +231,6 @@ def test_full_size_sampled_rows(name):
                                            delta_bias=d["delta_bias"], seqlens=d["seqlens"], chunk=c)
         torch.cuda.synchronize()
         ys = y[:, torch.from_numpy(rows).cuda(), :]
-        assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y chunk {c}", True)
+        assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y chunk {c}", store_bits(cfg))
         assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state chunk {c}")
         assert torch.isfinite(y.to(torch.float32)).all()

@@ -17,6 +17,15 @@ def test_bf16_rounding_matches_torch():
     assert np.array_equal(wl.bf16_bits_to_f32(bits), ref.to(torch.float32).numpy())
 
 
+def test_fp16_rounding_matches_torch():
+    rng = np.random.default_rng(1)
+    a = (rng.standard_normal(50000) * 50).astype(np.float32)
+    store, val = wl.store(a, wl.F16)
+    ref = torch.from_numpy(a).to(torch.float16)
+    assert np.array_equal(store.view(np.uint16), ref.view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(val, ref.to(torch.float32).numpy())
+
+
 def test_shapes_and_reproducibility():
     cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=8, L=64)
     a, b = wl.make(cfg), wl.make(cfg)
