@@ -1,0 +1,724 @@
+// Kernels of selective_scan_fwd (Mamba-1 selective-scan forward with a run-time chunk) for gfx950, as templates
+// over the storage type.  Each storage type is instantiated in a translation unit of its own (corey_scan_f32.hip,
+// corey_scan_bf16.hip, corey_scan_f16.hip) so that they compile in parallel; corey_scan.hip holds the host entry.
+//
+// Two kernels per call.
+//
+// k_relayout_bc   converts B and C ([B, N, L]) once to fp32 in the caller's workspace, tile by tile, in exactly
+//                 the order the scan's lanes read them.  B and C are shared by every channel of a sequence, so
+//                 doing this once per call removes all conversion work from the scan (a few MB of traffic against
+//                 the scan's hundreds).
+//
+// k_scan          A workgroup of 256 lanes owns ROWS channels of one sequence and walks the time axis in tiles of
+//                 CHUNK steps.  The tile geometry is a compile-time constant (one instantiation per chunk, chosen at
+//                 launch from the run-time chunk), so every LDS address in the inner loop is an immediate offset.
+//                 Inside a tile a row is spread over LPR = CHUNK / K consecutive lanes, each lane owning K (16 or 8)
+//                 consecutive time steps: loads of u / delta / z and the store of y are 16-byte vectors per lane,
+//                 contiguous along L.  The fp32 B / C values of a few states at a time are copied from the
+//                 workspace straight into LDS (global_load_lds, no registers), double buffered.  For every state
+//                 index n a lane
+//   1. discretises its K steps (a_i = exp2(dl_i A log2e), b_i = dl_i B_i u_i) and folds them, from a zero state,
+//      into the pair (P, h) of the affine map  x -> P x + h  of its sub-block (P is one exp2 of the summed dl);
+//      the first lane of the row also applies its map to the state carried from the previous tile;
+//   2. takes part in an inclusive scan of the pairs across the lanes of the row (the pair operator is associative),
+//      written as single DPP instructions; h then is the true state at the end of the lane's sub-block.  Rows
+//      wider than a wave pass the wave totals through LDS;
+//   3. receives the state entering its sub-block from the lane to its left, replays its K steps from it and
+//      accumulates y_i += C_i h_i.
+// The fp32 state carried from tile to tile lives in LDS; the last lane of a row refreshes it.
+// The work is a recurrence plus elementwise maths: no matrix instructions.
+#ifndef COREY_SCAN_IMPL_H
+#define COREY_SCAN_IMPL_H
+
+#include <hip/hip_runtime.h>
+
+#include "corey_internal.h"
+
+namespace corey_scan {
+
+using corey::bf16_to_f32;
+using corey::f32_to_bf16;
+
+constexpr int kBlock = 256;           // lanes per workgroup: four waves, one per SIMD of a compute unit
+constexpr int kWaves = kBlock / 64;
+constexpr int kStageFloats = 2048;    // fp32 values of B (and of C) per LDS staging buffer (two buffers)
+constexpr int kMaxGroup = 4;          // most states staged (and unrolled) per group
+constexpr int kPad = COREY_MAX_CHUNK; // the relaid-out time axis is padded to whole tiles
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Geometry of one (K, CHUNK) instantiation.
+template <int K, int CHUNK> struct Geo {
+    static_assert(CHUNK >= K && CHUNK / K <= kBlock, "a tile row must fit one workgroup");
+    static constexpr int LPR = CHUNK / K;                       // lanes per row
+    static constexpr int SEG = LPR < 64 ? LPR : 64;             // lanes of a row inside one wave
+    static constexpr int WPR = LPR > 64 ? LPR / 64 : 1;         // waves per row
+    static constexpr int ROWS = kBlock / LPR;                   // rows per workgroup
+    static constexpr int G = kStageFloats / CHUNK < 1 ? 1 : (kStageFloats / CHUNK > kMaxGroup ? kMaxGroup : kStageFloats / CHUNK);
+    static constexpr int STAGE = G * CHUNK;                     // floats per operand per staging buffer
+};
+
+// Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes and needs fewer registers,
+// which pays when 16 would leave the chip short of waves.  The same rule runs on the host (known chunk) and on
+// the device (per-sequence chunk read from memory); `rows` is B * D.
+__host__ __device__ inline int items_per_lane(int64_t rows, int chunk)
+{
+    return (chunk < 16 || rows * (chunk / 16) < 131072) ? 8 : 16;
+}
+
+// ------------------------------------------------------------------------------------------- storage types
+// A lane keeps its K consecutive stored values as raw 16-byte words (Raw) and widens them when needed.
+template <typename T> struct Io;
+template <> struct Io<float> {
+    static constexpr int kVec = 4;     // elements per 16-byte word
+    static __device__ __forceinline__ float ld(const float* p) { return *p; }
+    static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+    static __device__ __forceinline__ void unpack(const uint4v& q, float* out)
+    {
+        out[0] = __uint_as_float(q.x); out[1] = __uint_as_float(q.y);
+        out[2] = __uint_as_float(q.z); out[3] = __uint_as_float(q.w);
+    }
+    static __device__ __forceinline__ uint4v pack(const float* v)
+    {
+        uint4v q;
+        q.x = __float_as_uint(v[0]); q.y = __float_as_uint(v[1]); q.z = __float_as_uint(v[2]); q.w = __float_as_uint(v[3]);
+        return q;
+    }
+};
+template <> struct Io<uint16_t> {                         // bfloat16 storage
+    static constexpr int kVec = 8;
+    static __device__ __forceinline__ float ld(const uint16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void st(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+    static __device__ __forceinline__ void unpack(const uint4v& q, float* out)
+    {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            out[2 * k] = __uint_as_float(w[k] << 16);
+            out[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+        }
+    }
+    // round to nearest even in hardware (v_cvt_pk_bf16_f32)
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        float2v f;
+        f.x = lo; f.y = hi;
+        const bf16x2 h = __builtin_convertvector(f, bf16x2);
+        uint32_t r;
+        __builtin_memcpy(&r, &h, 4);
+        return r;
+    }
+    static __device__ __forceinline__ uint4v pack(const float* v)
+    {
+        uint4v q;
+        q.x = pack2(v[0], v[1]); q.y = pack2(v[2], v[3]); q.z = pack2(v[4], v[5]); q.w = pack2(v[6], v[7]);
+        return q;
+    }
+};
+template <> struct Io<_Float16> {                         // IEEE binary16 storage
+    static constexpr int kVec = 8;
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ float ld(const _Float16* p) { return (float)*p; }
+    static __device__ __forceinline__ void st(_Float16* p, float v) { *p = (_Float16)v; }
+    static __device__ __forceinline__ void unpack(const uint4v& q, float* out)
+    {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            h2 h;
+            __builtin_memcpy(&h, &w[k], 4);
+            out[2 * k] = (float)h.x;
+            out[2 * k + 1] = (float)h.y;
+        }
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)    // round to nearest even
+    {
+        float2v f;
+        f.x = lo; f.y = hi;
+        const h2 h = __builtin_convertvector(f, h2);
+        uint32_t r;
+        __builtin_memcpy(&r, &h, 4);
+        return r;
+    }
+    static __device__ __forceinline__ uint4v pack(const float* v)
+    {
+        uint4v q;
+        q.x = pack2(v[0], v[1]); q.y = pack2(v[2], v[3]); q.z = pack2(v[4], v[5]); q.w = pack2(v[6], v[7]);
+        return q;
+    }
+};
+
+template <typename T, int K> struct Raw {
+    static constexpr int kWords = K / Io<T>::kVec;
+    uint4v w[kWords];
+};
+
+// K consecutive stored values starting at p (the first nvalid exist); missing ones read as zero bits.
+template <typename T, int K>
+__device__ __forceinline__ Raw<T, K> load_raw(const T* p, int nvalid, bool vector_ok)
+{
+    constexpr int V = Io<T>::kVec;
+    Raw<T, K> r;
+    if (vector_ok && nvalid == K) {
+        const uint4v* pv = reinterpret_cast<const uint4v*>(p);
+#pragma unroll
+        for (int v = 0; v < Raw<T, K>::kWords; ++v) r.w[v] = pv[v];
+    } else {
+        T tmp[K];
+#pragma unroll
+        for (int i = 0; i < K; ++i) tmp[i] = (i < nvalid) ? p[i] : T(0);
+#pragma unroll
+        for (int v = 0; v < Raw<T, K>::kWords; ++v) __builtin_memcpy(&r.w[v], &tmp[v * V], 16);
+    }
+    return r;
+}
+
+template <typename T, int K>
+__device__ __forceinline__ void widen(const Raw<T, K>& r, float (&out)[K])
+{
+#pragma unroll
+    for (int v = 0; v < Raw<T, K>::kWords; ++v) Io<T>::unpack(r.w[v], &out[v * Io<T>::kVec]);
+}
+
+template <typename T, int K>
+__device__ __forceinline__ void store_items(T* p, int nstore, bool vector_ok, const float (&v)[K])
+{
+    constexpr int V = Io<T>::kVec;
+    if (vector_ok && nstore == K) {
+        uint4v* pv = reinterpret_cast<uint4v*>(p);
+#pragma unroll
+        for (int k = 0; k < K / V; ++k) pv[k] = Io<T>::pack(&v[k * V]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < K; ++i)
+            if (i < nstore) Io<T>::st(p + i, v[i]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------- elementwise maths
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// log(1 + e^x) = max(x, 0) + log1p(e^{-|x|}).  log1p(e) is taken as log(w), w = fl(1 + e), plus the repair
+// e - (w - 1) of the rounding in w (its 1/w factor lies in [1/2, 1] and the repair is below one ulp of w, so
+// dropping the factor costs < 3e-8 absolute): the small tail e << 1 stays accurate to binary32 relative precision.
+__device__ __forceinline__ float softplus(float x)
+{
+    const float e = fast_exp2(-fabsf(x) * kLog2e);
+    const float w = 1.f + e;
+    const float fix = e - (w - 1.f);
+    return fmaxf(x, 0.f) + fmaf(__builtin_amdgcn_logf(w), kLn2, fix);
+}
+
+// z * sigmoid(z)
+__device__ __forceinline__ float silu(float z)
+{
+    return z * __builtin_amdgcn_rcpf(1.f + fast_exp2(-z * kLog2e));
+}
+
+// ------------------------------------------------------------------------------------------- lane scan (DPP)
+// Inclusive scan, over the SEG consecutive lanes of a row inside one wave, of the per-lane affine maps
+// x -> P x + h (oldest lane first): a Hillis-Steele scan whose steps are single DPP instructions,
+//     h += h[lane - s] * P ;  P *= P[lane - s] ;
+// lanes without a source (DPP bound control off) keep their value, which is composing with the identity.
+// The instructions are written out because the hazard rules matter: a DPP source register needs two wait
+// states after the VALU write that produced it (inside a step pair: the other instruction plus s_nop 0), and
+// five after a VALU write of EXEC (s_nop 4 up front).  With NEED_P false the last step leaves P stale
+// (only h is wanted afterwards).
+#define COREY_DPP_H(ctrl) "v_fmac_f32_dpp %0, %0, %1 " ctrl " bank_mask:0xf\n\t"
+#define COREY_DPP_P(ctrl) "v_mul_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t"
+#define COREY_DPP_STEP(ctrl) COREY_DPP_H(ctrl) COREY_DPP_P(ctrl) "s_nop 0\n\t"
+#define COREY_ROW_STEPS3                                                                   \
+    COREY_DPP_STEP("row_shr:1 row_mask:0xf") COREY_DPP_STEP("row_shr:2 row_mask:0xf")      \
+    COREY_DPP_STEP("row_shr:4 row_mask:0xf")
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+template <int SEG, bool NEED_P>
+__device__ __forceinline__ void scan_inclusive(int jseg, float& P, float& h)
+{
+    if constexpr (SEG == 64) {
+        if constexpr (NEED_P)
+            asm volatile("s_nop 4\n\t" COREY_ROW_STEPS3 COREY_DPP_STEP("row_shr:8 row_mask:0xf")
+                         COREY_DPP_STEP("row_bcast:15 row_mask:0xa") COREY_DPP_STEP("row_bcast:31 row_mask:0xc")
+                         : "+v"(h), "+v"(P));
+        else
+            asm volatile("s_nop 4\n\t" COREY_ROW_STEPS3 COREY_DPP_STEP("row_shr:8 row_mask:0xf")
+                         COREY_DPP_STEP("row_bcast:15 row_mask:0xa") COREY_DPP_H("row_bcast:31 row_mask:0xc") "s_nop 1\n\t"
+                         : "+v"(h), "+v"(P));
+    } else if constexpr (SEG == 32) {
+        asm volatile("s_nop 4\n\t" COREY_ROW_STEPS3 COREY_DPP_STEP("row_shr:8 row_mask:0xf")
+                     COREY_DPP_H("row_bcast:15 row_mask:0xa") "s_nop 1\n\t" : "+v"(h), "+v"(P));
+    } else if constexpr (SEG == 16) {
+        asm volatile("s_nop 4\n\t" COREY_ROW_STEPS3 COREY_DPP_H("row_shr:8 row_mask:0xf") "s_nop 1\n\t" : "+v"(h), "+v"(P));
+    } else if constexpr (SEG > 1) {
+        // segments shorter than a DPP row: the shifted-in partner must come from the same segment
+        {
+            const float ho = dpp_move<0x111>(h), Po = dpp_move<0x111>(P);        // row_shr:1
+            const bool take = jseg >= 1;
+            h = take ? fmaf(P, ho, h) : h;
+            P = take ? P * Po : P;
+        }
+        if constexpr (SEG > 2) {
+            const float ho = dpp_move<0x112>(h), Po = dpp_move<0x112>(P);        // row_shr:2
+            const bool take = jseg >= 2;
+            h = take ? fmaf(P, ho, h) : h;
+            P = take ? P * Po : P;
+        }
+        if constexpr (SEG > 4) {
+            const float ho = dpp_move<0x114>(h), Po = dpp_move<0x114>(P);        // row_shr:4
+            const bool take = jseg >= 4;
+            h = take ? fmaf(P, ho, h) : h;
+            P = take ? P * Po : P;
+        }
+    }
+}
+
+// The value of the lane to the left inside the wave (lane 0 keeps `first`).
+__device__ __forceinline__ float from_left_lane(float v, float first)
+{
+    float r = first;
+    asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 wave_shr:1 row_mask:0xf bank_mask:0xf\n\ts_nop 0" : "+v"(r) : "v"(v));
+    return r;
+}
+
+// ------------------------------------------------------------------------------------------- kernel arguments
+struct ScanArgs {
+    const void* u;
+    const void* delta;
+    const float* A;
+    const void* Bm;
+    const void* Cm;
+    const float* Dv;
+    const void* z;
+    const float* dbias;
+    const float* h0;
+    const int32_t* seqlens;
+    const int32_t* chunks_dev;
+    void* y;
+    float* last_state;
+    float* ws_B;            // relaid-out fp32 B, [B][N * Lpad]
+    float* ws_C;
+    int64_t L, Lpad;
+    int64_t rows_total;     // B * D (input of the items-per-lane rule)
+    int32_t D, N;
+    int32_t chunk;          // host chunk (also the fallback for invalid device entries)
+    int32_t rows_cap;       // most rows a workgroup may hold (LDS budget for the carried state)
+    int32_t softplus;
+    int32_t vector_ok;      // rows of the [.., L] tensors are 16-byte aligned
+};
+
+__device__ __forceinline__ int resolve_chunk(const ScanArgs& a, int b)
+{
+    int chunk = a.chunk;
+    if (a.chunks_dev) {
+        const int c = a.chunks_dev[b];
+        if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
+    }
+    return chunk;
+}
+
+// Workspace layout of one operand for sequence b, chunk c (lpr = c / K lanes per row): value (n, t) of tile
+// tau = t / c lives at   b*N*Lpad + tau*N*c + ((n*(K/4) + q) * lpr + j) * 4 + e,   t - tau*c = j*K + q*4 + e.
+// For a fixed quarter q of a lane's K steps consecutive lanes j read consecutive 16-byte words, the values
+// of one state are c consecutive floats and a group of states of one tile is one contiguous block, so a
+// workgroup stages it with straight 16-byte copies.  Steps at or beyond the sequence length are written as 0.
+template <typename T>
+__global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, const T* __restrict__ Cm, float* __restrict__ ws_B,
+                                                     float* __restrict__ ws_C, const int32_t* __restrict__ seqlens,
+                                                     const int32_t* __restrict__ chunks_dev, int chunk_host, int items_host,
+                                                     int64_t rows_total, int N, int64_t L, int64_t Lpad)
+{
+    const int b = blockIdx.y;
+    int chunk = chunk_host;
+    int K = items_host;
+    if (chunks_dev) {
+        const int c = chunks_dev[b];
+        if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
+        K = items_per_lane(rows_total, chunk);
+    }
+    int64_t len = L;
+    if (seqlens) {
+        const int64_t sl = seqlens[b];
+        len = sl < 0 ? 0 : (sl > L ? L : sl);
+    }
+    const int lpr = chunk / K;
+    const int slots_log2 = __ffs(chunk / 4) - 1;                 // 16-byte slots per (tile, state)
+    const int lpr_log2 = __ffs(lpr) - 1;
+    const int64_t ntiles = (len + chunk - 1) / chunk;            // tiles the scan will actually visit
+    const int64_t total = (ntiles * N) << slots_log2;
+    const T* Bs = Bm + (int64_t)b * N * L;
+    const T* Cs = Cm + (int64_t)b * N * L;
+    float4v* oB = reinterpret_cast<float4v*>(ws_B + (int64_t)b * N * Lpad);
+    float4v* oC = reinterpret_cast<float4v*>(ws_C + (int64_t)b * N * Lpad);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int slot = (int)(i & ((1 << slots_log2) - 1));
+        const int64_t tn = i >> slots_log2;                      // tau * N + n
+        const int64_t tau = tn / N;
+        const int n = (int)(tn - tau * N);
+        const int j = slot & (lpr - 1);
+        const int q = slot >> lpr_log2;
+        const int64_t t = tau * chunk + (int64_t)j * K + q * 4;
+        const T* pb = Bs + (int64_t)n * L + t;
+        const T* pc = Cs + (int64_t)n * L + t;
+        float4v vb, vc;
+        vb.x = (t + 0 < len) ? Io<T>::ld(pb + 0) : 0.f; vb.y = (t + 1 < len) ? Io<T>::ld(pb + 1) : 0.f;
+        vb.z = (t + 2 < len) ? Io<T>::ld(pb + 2) : 0.f; vb.w = (t + 3 < len) ? Io<T>::ld(pb + 3) : 0.f;
+        vc.x = (t + 0 < len) ? Io<T>::ld(pc + 0) : 0.f; vc.y = (t + 1 < len) ? Io<T>::ld(pc + 1) : 0.f;
+        vc.z = (t + 2 < len) ? Io<T>::ld(pc + 2) : 0.f; vc.w = (t + 3 < len) ? Io<T>::ld(pc + 3) : 0.f;
+        oB[i] = vb;
+        oC[i] = vc;
+    }
+}
+
+// Start the copy of NFLOAT consecutive floats (a multiple of 256) of each operand from the workspace into an LDS
+// staging buffer.  Every wave copies 64 sixteen-byte words per instruction; the words go from global memory to
+// LDS without passing through registers and are complete when the wave's vmcnt reaches zero.
+template <int NFLOAT>
+__device__ __forceinline__ void stage_async(const float* __restrict__ srcB, const float* __restrict__ srcC, float* dstB,
+                                            float* dstC, int nfloat, int wave, int lane)
+{
+    constexpr int SLOTS = NFLOAT / 4;
+    const int slots = nfloat >> 2;
+#pragma unroll
+    for (int s0 = 0; s0 < SLOTS; s0 += kBlock) {
+        const int s = s0 + wave * 64;
+        if (s + lane < slots) {
+            __builtin_amdgcn_global_load_lds(srcB + (size_t)(s + lane) * 4, dstB + (size_t)s * 4, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(srcC + (size_t)(s + lane) * 4, dstC + (size_t)s * 4, 16, 0, 0);
+        }
+    }
+}
+
+// Floats of dynamic LDS one workgroup of the (K, CHUNK) geometry needs for `rows` rows of N states.
+template <int K, int CHUNK>
+__host__ __device__ constexpr int lds_floats(int rows, int N)
+{
+    return 4 * Geo<K, CHUNK>::STAGE + 2 * rows * N + N + 4 * kWaves;
+}
+
+// ------------------------------------------------------------------------------------------- the scan
+template <typename T, int K, int CHUNK>
+__device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
+{
+    using Gm = Geo<K, CHUNK>;
+    constexpr int LPR = Gm::LPR, SEG = Gm::SEG, WPR = Gm::WPR, G = Gm::G, STAGE = Gm::STAGE, KQ = K / 4;
+
+    const int b = blockIdx.y;
+    const int rows = Gm::ROWS < a.rows_cap ? Gm::ROWS : a.rows_cap;   // rows of this workgroup
+    const int d0 = blockIdx.x * rows;
+    if (d0 >= a.D) return;                                  // whole workgroup leaves together
+
+    const int tid = threadIdx.x;
+    const int row_local = tid / LPR;
+    const int j = tid % LPR;                                // sub-block of this lane inside the tile
+    const int d = d0 + row_local;
+    const bool active = row_local < rows && d < a.D;
+    const int rl = active ? row_local : 0;                  // safe LDS row for idle lanes
+    const int N = a.N;
+    const int64_t L = a.L;
+    int64_t len = L;
+    if (a.seqlens) {
+        const int64_t s = a.seqlens[b];
+        len = s < 0 ? 0 : (s > L ? L : s);
+    }
+
+    float* s_stage = s_mem;                                 // [2 buffers][B, C][STAGE] staged fp32 operands
+    float* s_carry = s_stage + 4 * STAGE;                   // [rows][N] state carried tile to tile
+    float* s_A2 = s_carry + rows * N;                       // [rows][N] A * log2(e)
+    float* s_zero = s_A2 + rows * N;                        // [N] zeros: the "carried state" of lanes that are not first in their row
+    float* s_xchg = s_zero + N;                             // [2][kWaves][2] wave totals when a row spans several waves
+    for (int i = tid; i < rows * N; i += kBlock) {
+        const int r = i / N, n = i - r * N;
+        const int dd = d0 + r;
+        const bool ok = dd < a.D;
+        s_carry[i] = (a.h0 && ok) ? a.h0[((int64_t)b * a.D + dd) * N + n] : 0.f;
+        s_A2[i] = ok ? a.A[(int64_t)dd * N + n] * kLog2e : 0.f;
+    }
+    for (int i = tid; i < N; i += kBlock) s_zero[i] = 0.f;
+
+    const int64_t row = (int64_t)b * a.D + (active ? d : d0);
+    const T* u_row = static_cast<const T*>(a.u) + row * L;
+    const T* dl_row = static_cast<const T*>(a.delta) + row * L;
+    const T* z_row = a.z ? static_cast<const T*>(a.z) + row * L : nullptr;
+    T* y_row = static_cast<T*>(a.y) + row * L;
+    const float* wsB = a.ws_B + (int64_t)b * N * a.Lpad;
+    const float* wsC = a.ws_C + (int64_t)b * N * a.Lpad;
+    const float bias = (a.dbias && active) ? a.dbias[d] : 0.f;
+    const float Dd = (a.Dv && active) ? a.Dv[d] : 0.f;
+    const bool vec = a.vector_ok != 0;
+    const bool sp = a.softplus != 0;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int jseg = lane & (SEG - 1);
+    const int wpos = wave & (WPR - 1);                      // this wave's position inside its row
+    const float* A2_row = s_A2 + rl * N;
+    const float* carry_rd = (active && j == 0) ? s_carry + rl * N : s_zero;
+    const bool carry_wr = active && j == LPR - 1;
+    float* carry_row = s_carry + rl * N;
+
+    int buf = 0;                                            // staging buffer holding the group about to be used
+    if (len > 0) stage_async<STAGE>(wsB, wsC, s_stage, s_stage + STAGE, (N < G ? N : G) * CHUNK, wave, lane);
+
+    const int64_t ntiles = (len + CHUNK - 1) / CHUNK;
+    for (int64_t tau = 0; tau < ntiles; ++tau) {
+        const int64_t tile = tau * CHUNK;
+        const int64_t t0 = tile + (int64_t)j * K;
+        // A full tile lies inside the sequence with aligned rows: no masks anywhere (idle lanes read row d0).
+        const bool full = vec && tile + CHUNK <= len;       // uniform over the workgroup
+        // otherwise: valid steps of this lane (within the sequence) and steps that get a y written (within L)
+        int nvalid = K, nstore = K;
+        if (!full) {
+            nvalid = nstore = 0;
+            if (active) {
+                nvalid = (t0 >= len) ? 0 : (len - t0 < K ? (int)(len - t0) : K);
+                nstore = (t0 >= L) ? 0 : (L - t0 < K ? (int)(L - t0) : K);
+            }
+        }
+        float dl[K], du[K], yv[K];
+        {
+            const Raw<T, K> u_raw = load_raw<T, K>(u_row + t0, nvalid, vec);
+            const Raw<T, K> d_raw = load_raw<T, K>(dl_row + t0, nvalid, vec);
+            widen<T, K>(d_raw, dl);
+            widen<T, K>(u_raw, du);
+        }
+        float S = 0.f;
+        if (sp) {
+#pragma unroll
+            for (int i = 0; i < K; ++i) dl[i] = softplus(dl[i] + bias);
+        } else {
+#pragma unroll
+            for (int i = 0; i < K; ++i) dl[i] = dl[i] + bias;
+        }
+        if (!full) {
+#pragma unroll
+            for (int i = 0; i < K; ++i) dl[i] = (i < nvalid) ? dl[i] : 0.f;   // padded steps: dl = 0 -> a = 1, b = 0 (identity)
+        }
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+            yv[i] = Dd * du[i];                             // the skip term D u opens the sum over states
+            du[i] = dl[i] * du[i];
+            S += dl[i];
+        }
+
+        for (int n0 = 0; n0 < N; n0 += G) {
+            const float* s_B = s_stage + buf * 2 * STAGE;
+            const float* s_C = s_B + STAGE;
+            // this group's copy (started one group earlier) has landed; every wave is past the previous group
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            {   // start the copy of the next group: same tile, or the first group of the next tile
+                int nn0 = n0 + G;
+                int64_t ntau = tau;
+                if (nn0 >= N) { nn0 = 0; ntau = tau + 1; }
+                if (ntau < ntiles) {
+                    const int nns = (N - nn0 < G) ? N - nn0 : G;
+                    const int64_t off = (ntau * N + nn0) * CHUNK;
+                    float* d_B = s_stage + (buf ^ 1) * 2 * STAGE;
+                    stage_async<STAGE>(wsB + off, wsC + off, d_B, d_B + STAGE, nns * CHUNK, wave, lane);
+                }
+            }
+            buf ^= 1;
+            const float4v* bq0 = reinterpret_cast<const float4v*>(s_B) + j;
+            const float4v* cq0 = reinterpret_cast<const float4v*>(s_C) + j;
+#pragma unroll
+            for (int nl = 0; nl < G; ++nl) {
+                const int n = n0 + nl;
+                if (n >= N) break;                          // uniform
+                const float A2 = A2_row[n];
+                const float cin = carry_rd[n];              // carried state for the first lane of the row, 0 elsewhere
+                const float4v* bq = bq0 + nl * KQ * LPR;
+                const float4v* cq = cq0 + nl * KQ * LPR;
+
+                float av[K], bv[K];
+                float h = 0.f;
+#pragma unroll
+                for (int q = 0; q < KQ; ++q) {
+                    const float4v b4 = bq[q * LPR];
+                    const float be[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = 4 * q + e;
+                        av[i] = fast_exp2(dl[i] * A2);
+                        bv[i] = du[i] * be[e];
+                        h = fmaf(av[i], h, bv[i]);
+                    }
+                }
+                float P = fast_exp2(S * A2);
+                h = fmaf(P, cin, h);                        // the row's first lane starts from the carried state
+                scan_inclusive<SEG, (WPR > 1)>(jseg, P, h); // h: state at the end of this lane's sub-block (within the wave)
+                float first = cin;                          // state entering the first lane of this wave's part of the row
+                if constexpr (WPR > 1) {                    // a row spans several waves: add what the waves before it did
+                    float* xc = s_xchg + (n & 1) * (2 * kWaves);
+                    if (lane == 63) { xc[2 * wave] = P; xc[2 * wave + 1] = h; }
+                    __syncthreads();
+                    float hw = 0.f;                         // state at the end of the wave to the left
+                    for (int w = 0; w < wpos; ++w) hw = fmaf(xc[2 * (wave - wpos + w)], hw, xc[2 * (wave - wpos + w) + 1]);
+                    h = fmaf(P, hw, h);
+                    if (wpos > 0) first = hw;
+                }
+                if (carry_wr) carry_row[n] = h;
+                float hh;                                   // true state entering this lane's sub-block
+                if constexpr (LPR == 1) {
+                    hh = cin;
+                } else {
+                    hh = from_left_lane(h, first);
+                    if constexpr (SEG < 64) hh = (jseg == 0) ? cin : hh;
+                }
+#pragma unroll
+                for (int q = 0; q < KQ; ++q) {
+                    const float4v c4 = cq[q * LPR];
+                    const float ce[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = 4 * q + e;
+                        hh = fmaf(av[i], hh, bv[i]);
+                        yv[i] = fmaf(ce[e], hh, yv[i]);
+                    }
+                }
+            }
+        }
+
+        if (full) {
+            if (z_row) {
+                float zz[K];
+                widen<T, K>(load_raw<T, K>(z_row + t0, K, true), zz);
+#pragma unroll
+                for (int i = 0; i < K; ++i) yv[i] *= silu(zz[i]);
+            }
+            if (active) store_items<T, K>(y_row + t0, K, true, yv);
+        } else if (nstore > 0) {
+            if (nvalid > 0 && z_row) {
+                float zz[K];
+                widen<T, K>(load_raw<T, K>(z_row + t0, nvalid, vec), zz);
+#pragma unroll
+                for (int i = 0; i < K; ++i) yv[i] *= silu(zz[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < K; ++i)
+                if (i >= nvalid) yv[i] = 0.f;                // padded positions are written as zero
+            store_items<T, K>(y_row + t0, nstore, vec, yv);
+        }
+    }
+
+    // tiles wholly beyond the sequence: y is written as zero
+    if (active) {
+        float zero[K];
+#pragma unroll
+        for (int i = 0; i < K; ++i) zero[i] = 0.f;
+        for (int64_t tile = ntiles * CHUNK; tile < L; tile += CHUNK) {
+            const int64_t t0 = tile + (int64_t)j * K;
+            const int nstore = (t0 >= L) ? 0 : (L - t0 < K ? (int)(L - t0) : K);
+            if (nstore > 0) store_items<T, K>(y_row + t0, nstore, vec, zero);
+        }
+    }
+    __syncthreads();                                         // last writes of the carried state are visible
+
+    for (int i = tid; i < rows * N; i += kBlock) {
+        const int r = i / N, n = i - r * N;
+        const int dd = d0 + r;
+        if (dd < a.D) a.last_state[((int64_t)b * a.D + dd) * N + n] = s_carry[i];
+    }
+}
+
+// Register budget: K = 16 keeps 16 x (dl, du, y, a, b) per lane and is built for four waves per SIMD (128 VGPRs);
+// K = 8 for five.
+template <int K> constexpr int waves_target() { return K == 8 ? 5 : 4; }
+
+// One geometry, chosen on the host from the run-time chunk.
+template <typename T, int K, int CHUNK>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_target<K>()))) void k_scan(const ScanArgs a)
+{
+    extern __shared__ float s_mem[];
+    scan_rows<T, K, CHUNK>(a, s_mem);
+}
+
+// Per-sequence chunk read from device memory: every geometry in one kernel, selected per workgroup.
+template <typename T>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void k_scan_any(const ScanArgs a)
+{
+    extern __shared__ float s_mem[];
+    const int chunk = resolve_chunk(a, blockIdx.y);
+    const int K = items_per_lane(a.rows_total, chunk);
+#define COREY_CASE(C)                                                                       \
+    case C:                                                                                 \
+        if (K == 8) { if constexpr (C >= 8) scan_rows<T, 8, C>(a, s_mem); }                 \
+        else { if constexpr (C >= 16) scan_rows<T, 16, C>(a, s_mem); }                      \
+        break;
+    switch (chunk) {
+        COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
+        COREY_CASE(2048)
+    default: break;
+    }
+#undef COREY_CASE
+}
+
+// ------------------------------------------------------------------------------------------- launch
+struct LaunchPlan {
+    int items;              // K when the chunk is known on the host
+    int chunk;              // host chunk
+    bool routed;            // per-sequence device chunks
+    int64_t B, D, N;
+    hipStream_t stream;
+};
+
+template <int K, int CHUNK>
+inline void geometry(const LaunchPlan& p, int rows_cap, int64_t& gx, size_t& lds)
+{
+    int rows = Geo<K, CHUNK>::ROWS < rows_cap ? Geo<K, CHUNK>::ROWS : rows_cap;
+    gx = (p.D + rows - 1) / rows;
+    lds = (size_t)lds_floats<K, CHUNK>(rows, (int)p.N) * sizeof(float);
+}
+
+template <typename T, int K, int CHUNK>
+inline void launch_one(const ScanArgs& a, const LaunchPlan& p)
+{
+    int64_t gx;
+    size_t lds;
+    geometry<K, CHUNK>(p, a.rows_cap, gx, lds);
+    k_scan<T, K, CHUNK><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
+}
+
+template <typename T>
+inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
+{
+    // relayout of B and C: one 16-byte word per lane, enough workgroups to cover the operand a few times over
+    int64_t rb = (p.N * a.Lpad / 4 + 255) / 256;
+    rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
+    k_relayout_bc<T><<<dim3((unsigned)rb, (unsigned)p.B), dim3(256), 0, p.stream>>>(
+        static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.seqlens, a.chunks_dev, p.chunk, p.items,
+        a.rows_total, (int)p.N, a.L, a.Lpad);
+    if (p.routed) {
+        // grid for the geometry with the fewest rows per workgroup (surplus workgroups leave at once), LDS for the largest need
+        int64_t gx = 0, g;
+        size_t lds = 0, l;
+#define COREY_GEO(K, C) geometry<K, C>(p, a.rows_cap, g, l); gx = g > gx ? g : gx; lds = l > lds ? l : lds;
+        COREY_GEO(8, 16) COREY_GEO(8, 32) COREY_GEO(8, 64) COREY_GEO(8, 128) COREY_GEO(8, 256) COREY_GEO(8, 512)
+        COREY_GEO(8, 1024) COREY_GEO(8, 2048) COREY_GEO(16, 16) COREY_GEO(16, 32) COREY_GEO(16, 64) COREY_GEO(16, 128)
+        COREY_GEO(16, 256) COREY_GEO(16, 512) COREY_GEO(16, 1024) COREY_GEO(16, 2048)
+#undef COREY_GEO
+        k_scan_any<T><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
+        return;
+    }
+#define COREY_CASE(C)                                                                       \
+    case C:                                                                                 \
+        if (p.items == 8) launch_one<T, 8, C>(a, p); else launch_one<T, 16, C>(a, p);       \
+        break;
+    switch (p.chunk) {
+        COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
+        COREY_CASE(2048)
+    default: break;
+    }
+#undef COREY_CASE
+}
+
+}  // namespace corey_scan
+#endif
