@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcorey.so")
+LIB_PATH = os.environ.get("COREY_LIB") or os.path.join(_HERE, "libcorey.so")   # COREY_LIB: another build of the same library
 
 COREY_F32, COREY_BF16, COREY_F16 = 0, 1, 2
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",

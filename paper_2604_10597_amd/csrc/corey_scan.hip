@@ -1,6 +1,7 @@
 // selective_scan_fwd: host entry.  Validates the arguments, lays out the launch and hands over to the kernels of
 // the storage type (corey_scan_impl.h, instantiated per type in corey_scan_f32/bf16/f16.hip).
 #include <hip/hip_runtime.h>
+#include <cstdlib>
 
 #include "corey_scan_impl.h"
 
@@ -17,7 +18,7 @@ int64_t padded_len(int64_t L) { return (L + corey_scan::kPad + 3) / 4 * 4; }
 extern "C" size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L)
 {
     if (B < 1 || N < 1 || N > COREY_MAX_STATE || L < 1) return 0;
-    return (size_t)2 * B * N * padded_len(L) * sizeof(float);
+    return (size_t)2 * B * corey_scan::a_np(N) * padded_len(L) * sizeof(float);
 }
 
 extern "C" int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
@@ -54,16 +55,20 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.seqlens = seqlens; a.chunks_dev = chunks_dev; a.y = y; a.last_state = last_state;
     a.Lpad = padded_len(L);
     a.ws_B = static_cast<float*>(workspace);
-    a.ws_C = a.ws_B + (size_t)B * N * a.Lpad;
+    a.Np = corey_scan::a_np(N);
+    a.ws_C = a.ws_B + (size_t)B * a.Np * a.Lpad;
     a.L = L; a.rows_total = B * D; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
     // LDS budget for the per-row arrays (carried state and A): 8 KiB each, so that the staging buffers and the
     // rows of a workgroup stay well below what a compute unit gives four workgroups.
-    int rows_cap = (int)(2048 / N);
+    int rows_cap = (int)(2048 / a.Np);
     a.rows_cap = rows_cap < 1 ? 1 : rows_cap;
 
     corey_scan::LaunchPlan p;
     p.items = corey_scan::items_per_lane(B * D, chunk);
+#ifdef COREY_DEV_KNOBS
+    if (const char* e = getenv("COREY_ITEMS")) p.items = atoi(e) == 8 ? 8 : 16;
+#endif
     p.chunk = chunk;
     p.routed = chunks_dev != nullptr;
     p.B = B; p.D = D; p.N = N;

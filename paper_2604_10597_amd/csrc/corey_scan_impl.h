@@ -41,7 +41,19 @@ using corey::f32_to_bf16;
 
 constexpr int kBlock = 256;           // lanes per workgroup: four waves, one per SIMD of a compute unit
 constexpr int kWaves = kBlock / 64;
-constexpr int kStageFloats = 2048;    // fp32 values of B (and of C) per LDS staging buffer (two buffers)
+// Build-time tuning knobs (defaults are the measured best on MI355X).
+#ifndef COREY_STAGE_FLOATS_K16
+#define COREY_STAGE_FLOATS_K16 2048   // fp32 values of B (and of C) per LDS staging buffer (two buffers), 16 steps per lane
+#endif
+#ifndef COREY_STAGE_FLOATS_K8
+#define COREY_STAGE_FLOATS_K8 2048    // the same for 8 steps per lane
+#endif
+#ifndef COREY_WAVES_K16
+#define COREY_WAVES_K16 4             // waves per SIMD the register allocation of the 16-step kernels leaves room for
+#endif
+#ifndef COREY_WAVES_K8
+#define COREY_WAVES_K8 5
+#endif
 constexpr int kMaxGroup = 4;          // most states staged (and unrolled) per group
 constexpr int kPad = COREY_MAX_CHUNK; // the relaid-out time axis is padded to whole tiles
 constexpr float kLog2e = 1.4426950408889634f;
@@ -59,7 +71,9 @@ template <int K, int CHUNK> struct Geo {
     static constexpr int SEG = LPR < 64 ? LPR : 64;             // lanes of a row inside one wave
     static constexpr int WPR = LPR > 64 ? LPR / 64 : 1;         // waves per row
     static constexpr int ROWS = kBlock / LPR;                   // rows per workgroup
+    static constexpr int kStageFloats = K == 8 ? COREY_STAGE_FLOATS_K8 : COREY_STAGE_FLOATS_K16;
     static constexpr int G = kStageFloats / CHUNK < 1 ? 1 : (kStageFloats / CHUNK > kMaxGroup ? kMaxGroup : kStageFloats / CHUNK);
+    static_assert(kMaxGroup % G == 0, "the padded state count must be whole groups");
     static constexpr int STAGE = G * CHUNK;                     // floats per operand per staging buffer
 };
 
@@ -310,6 +324,7 @@ struct ScanArgs {
     int64_t L, Lpad;
     int64_t rows_total;     // B * D (input of the items-per-lane rule)
     int32_t D, N;
+    int32_t Np;             // N rounded up to whole staging groups (a multiple of 4); states N..Np-1 are zero padding
     int32_t chunk;          // host chunk (also the fallback for invalid device entries)
     int32_t rows_cap;       // most rows a workgroup may hold (LDS budget for the carried state)
     int32_t softplus;
@@ -330,12 +345,13 @@ __device__ __forceinline__ int resolve_chunk(const ScanArgs& a, int b)
 // tau = t / c lives at   b*N*Lpad + tau*N*c + ((n*(K/4) + q) * lpr + j) * 4 + e,   t - tau*c = j*K + q*4 + e.
 // For a fixed quarter q of a lane's K steps consecutive lanes j read consecutive 16-byte words, the values
 // of one state are c consecutive floats and a group of states of one tile is one contiguous block, so a
-// workgroup stages it with straight 16-byte copies.  Steps at or beyond the sequence length are written as 0.
+// workgroup stages it with straight 16-byte copies.  Steps at or beyond the sequence length are written as 0, and so
+// are the padding states N..Np-1 (N here is the padded count Np): with B = C = 0 they contribute nothing.
 template <typename T>
 __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, const T* __restrict__ Cm, float* __restrict__ ws_B,
                                                      float* __restrict__ ws_C, const int32_t* __restrict__ seqlens,
                                                      const int32_t* __restrict__ chunks_dev, int chunk_host, int items_host,
-                                                     int64_t rows_total, int N, int64_t L, int64_t Lpad)
+                                                     int64_t rows_total, int Nreal, int N, int64_t L, int64_t Lpad)
 {
     const int b = blockIdx.y;
     int chunk = chunk_host;
@@ -355,8 +371,8 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
     const int lpr_log2 = __ffs(lpr) - 1;
     const int64_t ntiles = (len + chunk - 1) / chunk;            // tiles the scan will actually visit
     const int64_t total = (ntiles * N) << slots_log2;
-    const T* Bs = Bm + (int64_t)b * N * L;
-    const T* Cs = Cm + (int64_t)b * N * L;
+    const T* Bs = Bm + (int64_t)b * Nreal * L;
+    const T* Cs = Cm + (int64_t)b * Nreal * L;
     float4v* oB = reinterpret_cast<float4v*>(ws_B + (int64_t)b * N * Lpad);
     float4v* oC = reinterpret_cast<float4v*>(ws_C + (int64_t)b * N * Lpad);
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
@@ -366,7 +382,7 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
         const int n = (int)(tn - tau * N);
         const int j = slot & (lpr - 1);
         const int q = slot >> lpr_log2;
-        const int64_t t = tau * chunk + (int64_t)j * K + q * 4;
+        const int64_t t = n < Nreal ? tau * chunk + (int64_t)j * K + q * 4 : len;     // padding states read nothing
         const T* pb = Bs + (int64_t)n * L + t;
         const T* pc = Cs + (int64_t)n * L + t;
         float4v vb, vc;
@@ -379,19 +395,18 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
     }
 }
 
-// Start the copy of NFLOAT consecutive floats (a multiple of 256) of each operand from the workspace into an LDS
+// Start the copy of NFLOAT consecutive floats (a multiple of 4) of each operand from the workspace into an LDS
 // staging buffer.  Every wave copies 64 sixteen-byte words per instruction; the words go from global memory to
 // LDS without passing through registers and are complete when the wave's vmcnt reaches zero.
 template <int NFLOAT>
 __device__ __forceinline__ void stage_async(const float* __restrict__ srcB, const float* __restrict__ srcC, float* dstB,
-                                            float* dstC, int nfloat, int wave, int lane)
+                                            float* dstC, int wave, int lane)
 {
     constexpr int SLOTS = NFLOAT / 4;
-    const int slots = nfloat >> 2;
 #pragma unroll
     for (int s0 = 0; s0 < SLOTS; s0 += kBlock) {
         const int s = s0 + wave * 64;
-        if (s + lane < slots) {
+        if (SLOTS % kBlock == 0 || s + lane < SLOTS) {
             __builtin_amdgcn_global_load_lds(srcB + (size_t)(s + lane) * 4, dstB + (size_t)s * 4, 16, 0, 0);
             __builtin_amdgcn_global_load_lds(srcC + (size_t)(s + lane) * 4, dstC + (size_t)s * 4, 16, 0, 0);
         }
@@ -402,7 +417,7 @@ __device__ __forceinline__ void stage_async(const float* __restrict__ srcB, cons
 template <int K, int CHUNK>
 __host__ __device__ constexpr int lds_floats(int rows, int N)
 {
-    return 4 * Geo<K, CHUNK>::STAGE + 2 * rows * N + N + 4 * kWaves;
+    return 4 * Geo<K, CHUNK>::STAGE + 2 * rows * N + N + 4 * kWaves + kBlock + N;    // N: padded state count
 }
 
 // ------------------------------------------------------------------------------------------- the scan
@@ -423,7 +438,8 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
     const int d = d0 + row_local;
     const bool active = row_local < rows && d < a.D;
     const int rl = active ? row_local : 0;                  // safe LDS row for idle lanes
-    const int N = a.N;
+    const int N = a.Np;                                     // padded state count: whole staging groups, no tail group
+    const int Nreal = a.N;
     const int64_t L = a.L;
     int64_t len = L;
     if (a.seqlens) {
@@ -436,12 +452,13 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
     float* s_A2 = s_carry + rows * N;                       // [rows][N] A * log2(e)
     float* s_zero = s_A2 + rows * N;                        // [N] zeros: the "carried state" of lanes that are not first in their row
     float* s_xchg = s_zero + N;                             // [2][kWaves][2] wave totals when a row spans several waves
+    float* s_sink = s_xchg + 4 * kWaves;                    // [kBlock + N] where lanes that are not last in their row "store" the state
     for (int i = tid; i < rows * N; i += kBlock) {
         const int r = i / N, n = i - r * N;
         const int dd = d0 + r;
-        const bool ok = dd < a.D;
-        s_carry[i] = (a.h0 && ok) ? a.h0[((int64_t)b * a.D + dd) * N + n] : 0.f;
-        s_A2[i] = ok ? a.A[(int64_t)dd * N + n] * kLog2e : 0.f;
+        const bool ok = dd < a.D && n < Nreal;
+        s_carry[i] = (a.h0 && ok) ? a.h0[((int64_t)b * a.D + dd) * Nreal + n] : 0.f;
+        s_A2[i] = ok ? a.A[(int64_t)dd * Nreal + n] * kLog2e : 0.f;
     }
     for (int i = tid; i < N; i += kBlock) s_zero[i] = 0.f;
 
@@ -462,11 +479,12 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
     const int wpos = wave & (WPR - 1);                      // this wave's position inside its row
     const float* A2_row = s_A2 + rl * N;
     const float* carry_rd = (active && j == 0) ? s_carry + rl * N : s_zero;
-    const bool carry_wr = active && j == LPR - 1;
-    float* carry_row = s_carry + rl * N;
+    // every lane stores its end-of-sub-block state each step (no branch in the inner loop): the row's last lane into
+    // the carried state, all others into a scratch slot of their own
+    float* carry_wr = (active && j == LPR - 1) ? s_carry + rl * N : s_sink + tid;
 
     int buf = 0;                                            // staging buffer holding the group about to be used
-    if (len > 0) stage_async<STAGE>(wsB, wsC, s_stage, s_stage + STAGE, (N < G ? N : G) * CHUNK, wave, lane);
+    if (len > 0) stage_async<STAGE>(wsB, wsC, s_stage, s_stage + STAGE, wave, lane);
 
     const int64_t ntiles = (len + CHUNK - 1) / CHUNK;
     for (int64_t tau = 0; tau < ntiles; ++tau) {
@@ -484,9 +502,11 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
             }
         }
         float dl[K], du[K], yv[K];
+        Raw<T, K> z_raw;                                    // the gate is fetched with the tile and used after the last state
         {
             const Raw<T, K> u_raw = load_raw<T, K>(u_row + t0, nvalid, vec);
             const Raw<T, K> d_raw = load_raw<T, K>(dl_row + t0, nvalid, vec);
+            if (z_row) z_raw = load_raw<T, K>(z_row + t0, nvalid, vec);
             widen<T, K>(d_raw, dl);
             widen<T, K>(u_raw, du);
         }
@@ -520,19 +540,15 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
                 int64_t ntau = tau;
                 if (nn0 >= N) { nn0 = 0; ntau = tau + 1; }
                 if (ntau < ntiles) {
-                    const int nns = (N - nn0 < G) ? N - nn0 : G;
                     const int64_t off = (ntau * N + nn0) * CHUNK;
                     float* d_B = s_stage + (buf ^ 1) * 2 * STAGE;
-                    stage_async<STAGE>(wsB + off, wsC + off, d_B, d_B + STAGE, nns * CHUNK, wave, lane);
+                    stage_async<STAGE>(wsB + off, wsC + off, d_B, d_B + STAGE, wave, lane);
                 }
             }
             buf ^= 1;
             const float4v* bq0 = reinterpret_cast<const float4v*>(s_B) + j;
             const float4v* cq0 = reinterpret_cast<const float4v*>(s_C) + j;
-#pragma unroll
-            for (int nl = 0; nl < G; ++nl) {
-                const int n = n0 + nl;
-                if (n >= N) break;                          // uniform
+            auto one_state = [&](const int nl, const int n) __attribute__((always_inline)) {
                 const float A2 = A2_row[n];
                 const float cin = carry_rd[n];              // carried state for the first lane of the row, 0 elsewhere
                 const float4v* bq = bq0 + nl * KQ * LPR;
@@ -565,7 +581,7 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
                     h = fmaf(P, hw, h);
                     if (wpos > 0) first = hw;
                 }
-                if (carry_wr) carry_row[n] = h;
+                carry_wr[n] = h;
                 float hh;                                   // true state entering this lane's sub-block
                 if constexpr (LPR == 1) {
                     hh = cin;
@@ -584,13 +600,15 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
                         yv[i] = fmaf(ce[e], hh, yv[i]);
                     }
                 }
-            }
+            };
+#pragma unroll
+            for (int nl = 0; nl < G; ++nl) one_state(nl, n0 + nl);       // straight-line code for the whole group
         }
 
         if (full) {
             if (z_row) {
                 float zz[K];
-                widen<T, K>(load_raw<T, K>(z_row + t0, K, true), zz);
+                widen<T, K>(z_raw, zz);
 #pragma unroll
                 for (int i = 0; i < K; ++i) yv[i] *= silu(zz[i]);
             }
@@ -598,7 +616,7 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
         } else if (nstore > 0) {
             if (nvalid > 0 && z_row) {
                 float zz[K];
-                widen<T, K>(load_raw<T, K>(z_row + t0, nvalid, vec), zz);
+                widen<T, K>(z_raw, zz);
 #pragma unroll
                 for (int i = 0; i < K; ++i) yv[i] *= silu(zz[i]);
             }
@@ -625,13 +643,13 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
     for (int i = tid; i < rows * N; i += kBlock) {
         const int r = i / N, n = i - r * N;
         const int dd = d0 + r;
-        if (dd < a.D) a.last_state[((int64_t)b * a.D + dd) * N + n] = s_carry[i];
+        if (dd < a.D && n < Nreal) a.last_state[((int64_t)b * a.D + dd) * Nreal + n] = s_carry[i];
     }
 }
 
 // Register budget: K = 16 keeps 16 x (dl, du, y, a, b) per lane and is built for four waves per SIMD (128 VGPRs);
 // K = 8 for five.
-template <int K> constexpr int waves_target() { return K == 8 ? 5 : 4; }
+template <int K> constexpr int waves_target() { return K == 8 ? COREY_WAVES_K8 : COREY_WAVES_K16; }
 
 // One geometry, chosen on the host from the run-time chunk.
 template <typename T, int K, int CHUNK>
@@ -670,12 +688,14 @@ struct LaunchPlan {
     hipStream_t stream;
 };
 
+inline int a_np(int64_t N) { return (int)((N + kMaxGroup - 1) / kMaxGroup * kMaxGroup); }
+
 template <int K, int CHUNK>
 inline void geometry(const LaunchPlan& p, int rows_cap, int64_t& gx, size_t& lds)
 {
     int rows = Geo<K, CHUNK>::ROWS < rows_cap ? Geo<K, CHUNK>::ROWS : rows_cap;
     gx = (p.D + rows - 1) / rows;
-    lds = (size_t)lds_floats<K, CHUNK>(rows, (int)p.N) * sizeof(float);
+    lds = (size_t)lds_floats<K, CHUNK>(rows, a_np(p.N)) * sizeof(float);
 }
 
 template <typename T, int K, int CHUNK>
@@ -691,11 +711,11 @@ template <typename T>
 inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
 {
     // relayout of B and C: one 16-byte word per lane, enough workgroups to cover the operand a few times over
-    int64_t rb = (p.N * a.Lpad / 4 + 255) / 256;
+    int64_t rb = (a.Np * a.Lpad / 4 + 255) / 256;
     rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
     k_relayout_bc<T><<<dim3((unsigned)rb, (unsigned)p.B), dim3(256), 0, p.stream>>>(
         static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.seqlens, a.chunks_dev, p.chunk, p.items,
-        a.rows_total, (int)p.N, a.L, a.Lpad);
+        a.rows_total, (int)p.N, a.Np, a.L, a.Lpad);
     if (p.routed) {
         // grid for the geometry with the fewest rows per workgroup (surplus workgroups leave at once), LDS for the largest need
         int64_t gx = 0, g;
