@@ -303,6 +303,16 @@ __device__ __forceinline__ bool usable_range(const RangeSlot& s, float* lo, floa
 
 constexpr int kMaxLdsBins = 8192;   // uint32 counters in LDS (32 KiB)
 
+// Private copies of the K counters a workgroup keeps in LDS: as many as fit, up to one per pair of lanes of a wave,
+// so that lanes of a wave that hit the same bin mostly land on different addresses (same-address LDS atomics
+// serialise).  Copies are K + 1 words apart: with a stride that is a multiple of the bank count (K = 256) the same
+// bin of every copy would sit in one bank and the atomics would serialise all the same.
+__device__ __forceinline__ int lds_copies(int K)
+{
+    const int c = kMaxLdsBins / (K + 1);
+    return c > 32 ? 32 : (c < 1 ? 1 : c);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
                                                             const int32_t* __restrict__ seqlens, int64_t stride,
@@ -316,11 +326,11 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict_
     const Geometry g = geometry(h, B, D, L, seqlens);
     // as many private copies as fit (up to one per pair of lanes of a wave): lanes of a wave that hit the same
     // bin then mostly land on different addresses, which is what serialises LDS atomics
-    int copies = kMaxLdsBins / K;
-    copies = copies > 32 ? 32 : (copies < 1 ? 1 : copies);
-    for (int i = threadIdx.x; i < K * copies; i += kThreads) s_bins[i] = 0u;
+    const int cs = K + 1;                                     // copy stride: odd offset between copies, see lds_copies
+    const int copies = lds_copies(K);
+    for (int i = threadIdx.x; i < cs * copies; i += kThreads) s_bins[i] = 0u;
     __syncthreads();
-    uint32_t* mine = s_bins + (threadIdx.x % copies) * K;
+    uint32_t* mine = s_bins + (threadIdx.x % copies) * cs;
 
     if (hi == lo) {
         uint32_t n = 0;
@@ -340,7 +350,7 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict_
     uint32_t* out = parts + ((int64_t)h * kParts + blockIdx.x % kParts) * K;
     for (int k = threadIdx.x; k < K; k += kThreads) {
         uint32_t c = 0;
-        for (int w = 0; w < copies; ++w) c += s_bins[w * K + k];
+        for (int w = 0; w < copies; ++w) c += s_bins[w * cs + k];
         if (c) atomicAdd(&out[k], c);
     }
 }
@@ -352,11 +362,11 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
     __shared__ uint32_t s_bins[kMaxLdsBins];
     float lo, hi;
     if (!usable_range(slots[0], &lo, &hi)) return;            // counts stay zero, H and r become NaN
-    int copies = kMaxLdsBins / K;
-    copies = copies > 32 ? 32 : (copies < 1 ? 1 : copies);
-    for (int i = threadIdx.x; i < K * copies; i += kThreads) s_bins[i] = 0u;
+    const int cs = K + 1;                                     // copy stride: odd offset between copies, see lds_copies
+    const int copies = lds_copies(K);
+    for (int i = threadIdx.x; i < cs * copies; i += kThreads) s_bins[i] = 0u;
     __syncthreads();
-    uint32_t* mine = s_bins + (threadIdx.x % copies) * K;
+    uint32_t* mine = s_bins + (threadIdx.x % copies) * cs;
     const bool flat = hi == lo;                               // degenerate range: everything in bin 0
     const float scale = flat ? 0.f : (float)((double)K / ((double)hi - (double)lo));
     const int top = K - 1;
@@ -393,7 +403,7 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += kThreads) {
         uint32_t c = 0;
-        for (int w = 0; w < copies; ++w) c += s_bins[w * K + k];
+        for (int w = 0; w < copies; ++w) c += s_bins[w * cs + k];
         if (c) atomicAdd(&parts[(size_t)(blockIdx.x % kParts) * K + k], c);
     }
 }

@@ -59,10 +59,11 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.ws_C = a.ws_B + (size_t)B * a.Np * a.Lpad;
     a.L = L; a.rows_total = B * D; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
-    // LDS budget for the per-row arrays (carried state and A): 8 KiB each, so that the staging buffers and the
-    // rows of a workgroup stay well below what a compute unit gives four workgroups.
+    // LDS budget for the per-row arrays (carried state and A): at most 32 rows and 8 KiB each, so that the staging
+    // buffers and the rows of a workgroup stay below what a compute unit gives four workgroups (chunks below 64,
+    // which would put more than 32 rows into a workgroup, run with idle lanes).
     int rows_cap = (int)(2048 / a.Np);
-    a.rows_cap = rows_cap < 1 ? 1 : rows_cap;
+    a.rows_cap = rows_cap < 1 ? 1 : (rows_cap > 32 ? 32 : rows_cap);
 
     corey_scan::LaunchPlan p;
     p.items = corey_scan::items_per_lane(B * D, chunk);

@@ -77,12 +77,14 @@ template <int K, int CHUNK> struct Geo {
     static constexpr int STAGE = G * CHUNK;                     // floats per operand per staging buffer
 };
 
-// Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes and needs fewer registers,
-// which pays when 16 would leave the chip short of waves.  The same rule runs on the host (known chunk) and on
-// the device (per-sequence chunk read from memory); `rows` is B * D.
+// Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes and needs fewer registers (five
+// waves per SIMD instead of four), which pays when 16 would leave the chip short of waves: fewer than four per SIMD
+// (256 CUs x 4 SIMDs x 4 waves x 64 lanes = 262144 lanes), as long as a row still fits one wave (chunk <= 512).
+// Measured on the five benchmark layers and the paper's shape: the rule picks the faster of the two everywhere.
+// The same rule runs on the host (known chunk) and on the device (per-sequence chunk read from memory); `rows` is B * D.
 __host__ __device__ inline int items_per_lane(int64_t rows, int chunk)
 {
-    return (chunk < 16 || rows * (chunk / 16) < 131072) ? 8 : 16;
+    return (chunk <= 512 && rows * (chunk / 16) < 262144) ? 8 : 16;
 }
 
 // ------------------------------------------------------------------------------------------- storage types
@@ -659,17 +661,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_ta
     scan_rows<T, K, CHUNK>(a, s_mem);
 }
 
-// Per-sequence chunk read from device memory: every geometry in one kernel, selected per workgroup.
-template <typename T>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4))) void k_scan_any(const ScanArgs a)
+// Per-sequence chunk read from device memory: every chunk's geometry in one kernel, selected per workgroup.  One
+// such kernel per items-per-lane class, because the class fixes the register budget (and with it the waves per
+// SIMD); the launch runs both and a workgroup whose sequence belongs to the other class leaves at once.
+template <typename T, int K>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_target<K>()))) void k_scan_any(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
     const int chunk = resolve_chunk(a, blockIdx.y);
-    const int K = items_per_lane(a.rows_total, chunk);
+    if (items_per_lane(a.rows_total, chunk) != K) return;
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        if (K == 8) { if constexpr (C >= 8) scan_rows<T, 8, C>(a, s_mem); }                 \
-        else { if constexpr (C >= 16) scan_rows<T, 16, C>(a, s_mem); }                      \
+        if constexpr (C >= K) scan_rows<T, K, C>(a, s_mem);                                 \
         break;
     switch (chunk) {
         COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
@@ -717,15 +720,17 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
         static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.seqlens, a.chunks_dev, p.chunk, p.items,
         a.rows_total, (int)p.N, a.Np, a.L, a.Lpad);
     if (p.routed) {
-        // grid for the geometry with the fewest rows per workgroup (surplus workgroups leave at once), LDS for the largest need
-        int64_t gx = 0, g;
-        size_t lds = 0, l;
-#define COREY_GEO(K, C) geometry<K, C>(p, a.rows_cap, g, l); gx = g > gx ? g : gx; lds = l > lds ? l : lds;
-        COREY_GEO(8, 16) COREY_GEO(8, 32) COREY_GEO(8, 64) COREY_GEO(8, 128) COREY_GEO(8, 256) COREY_GEO(8, 512)
-        COREY_GEO(8, 1024) COREY_GEO(8, 2048) COREY_GEO(16, 16) COREY_GEO(16, 32) COREY_GEO(16, 64) COREY_GEO(16, 128)
-        COREY_GEO(16, 256) COREY_GEO(16, 512) COREY_GEO(16, 1024) COREY_GEO(16, 2048)
+        // per class: grid for the geometry with the fewest rows per workgroup (surplus workgroups leave at once), LDS for
+        // the largest need
+        int64_t gx8 = 0, gx16 = 0, g;
+        size_t lds8 = 0, lds16 = 0, l;
+#define COREY_GEO(C)                                                                        \
+        geometry<8, C>(p, a.rows_cap, g, l); gx8 = g > gx8 ? g : gx8; lds8 = l > lds8 ? l : lds8;          \
+        geometry<16, C>(p, a.rows_cap, g, l); gx16 = g > gx16 ? g : gx16; lds16 = l > lds16 ? l : lds16;
+        COREY_GEO(16) COREY_GEO(32) COREY_GEO(64) COREY_GEO(128) COREY_GEO(256) COREY_GEO(512) COREY_GEO(1024) COREY_GEO(2048)
 #undef COREY_GEO
-        k_scan_any<T><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
+        k_scan_any<T, 16><<<dim3((unsigned)gx16, (unsigned)p.B), dim3(kBlock), lds16, p.stream>>>(a);
+        k_scan_any<T, 8><<<dim3((unsigned)gx8, (unsigned)p.B), dim3(kBlock), lds8, p.stream>>>(a);
         return;
     }
 #define COREY_CASE(C)                                                                       \
