@@ -74,18 +74,22 @@ typedef enum {
  *               histogram per sequence b over the positions t < seqlens[b] of its D channels (nh = B);
  *               0 <= seqlens[b] <= L is the caller's responsibility (values are clamped to [0, L]).
  *   K           number of bins, 2 <= K <= COREY_MAX_BINS.   eps >= 0 (the paper's hook uses 1e-8).
- *   stride      >= 1.  Number the values of one histogram in memory order j = 0, 1, ...; value j is used
- *               iff j % stride == 0.  1 is the exact statistic; 8 is the paper's sampled variant.
+ *   stride, block   >= 1.  Number the values of one histogram in memory order j = 0, 1, ... and cut them into blocks
+ *               of `block` consecutive values; value j is used iff (j / block) % stride == 0 (every stride-th block).
+ *               stride 1 is the exact statistic.  stride 8 with block 1 is the paper's sampled variant (its routed
+ *               ablation's "sampled histogram (stride 8)"), which thins the arithmetic but still touches every cache
+ *               line; with a block of a few hundred values (a power-of-two number of 16-byte words, e.g. 512) only
+ *               the sampled runs of memory are fetched, so the statistic costs 1/stride of the traffic.
  *   counts_out  DEVICE uint32[nh * K].   H_out, r_out: DEVICE double[nh].
  *   range_out   DEVICE float[nh * 2] (lo, hi per histogram) or NULL.
  *   workspace   DEVICE, at least corey_entropy_hist_workspace(B, K) bytes, 256-byte aligned; scratch only,
  *               contents are undefined afterwards.
- * The work is two sweeps over x (range, then counts) plus an O(K) reduction, as the paper's protocol
- * states; H is summed in double.  Counts are exact integers; H and r agree with a sequential double
+ * The work is two sweeps over the sampled values of x (range, then counts) plus an O(K) reduction, as the paper's
+ * protocol states; H is summed in double.  Counts are exact integers; H and r agree with a sequential double
  * evaluation to summation-order rounding (about 1e-15 relative).
  * ----------------------------------------------------------------------------------------------------- */
 int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
-                       const int32_t* seqlens, int32_t K, double eps, int64_t stride,
+                       const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
                        uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
@@ -180,7 +184,7 @@ int selective_scan_fwd(const void* u, const void* delta, const float* A, const v
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of workspace selective_scan_fwd needs (0 if the arguments are invalid): room for B and C as fp32,
- * padded along L to whole tiles, 2 * B * N * (L + 2048 rounded up to 4) * 4. */
+ * padded along L to whole tiles and in N to a multiple of 4:  2 * B * roundup(N, 4) * roundup(L + 2048, 4) * 4. */
 size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L);
 
 /* Message for the most recent failing call on this thread ("" if none).  Static storage; do not free. */

@@ -72,17 +72,20 @@ enum {
  * x        float[B][D][L]; low-precision inputs are widened exactly by the caller.
  * seqlens  NULL: one histogram over every element.  Otherwise int32[B]: one histogram per sequence b
  *          over the valid positions t < seqlens[b] of all D channels (nh = B histograms).
- * stride   >= 1.  The valid elements of one histogram, taken in memory order (d major, t minor, and b
- *          outermost for the whole-tensor case), are numbered j = 0, 1, ...; element j is used iff
- *          j % stride == 0.  stride 1 is the exact statistic; stride 8 is the paper's sampled variant.
+ * stride, block  >= 1.  The valid elements of one histogram, taken in memory order (d major, t minor, and b
+ *          outermost for the whole-tensor case), are numbered j = 0, 1, ... and cut into blocks of `block`
+ *          consecutive elements; element j is used iff (j / block) % stride == 0, i.e. every stride-th block.
+ *          stride 1 is the exact statistic; stride 8 with block 1 is the paper's sampled variant ("sampled
+ *          histogram (stride 8)" of the routed ablation, which does not say along which axis it strides: memory
+ *          order is the reading taken); block > 1 samples whole runs of memory instead of single elements.
  * counts   uint32[nh][K] out.   H, r: double[nh] out.   lo, hi: float[nh] out (may be NULL).
  * ---------------------------------------------------------------------------------------------- */
 int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
-                        int32_t K, double eps, int64_t stride,
+                        int32_t K, double eps, int64_t stride, int64_t block,
                         uint32_t* counts, double* H, double* r, float* lo_out, float* hi_out)
 {
     if (!x || !counts || !H || !r) return ORACLE_EINVAL;
-    if (B < 1 || D < 1 || L < 1 || K < 2 || stride < 1 || !(eps >= 0.0)) return ORACLE_EINVAL;
+    if (B < 1 || D < 1 || L < 1 || K < 2 || stride < 1 || block < 1 || !(eps >= 0.0)) return ORACLE_EINVAL;
     const int64_t nh = seqlens ? B : 1;
     int status = ORACLE_OK;
 
@@ -101,7 +104,7 @@ int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const i
             if (len < 0 || len > L) return ORACLE_EINVAL;
             for (int64_t d = 0; d < D; ++d)
                 for (int64_t t = 0; t < len; ++t, ++j) {
-                    if (j % stride) continue;
+                    if ((j / block) % stride) continue;
                     float v = x[(b * D + d) * L + t];
                     if (v != v) seen_nan = 1;
                     if (v < lo) lo = v;
@@ -127,7 +130,7 @@ int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const i
                 int64_t len = seqlens ? seqlens[b] : L;
                 for (int64_t d = 0; d < D; ++d)
                     for (int64_t t = 0; t < len; ++t, ++j) {
-                        if (j % stride) continue;
+                        if ((j / block) % stride) continue;
                         const float tt = x[(b * D + d) * L + t] - lo;   /* one binary32 subtract */
                         const float q = tt * scale;                     /* one binary32 multiply */
                         int64_t k = (int64_t)q;                            /* truncate, q >= 0 */

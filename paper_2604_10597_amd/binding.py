@@ -48,7 +48,7 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         i64, i32, vp, dbl = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_double
         L.corey_entropy_hist.restype = ctypes.c_int
-        L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, vp, vp, vp, vp, vp,
+        L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp,
                                          ctypes.c_size_t, vp]
         L.corey_entropy_hist_workspace.restype = ctypes.c_size_t
         L.corey_entropy_hist_workspace.argtypes = [i64, i32]
@@ -112,7 +112,7 @@ def corey_entropy_hist_workspace(B: int, K: int) -> int:
 
 
 def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int = 1, seqlens: torch.Tensor | None = None,
-                       out: dict | None = None, workspace: torch.Tensor | None = None):
+                       out: dict | None = None, workspace: torch.Tensor | None = None, block: int = 1):
     """x: [B, D, L] GPU tensor (float32 or bfloat16).  Returns dict(counts, H, r, range) of GPU tensors;
     nothing is copied to the host and the call does not synchronise."""
     _dev(x, "x"), _dev(seqlens, "seqlens")
@@ -128,7 +128,7 @@ def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int =
     need = corey_entropy_hist_workspace(B, K)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
-    _check(lib().corey_entropy_hist(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride,
+    _check(lib().corey_entropy_hist(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride, block,
                                     _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
                                     _ptr(workspace), workspace.numel(), _stream()))
     out["workspace"] = workspace

@@ -3,7 +3,7 @@
 // Three sweeps, as the paper's estimation protocol states them (a min/max pass, a bin-count pass, an
 // O(K) reduction):
 //   k_entropy_init      clears the partial counts and the range keys (a kernel, not a memset, so a caller may
-//                       capture it)
+//                       capture it); only the general path needs it
 //   k_entropy_range     lo/hi per histogram: 16-byte loads, wave + workgroup reduction, one pair of integer
 //                       atomics per workgroup on order-preserving keys
 //   k_entropy_count     bin index per value in binary32 (subtract, multiply, truncate: the ABI's definition),
@@ -13,6 +13,10 @@
 //                       of many workgroups do not all queue on the same few cache lines)
 //   k_entropy_finalise  sums the partial histograms into counts, then p_k, H = -sum p log(p + eps) and r in
 //                       double, one workgroup per histogram
+// The common call (one histogram over the whole tensor, aligned, every value or every stride-th block of a
+// power-of-two number of 16-byte words) takes the *_flat kernels: the range sweep leaves one partial range per
+// workgroup (no atomics, so nothing has to be cleared first; it also clears the partial counts), the count sweep
+// starts by reducing those partials, and only the sampled 16-byte words are fetched at all.
 // All of it is bandwidth work: no matrix instructions.
 #include <hip/hip_runtime.h>
 
@@ -99,18 +103,40 @@ __device__ __forceinline__ Geometry geometry(int h, int64_t B, int64_t D, int64_
 
 constexpr int kUnroll = 4;   // 16-byte loads a thread keeps in flight
 
+// Which of the values numbered idx, idx + 1, ... (memory order within one histogram) are sampled: every stride-th
+// block of `block` consecutive values.
+struct SamplePhase {
+    int64_t pos, bph, block, stride;
+    __device__ __forceinline__ SamplePhase(int64_t idx, int64_t block_, int64_t stride_) : block(block_), stride(stride_)
+    {
+        const int64_t blk = idx / block;
+        pos = idx - blk * block;
+        bph = blk % stride;
+    }
+    __device__ __forceinline__ bool take_and_advance()
+    {
+        const bool take = bph == 0;
+        if (++pos == block) {
+            pos = 0;
+            if (++bph == stride) bph = 0;
+        }
+        return take;
+    }
+};
+
 // Visit every sampled value of histogram `h` once: f(value).  A workgroup takes (row, segment) units
 // grid-stride; inside a unit every thread owns kUnroll 16-byte vectors, kThreads vectors apart, all loaded
 // before any is consumed so that enough bytes are in flight to cover HBM latency.  `vector_ok` says rows are
 // 16-byte aligned (pointer and L); otherwise, and in the ragged last segment of a row, values are fetched
 // one by one.
 template <typename T, typename F>
-__device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, int64_t stride, bool vector_ok, F&& f)
+__device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, int64_t stride, int64_t block, bool vector_ok, F&& f)
 {
     constexpr int V = Elem<T>::kVec;
     constexpr int64_t kSeg = (int64_t)kThreads * V * kUnroll;
     typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
     if (g.len == 0) return;
+    const bool all = stride == 1;
     const int64_t nseg = (g.len + kSeg - 1) / kSeg;
     const int64_t units = g.rows * nseg;
     for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
@@ -126,17 +152,15 @@ __device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, in
             for (int k = 0; k < kUnroll; ++k) {
                 T v[V];
                 __builtin_memcpy(v, &raw[k], kVecBytes);
-                if (stride == 1) {
+                if (all) {
 #pragma unroll
                     for (int e = 0; e < V; ++e) f(Elem<T>::widen(v[e]));
                 } else {
                     const int64_t t0 = seg0 + ((int64_t)k * kThreads + threadIdx.x) * V;
-                    int64_t phase = (r * g.len + t0) % stride;     // index of v[0] in memory order, modulo stride
+                    SamplePhase ph(r * g.len + t0, block, stride);     // index of v[0] in memory order
 #pragma unroll
-                    for (int e = 0; e < V; ++e) {
-                        if (phase == 0) f(Elem<T>::widen(v[e]));
-                        if (++phase == stride) phase = 0;
-                    }
+                    for (int e = 0; e < V; ++e)
+                        if (ph.take_and_advance()) f(Elem<T>::widen(v[e]));
                 }
             }
         } else {
@@ -144,11 +168,9 @@ __device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, in
                 const int64_t t0 = seg0 + ((int64_t)k * kThreads + threadIdx.x) * V;
                 if (t0 >= g.len) break;
                 const int nvalid = (g.len - t0 < V) ? (int)(g.len - t0) : V;
-                int64_t phase = (stride == 1) ? 0 : (r * g.len + t0) % stride;
-                for (int e = 0; e < nvalid; ++e) {
-                    if (phase == 0) f(Elem<T>::widen(row[t0 + e]));
-                    if (stride != 1 && ++phase == stride) phase = 0;
-                }
+                SamplePhase ph(all ? 0 : r * g.len + t0, block, stride);
+                for (int e = 0; e < nvalid; ++e)
+                    if (all || ph.take_and_advance()) f(Elem<T>::widen(row[t0 + e]));
             }
         }
     }
@@ -166,14 +188,9 @@ __global__ void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots
     }
 }
 
-// Workgroup reduction of (lo, hi, nan flag) and the integer atomics that publish it.  The slot is read
-// first and an atomic is issued only if it would change it: extremes only move one way, so a stale read can
-// cost a redundant atomic but never lose an update, and almost all workgroups skip the contended atomics.
-__device__ __forceinline__ void publish_range(float lo, float hi, bool nan, RangeSlot* slot)
+// Workgroup reduction of (lo, hi, nan flag) as order-preserving keys; the result is valid in thread 0.
+__device__ __forceinline__ void reduce_range_keys(uint32_t& klo, uint32_t& khi, uint32_t& knan)
 {
-    uint32_t klo = (lo <= hi) ? order_key(lo) : 0xffffffffu;
-    uint32_t khi = (lo <= hi) ? order_key(hi) : 0u;
-    uint32_t knan = nan ? 1u : 0u;
     for (int off = 32; off > 0; off >>= 1) {
         klo = min(klo, (uint32_t)__shfl_xor((int)klo, off));
         khi = max(khi, (uint32_t)__shfl_xor((int)khi, off));
@@ -189,6 +206,19 @@ __device__ __forceinline__ void publish_range(float lo, float hi, bool nan, Rang
             khi = max(khi, s_hi[w]);
             knan |= s_nan[w];
         }
+    }
+}
+
+// ... and the integer atomics that publish it.  The slot is read first and an atomic is issued only if it
+// would change it: extremes only move one way, so a stale read can cost a redundant atomic but never lose an
+// update, and almost all workgroups skip the contended atomics.
+__device__ __forceinline__ void publish_range(float lo, float hi, bool nan, RangeSlot* slot)
+{
+    uint32_t klo = (lo <= hi) ? order_key(lo) : 0xffffffffu;
+    uint32_t khi = (lo <= hi) ? order_key(hi) : 0u;
+    uint32_t knan = nan ? 1u : 0u;
+    reduce_range_keys(klo, khi, knan);
+    if (threadIdx.x == 0) {
         if (klo < __atomic_load_n(&slot->lo_key, __ATOMIC_RELAXED)) atomicMin(&slot->lo_key, klo);
         if (khi > __atomic_load_n(&slot->hi_key, __ATOMIC_RELAXED)) atomicMax(&slot->hi_key, khi);
         if (knan) atomicOr(&slot->saw_nan, 1u);
@@ -197,14 +227,14 @@ __device__ __forceinline__ void publish_range(float lo, float hi, bool nan, Rang
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_entropy_range(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
-                                                            const int32_t* __restrict__ seqlens, int64_t stride,
+                                                            const int32_t* __restrict__ seqlens, int64_t stride, int64_t block,
                                                             int vector_ok, RangeSlot* slots)
 {
     const int h = blockIdx.y;
     const Geometry g = geometry(h, B, D, L, seqlens);
     float lo = INFINITY, hi = -INFINITY;
     bool nan = false;
-    for_each_value(x, g, stride, vector_ok != 0, [&](float v) {
+    for_each_value(x, g, stride, block, vector_ok != 0, [&](float v) {
         nan |= (v != v);
         lo = fminf(lo, v);       // fminf/fmaxf drop a NaN operand; NaNs are flagged separately
         hi = fmaxf(hi, v);
@@ -272,9 +302,30 @@ template <> struct RangeFold<float> {
     static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return mag > 0x7f800000u; }
 };
 
-template <typename T>
-__global__ __launch_bounds__(kThreads) void k_entropy_range_flat(const word4* __restrict__ x, int64_t nwords, RangeSlot* slots)
+// The 16-byte words of a flat sweep.  Unsampled: word i is word i.  Sampled: the tensor is cut into blocks of
+// 2^bw_log2 words and every stride-th block is used; the sampled words are numbered consecutively.
+template <bool SAMPLED> struct WordMap {
+    int bw_log2;
+    int64_t stride;
+    __device__ __forceinline__ int64_t operator()(int64_t i) const
+    {
+        if constexpr (!SAMPLED) return i;
+        const int64_t sb = i >> bw_log2;
+        return ((sb * stride) << bw_log2) + (i - (sb << bw_log2));
+    }
+};
+
+struct RangePart {        // what one workgroup of the flat range sweep saw
+    uint32_t lo_key, hi_key, saw_nan, pad;
+};
+
+template <typename T, bool SAMPLED>
+__global__ __launch_bounds__(kThreads) void k_entropy_range_flat(const word4* __restrict__ x, int64_t nwords, WordMap<SAMPLED> map,
+                                                                 RangePart* __restrict__ rparts, uint32_t* __restrict__ parts,
+                                                                 int nparts)
 {
+    // the partial counts the next sweep adds into
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < nparts; i += gridDim.x * kThreads) parts[i] = 0u;
     float lo = INFINITY, hi = -INFINITY;
     uint32_t mag = 0u;
     const int64_t step = (int64_t)gridDim.x * kThreads * kUnroll;
@@ -282,15 +333,23 @@ __global__ __launch_bounds__(kThreads) void k_entropy_range_flat(const word4* __
     for (; base + kThreads * kUnroll <= nwords; base += step) {
         word4 q[kUnroll];
 #pragma unroll
-        for (int k = 0; k < kUnroll; ++k) q[k] = x[base + k * kThreads + threadIdx.x];
+        for (int k = 0; k < kUnroll; ++k) q[k] = x[map(base + k * kThreads + threadIdx.x)];
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) RangeFold<T>::fold(q[k], lo, hi, mag);
     }
     for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) {     // ragged end: at most one workgroup gets here
-        const word4 q = x[i];
+        const word4 q = x[map(i)];
         RangeFold<T>::fold(q, lo, hi, mag);
     }
-    publish_range(lo, hi, RangeFold<T>::saw_nan(mag), &slots[0]);
+    uint32_t klo = (lo <= hi) ? order_key(lo) : 0xffffffffu;
+    uint32_t khi = (lo <= hi) ? order_key(hi) : 0u;
+    uint32_t knan = RangeFold<T>::saw_nan(mag) ? 1u : 0u;
+    reduce_range_keys(klo, khi, knan);
+    if (threadIdx.x == 0) {
+        RangePart rp;
+        rp.lo_key = klo; rp.hi_key = khi; rp.saw_nan = knan; rp.pad = 0u;
+        rparts[blockIdx.x] = rp;
+    }
 }
 
 __device__ __forceinline__ bool usable_range(const RangeSlot& s, float* lo, float* hi)
@@ -315,7 +374,7 @@ __device__ __forceinline__ int lds_copies(int K)
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
-                                                            const int32_t* __restrict__ seqlens, int64_t stride,
+                                                            const int32_t* __restrict__ seqlens, int64_t stride, int64_t block,
                                                             int vector_ok, int K, const RangeSlot* __restrict__ slots,
                                                             uint32_t* parts)
 {
@@ -334,12 +393,12 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict_
 
     if (hi == lo) {
         uint32_t n = 0;
-        for_each_value(x, g, stride, vector_ok != 0, [&](float) { ++n; });
+        for_each_value(x, g, stride, block, vector_ok != 0, [&](float) { ++n; });
         if (n) atomicAdd(&mine[0], n);
     } else {
         const float scale = (float)((double)K / ((double)hi - (double)lo));
         const int top = K - 1;
-        for_each_value(x, g, stride, vector_ok != 0, [&](float v) {
+        for_each_value(x, g, stride, block, vector_ok != 0, [&](float v) {
             const float q = __fmul_rn(__fsub_rn(v, lo), scale);   // two separate binary32 roundings
             int k = (int)q;                                        // truncation; q >= 0
             k = k > top ? top : (k < 0 ? 0 : k);
@@ -355,13 +414,30 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict_
     }
 }
 
-template <typename T>
-__global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __restrict__ x, int64_t nwords, int K,
-                                                                 const RangeSlot* __restrict__ slots, uint32_t* parts)
+template <typename T, bool SAMPLED>
+__global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __restrict__ x, int64_t nwords, WordMap<SAMPLED> map, int K,
+                                                                 const RangePart* __restrict__ rparts, int nrparts,
+                                                                 RangeSlot* __restrict__ slots, uint32_t* parts)
 {
     __shared__ uint32_t s_bins[kMaxLdsBins];
+    __shared__ RangeSlot s_slot;
+    {   // the range: every workgroup reduces the partial ranges of the sweep before (a few KB from L2)
+        uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
+        for (int i = threadIdx.x; i < nrparts; i += kThreads) {
+            const RangePart rp = rparts[i];
+            klo = min(klo, rp.lo_key);
+            khi = max(khi, rp.hi_key);
+            knan |= rp.saw_nan;
+        }
+        reduce_range_keys(klo, khi, knan);
+        if (threadIdx.x == 0) {
+            s_slot.lo_key = klo; s_slot.hi_key = khi; s_slot.saw_nan = knan; s_slot.pad = 0u;
+            if (blockIdx.x == 0) slots[0] = s_slot;           // for the reduction kernel
+        }
+        __syncthreads();
+    }
     float lo, hi;
-    if (!usable_range(slots[0], &lo, &hi)) return;            // counts stay zero, H and r become NaN
+    if (!usable_range(s_slot, &lo, &hi)) return;              // counts stay zero, H and r become NaN
     const int cs = K + 1;                                     // copy stride: odd offset between copies, see lds_copies
     const int copies = lds_copies(K);
     for (int i = threadIdx.x; i < cs * copies; i += kThreads) s_bins[i] = 0u;
@@ -395,11 +471,11 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
     for (; base + kThreads * kUnroll <= nwords; base += step) {
         word4 q[kUnroll];
 #pragma unroll
-        for (int k = 0; k < kUnroll; ++k) q[k] = x[base + k * kThreads + threadIdx.x];
+        for (int k = 0; k < kUnroll; ++k) q[k] = x[map(base + k * kThreads + threadIdx.x)];
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) fold(q[k]);
     }
-    for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) fold(x[i]);
+    for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) fold(x[map(i)]);
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += kThreads) {
         uint32_t c = 0;
@@ -507,27 +583,50 @@ size_t slots_bytes(int64_t nh)
     return (raw + 255) / 256 * 256;
 }
 
-size_t workspace_bytes(int64_t nh, int32_t K) { return slots_bytes(nh) + (size_t)nh * kParts * K * sizeof(uint32_t); }
+size_t parts_bytes(int64_t nh, int32_t K) { return ((size_t)nh * kParts * K * sizeof(uint32_t) + 255) / 256 * 256; }
+
+size_t workspace_bytes(int64_t nh, int32_t K) { return slots_bytes(nh) + parts_bytes(nh, K) + (size_t)kMaxBlocks * sizeof(RangePart); }
+
+template <typename T, bool SAMPLED>
+void launch_flat(const word4* x, int64_t nwords, WordMap<SAMPLED> map, int32_t K, RangeSlot* slots, uint32_t* parts,
+                 RangePart* rparts, hipStream_t stream)
+{
+    int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
+    blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
+    k_entropy_range_flat<T, SAMPLED><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(x, nwords, map, rparts, parts, kParts * K);
+    k_entropy_count_flat<T, SAMPLED><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(x, nwords, map, K, rparts, (int)blocks,
+                                                                                          slots, parts);
+}
 
 template <typename T>
 int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K, double eps, int64_t stride,
-           uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream)
+           int64_t block, uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream)
 {
     const int nh = seqlens ? (int)B : 1;
     uint32_t* parts = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(slots) + slots_bytes(B));
+    RangePart* rparts = reinterpret_cast<RangePart*>(reinterpret_cast<char*>(parts) + parts_bytes(B, K));
     const int64_t nparts = (int64_t)nh * kParts * K;
-    k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
 
     constexpr int V = Elem<T>::kVec;
     const int64_t E = B * D * L;
-    if (!seqlens && stride == 1 && reinterpret_cast<uintptr_t>(x) % kVecBytes == 0 && E % V == 0) {
+    const bool flat_ok = !seqlens && reinterpret_cast<uintptr_t>(x) % kVecBytes == 0 && E % V == 0;
+    const int64_t bw = block / V;                              // 16-byte words per sampling block
+    if (flat_ok && stride == 1) {
         // whole tensor, every value, aligned: flat sweeps
-        const int64_t nwords = E / V;
-        int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
-        blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
-        k_entropy_range_flat<T><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(static_cast<const word4*>(x), nwords, slots);
-        k_entropy_count_flat<T><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(static_cast<const word4*>(x), nwords, K, slots, parts);
+        launch_flat<T, false>(static_cast<const word4*>(x), E / V, WordMap<false>{0, 1}, K, slots, parts, rparts, stream);
+    } else if (flat_ok && block % V == 0 && corey::is_pow2(bw)) {
+        // whole tensor, every stride-th block of a power-of-two number of words: flat sweeps over the sampled words only
+        const int64_t nwords_all = E / V;
+        const int64_t nb = (nwords_all + bw - 1) / bw;          // blocks in the tensor (the last may be short)
+        const int64_t ns = (nb + stride - 1) / stride;          // sampled blocks
+        const int64_t last_first = (ns - 1) * stride * bw;      // first word of the last sampled block
+        const int64_t last_words = nwords_all - last_first < bw ? nwords_all - last_first : bw;
+        int bw_log2 = 0;
+        while (((int64_t)1 << bw_log2) < bw) ++bw_log2;
+        launch_flat<T, true>(static_cast<const word4*>(x), (ns - 1) * bw + last_words, WordMap<true>{bw_log2, stride}, K, slots,
+                             parts, rparts, stream);
     } else {
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
         const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
         const int64_t rows = seqlens ? D : B * D;
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
@@ -535,9 +634,9 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         int64_t blocks = units < 1 ? 1 : units;
         if (blocks > kMaxBlocks) blocks = kMaxBlocks;
         const dim3 grid((unsigned)blocks, (unsigned)nh);
-        k_entropy_range<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride,
+        k_entropy_range<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride, block,
                                                                vector_ok ? 1 : 0, slots);
-        k_entropy_count<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride,
+        k_entropy_count<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride, block,
                                                                vector_ok ? 1 : 0, K, slots, parts);
     }
     k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, slots, H_out, r_out, range_out);
@@ -574,8 +673,8 @@ extern "C" size_t corey_entropy_hist_workspace(int64_t B, int32_t K)
 }
 
 extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
-                                  int32_t K, double eps, int64_t stride, uint32_t* counts_out, double* H_out, double* r_out,
-                                  float* range_out, void* workspace, size_t workspace_bytes_given, void* hip_stream)
+                                  int32_t K, double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out,
+                                  double* r_out, float* range_out, void* workspace, size_t workspace_bytes_given, void* hip_stream)
 {
     using corey::fail;
     if (!x || !counts_out || !H_out || !r_out) return fail(COREY_ENULL, "corey_entropy_hist: x, counts_out, H_out and r_out are required");
@@ -587,7 +686,7 @@ extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int6
         return fail(COREY_ESHAPE, "corey_entropy_hist: more than 2^32-1 samples would overflow the 32-bit counts");
     if (K < 2 || K > COREY_MAX_BINS) return fail(COREY_EINVAL, "corey_entropy_hist: K = %d outside [2, %d]", K, COREY_MAX_BINS);
     if (!(eps >= 0.0)) return fail(COREY_EINVAL, "corey_entropy_hist: eps must be >= 0");
-    if (stride < 1) return fail(COREY_EINVAL, "corey_entropy_hist: stride must be >= 1");
+    if (stride < 1 || block < 1) return fail(COREY_EINVAL, "corey_entropy_hist: stride and block must be >= 1");
     const size_t need = workspace_bytes(B, K);
     if (!workspace || workspace_bytes_given < need)
         return fail(COREY_EWORKSPACE, "corey_entropy_hist: workspace of %zu bytes required", need);
@@ -595,8 +694,8 @@ extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int6
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     RangeSlot* slots = static_cast<RangeSlot*>(workspace);
     if (dt == COREY_F32)
-        return launch<float>(x, B, D, L, seqlens, K, eps, stride, counts_out, H_out, r_out, range_out, slots, stream);
+        return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream);
     if (dt == COREY_F16)
-        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, counts_out, H_out, r_out, range_out, slots, stream);
-    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, counts_out, H_out, r_out, range_out, slots, stream);
+        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream);
+    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream);
 }

@@ -423,17 +423,14 @@ __host__ __device__ constexpr int lds_floats(int rows, int N)
 }
 
 // ------------------------------------------------------------------------------------------- the scan
+// The rows d0 .. d0 + rows - 1 of sequence blockIdx.y, start to end.
 template <typename T, int K, int CHUNK>
-__device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
+__device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, const int rows, const int d0)
 {
     using Gm = Geo<K, CHUNK>;
     constexpr int LPR = Gm::LPR, SEG = Gm::SEG, WPR = Gm::WPR, G = Gm::G, STAGE = Gm::STAGE, KQ = K / 4;
 
     const int b = blockIdx.y;
-    const int rows = Gm::ROWS < a.rows_cap ? Gm::ROWS : a.rows_cap;   // rows of this workgroup
-    const int d0 = blockIdx.x * rows;
-    if (d0 >= a.D) return;                                  // whole workgroup leaves together
-
     const int tid = threadIdx.x;
     const int row_local = tid / LPR;
     const int j = tid % LPR;                                // sub-block of this lane inside the tile
@@ -649,6 +646,20 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
     }
 }
 
+// A workgroup takes groups of `rows` rows of its sequence, grid-stride.  A launch whose grid was sized from the
+// run-time chunk gives every workgroup exactly one group; a launch that reads the chunk from device memory sizes
+// its grid from the host's hint and is correct for any chunk (more groups than workgroups: some take several in
+// turn; fewer: the surplus leaves at once).
+template <typename T, int K, int CHUNK>
+__device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
+{
+    const int rows = Geo<K, CHUNK>::ROWS < a.rows_cap ? Geo<K, CHUNK>::ROWS : a.rows_cap;
+    for (int64_t d0 = (int64_t)blockIdx.x * rows; d0 < a.D; d0 += (int64_t)gridDim.x * rows) {   // uniform over the workgroup
+        scan_group<T, K, CHUNK>(a, s_mem, rows, (int)d0);
+        __syncthreads();                                     // the LDS arrays are set up afresh for the next group
+    }
+}
+
 // Register budget: K = 16 keeps 16 x (dl, du, y, a, b) per lane and is built for four waves per SIMD (128 VGPRs);
 // K = 8 for five.
 template <int K> constexpr int waves_target() { return K == 8 ? COREY_WAVES_K8 : COREY_WAVES_K16; }
@@ -661,18 +672,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_ta
     scan_rows<T, K, CHUNK>(a, s_mem);
 }
 
-// Per-sequence chunk read from device memory: every chunk's geometry in one kernel, selected per workgroup.  One
-// such kernel per items-per-lane class, because the class fixes the register budget (and with it the waves per
-// SIMD); the launch runs both and a workgroup whose sequence belongs to the other class leaves at once.
-template <typename T, int K>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_target<K>()))) void k_scan_any(const ScanArgs a)
+// Per-sequence chunk read from device memory: every geometry in one kernel, selected per workgroup (register budget
+// of the 16-step geometries).
+template <typename T>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WAVES_K16))) void k_scan_any(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
     const int chunk = resolve_chunk(a, blockIdx.y);
-    if (items_per_lane(a.rows_total, chunk) != K) return;
+    const int K = items_per_lane(a.rows_total, chunk);
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        if constexpr (C >= K) scan_rows<T, K, C>(a, s_mem);                                 \
+        if (K == 8) { if constexpr (C >= 8) scan_rows<T, 8, C>(a, s_mem); }                 \
+        else { if constexpr (C >= 16) scan_rows<T, 16, C>(a, s_mem); }                      \
         break;
     switch (chunk) {
         COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
@@ -720,17 +731,17 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
         static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.seqlens, a.chunks_dev, p.chunk, p.items,
         a.rows_total, (int)p.N, a.Np, a.L, a.Lpad);
     if (p.routed) {
-        // per class: grid for the geometry with the fewest rows per workgroup (surplus workgroups leave at once), LDS for
-        // the largest need
-        int64_t gx8 = 0, gx16 = 0, g;
-        size_t lds8 = 0, lds16 = 0, l;
+        // grid from the host's chunk (the caller's hint: workgroups take row groups grid-stride, so any grid is correct),
+        // LDS for the largest need of any geometry the rule can pick
+        int64_t gx = 0, g;
+        size_t lds = 0, l;
 #define COREY_GEO(C)                                                                        \
-        geometry<8, C>(p, a.rows_cap, g, l); gx8 = g > gx8 ? g : gx8; lds8 = l > lds8 ? l : lds8;          \
-        geometry<16, C>(p, a.rows_cap, g, l); gx16 = g > gx16 ? g : gx16; lds16 = l > lds16 ? l : lds16;
+        if (items_per_lane(a.rows_total, C) == 8) geometry<8, C>(p, a.rows_cap, g, l); else geometry<16, C>(p, a.rows_cap, g, l); \
+        lds = l > lds ? l : lds;                                                            \
+        if (C == p.chunk) gx = g;
         COREY_GEO(16) COREY_GEO(32) COREY_GEO(64) COREY_GEO(128) COREY_GEO(256) COREY_GEO(512) COREY_GEO(1024) COREY_GEO(2048)
 #undef COREY_GEO
-        k_scan_any<T, 16><<<dim3((unsigned)gx16, (unsigned)p.B), dim3(kBlock), lds16, p.stream>>>(a);
-        k_scan_any<T, 8><<<dim3((unsigned)gx8, (unsigned)p.B), dim3(kBlock), lds8, p.stream>>>(a);
+        k_scan_any<T><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
         return;
     }
 #define COREY_CASE(C)                                                                       \

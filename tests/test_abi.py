@@ -77,10 +77,10 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     none = ctypes.c_void_p(0)
     eh = lambda **kw: lib.corey_entropy_hist(
         kw.get("x", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("L", 8), none, kw.get("K", 16),
-        kw.get("eps", 1e-8), kw.get("stride", 1), kw.get("counts", fake), fake, fake, none, kw.get("ws", fake),
+        kw.get("eps", 1e-8), kw.get("stride", 1), kw.get("block", 1), kw.get("counts", fake), fake, fake, none, kw.get("ws", fake),
         kw.get("wsb", 256), none)
     assert eh(x=none) == 2 and eh(counts=none) == 2
-    assert eh(dt=7) == 1 and eh(K=1) == 1 and eh(K=5000) == 1 and eh(stride=0) == 1 and eh(eps=-1.0) == 1
+    assert eh(dt=7) == 1 and eh(K=1) == 1 and eh(K=5000) == 1 and eh(stride=0) == 1 and eh(block=0) == 1 and eh(eps=-1.0) == 1
     assert eh(B=0) == 3 and eh(L=0) == 3
     assert eh(ws=none) == 7 and eh(wsb=8) == 7
     assert lib.corey_entropy_hist_workspace(0, 16) == 0 and lib.corey_entropy_hist_workspace(3, 1) == 0

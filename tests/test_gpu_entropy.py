@@ -17,12 +17,12 @@ def _say(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def _check(x_store, x_val, dtype, K, eps=1e-8, stride=1, seqlens=None):
+def _check(x_store, x_val, dtype, K, eps=1e-8, stride=1, seqlens=None, block=1):
     xd = to_dev(x_store, dtype)
     sl = None if seqlens is None else torch.from_numpy(np.asarray(seqlens, dtype=np.int32)).cuda()
-    out = corey.corey_entropy_hist(xd, K, eps=eps, stride=stride, seqlens=sl)
+    out = corey.corey_entropy_hist(xd, K, eps=eps, stride=stride, seqlens=sl, block=block)
     torch.cuda.synchronize()
-    ref = oracle.entropy_hist(x_val, K, eps=eps, stride=stride, seqlens=seqlens)
+    ref = oracle.entropy_hist(x_val, K, eps=eps, stride=stride, seqlens=seqlens, block=block)
     got_counts = counts_u32(out["counts"])
     assert np.array_equal(got_counts, ref["counts"]), "bin counts differ"
     H, r, rng = out["H"].cpu().numpy(), out["r"].cpu().numpy(), out["range"].cpu().numpy()
@@ -74,6 +74,22 @@ def test_sampled_histogram(stride):
     w = wl.make(cfg)
     _check(w.dev["u"], w.val["u"], cfg.dtype, 256, stride=stride)
     _check(w.dev["u"], w.val["u"], cfg.dtype, 256, stride=stride, seqlens=np.array([520, 100, 7, 333], np.int32))
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F16, wl.F32])
+def test_block_sampled_histogram(dtype):
+    """Every stride-th block of consecutive values: the flat path (power-of-two blocks of whole 16-byte words, which
+    fetches only the sampled runs) and the general path (any block, per-sequence histograms, ragged ends)."""
+    cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=40, L=520, dtype=dtype)          # 83200 values: ragged against every block below
+    w = wl.make(cfg)
+    for stride, block in ((8, 512), (8, 8), (3, 64), (2, 4096), (5, 32768), (8, 262144), (4, 24), (8, 100), (7, 1)):
+        _say(f"entropy {dtype} stride {stride} block {block}")
+        _check(w.dev["u"], w.val["u"], cfg.dtype, 256, stride=stride, block=block)
+    _check(w.dev["u"], w.val["u"], cfg.dtype, 256, stride=4, block=16, seqlens=np.array([520, 100, 7, 333], np.int32))
+    cfg = wl.scaled(wl.CONFIGS["c4_mamba2p8b"], D=512, L=4096, dtype=dtype)       # large enough for every workgroup to loop
+    w = wl.make(cfg)
+    _say(f"entropy {dtype} 2M values stride 8 block 512")
+    _check(w.dev["u"], w.val["u"], cfg.dtype, 256, stride=8, block=512)
 
 
 def test_bin_limits_and_eps():

@@ -131,6 +131,20 @@ def test_layout_seqlens_and_stride():
         v = x[b, :, :lens[b]].reshape(-1)[::3]
         one = oracle.entropy_hist(v.reshape(1, 1, -1), 16)
         assert (ps["counts"][b] == one["counts"][0]).all()
+    # blocks: every stride-th run of `block` consecutive elements of the flattened tensor (ragged last run kept)
+    flat_x = x.reshape(-1)
+    for stride, block in ((2, 5), (3, 4), (8, 1), (4, 16), (2, 1000)):
+        keep = (np.arange(flat_x.size) // block) % stride == 0
+        s = oracle.entropy_hist(x, 16, stride=stride, block=block)
+        sub = oracle.entropy_hist(flat_x[keep].reshape(1, 1, -1), 16)
+        assert (s["counts"] == sub["counts"]).all() and s["H"][0] == sub["H"][0] and s["counts"].sum() == keep.sum()
+    pb = oracle.entropy_hist(x, 16, seqlens=lens, stride=2, block=3)
+    for b in range(B):
+        v = x[b, :, :lens[b]].reshape(-1)
+        v = v[(np.arange(v.size) // 3) % 2 == 0]
+        one = oracle.entropy_hist(v.reshape(1, 1, -1), 16)
+        assert (pb["counts"][b] == one["counts"][0]).all()
+    assert oracle.entropy_hist(x, 16, block=0)["status"] == oracle.EINVAL
 
 
 def _draw(kind, n, rng):
