@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the COREY hot path on one MI355X.
 
-One step = one pass of the whole path over one batch that already sits in HBM: corey_entropy_hist on u,
-corey_select_chunk_device on r, selective_scan_fwd reading the routed chunk from device memory (no host round
-trip inside a step).  Prints ONE JSON line.
+One step = one pass of the whole path over one batch that already sits in HBM: corey_route_device on u (the exact
+full histogram, H, r and the chunk rule on the GPU), then selective_scan_fwd reading the routed chunk from device
+memory (no host round trip inside a step).  Prints ONE JSON line.
 
   value      scan algorithmic bytes (u, delta, z in; y out; B, C, parameters, final state) per step time, GB/s
   roofline   for the dominant kernel (the scan): algorithmic bytes / its own launch duration, measured with
              events on the launch stream inside the timed region, against the 8 TB/s HBM peak; the `alu` block
              beside it prices the same launches against the fp32 vector peak, which is the bound that binds
   per_chunk  scan-only latency, GB/s and tokens/s for every chunk of the sweep
-  overhead   entropy + routing cost relative to the scan alone at the routed chunk
+  overhead   entropy + routing cost relative to the scan alone at the routed chunk, for the exact statistic (the
+             timed step) and for the sampled one (every 8th block of 512 values, the paper's stride-8 variant at
+             cache-line granularity), and with the chunk rule on the host instead
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload on this host's cores
 """
 from __future__ import annotations
@@ -89,14 +91,17 @@ def main() -> int:
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
                                  delta_bias=d["delta_bias"], seqlens=seqlens, chunk=chunk, y=y, last_state=last, workspace=scan_ws)
 
-    chunks_dev = torch.empty(ent["r"].numel(), dtype=torch.int32, device="cuda")
+    ent["chunks"] = torch.empty(ent["r"].numel(), dtype=torch.int32, device="cuda")
+    chunks_dev = ent["chunks"]
+    # the host's chunk is only the launch-shape hint of the device-routed scan: the chunk this workload routes to
+    hint = max(corey.corey_select_chunk(float(v), int(n), pol) for v, n in
+               zip(ent["r"].cpu().tolist(), (w.seqlens if w.seqlens is not None else [cfg.L] * ent["r"].numel())))
 
-    def scan_routed():
-        """The whole path with no host round trip: statistic -> chunk rule on the GPU -> scan that reads the chunk."""
-        corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
-        corey.corey_select_chunk_device(ent["r"], cfg.L, pol, seqlens=seqlens, out=chunks_dev)
+    def scan_routed(stride=1, block=1):
+        """The whole path with no host round trip: statistic and chunk rule on the GPU -> scan that reads the chunk."""
+        corey.corey_route_device(d["u"], cfg.K, pol, seqlens=seqlens, out=ent, stride=stride, block=block)
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
-                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=512, chunks_dev=chunks_dev,
+                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=hint, chunks_dev=chunks_dev,
                                  y=y, last_state=last, workspace=scan_ws)
 
     def route_on_host():
@@ -122,11 +127,10 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
-        corey.corey_select_chunk_device(ent["r"], cfg.L, pol, seqlens=seqlens, out=chunks_dev)
+        corey.corey_route_device(d["u"], cfg.K, pol, seqlens=seqlens, out=ent)
         ev0[i].record()
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
-                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=512, chunks_dev=chunks_dev,
+                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=hint, chunks_dev=chunks_dev,
                                  y=y, last_state=last, workspace=scan_ws)
         ev1[i].record()
     torch.cuda.synchronize()
@@ -134,6 +138,21 @@ def main() -> int:
     ms_step = (t1 - t0) * 1e3 / args.steps
     scan_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev0, ev1)]))
     chunk = int(chunks_dev.max().item())
+
+    # the same step with the sampled statistic (every 8th block of 512 values: 1/8 of the bytes of u)
+    def time_steps(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0s = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0s) * 1e3 / args.steps
+
+    ms_step_sampled = time_steps(lambda: scan_routed(8, 512))
+    r_sampled = [round(float(v), 6) for v in ent["r"].cpu().tolist()]
+    chunk_sampled = int(chunks_dev.max().item())
 
     # the same step with the chunk rule on the host (one 8-byte read of r and a synchronisation per step)
     for _ in range(2):
@@ -166,6 +185,12 @@ def main() -> int:
     hist_b.record()
     torch.cuda.synchronize()
     hist_ms = hist_a.elapsed_time(hist_b) / args.steps
+    hist_a.record()
+    for _ in range(args.steps):
+        corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"], stride=8, block=512)
+    hist_b.record()
+    torch.cuda.synchronize()
+    hist_sampled_ms = hist_a.elapsed_time(hist_b) / args.steps
     per_chunk = {}
     if not args.no_sweep:
         for c in cfg.chunks:
@@ -255,7 +280,11 @@ def main() -> int:
                      "host_routed_ms_per_step": round(ms_step_host, 4),
                      "host_routed_pct_of_scan": round((ms_step_host - scan_alone_ms) / scan_alone_ms * 100, 2),
                      "hist_kernels_ms": round(hist_ms, 4), "scan_alone_ms": round(scan_alone_ms, 4),
-                     "hist_pct_of_scan": round(hist_ms / scan_alone_ms * 100, 2)},
+                     "hist_pct_of_scan": round(hist_ms / scan_alone_ms * 100, 2),
+                     "sampled_stride8_block512": {"ms_per_step": round(ms_step_sampled, 4),
+                                                  "entropy_routing_pct_of_scan": round((ms_step_sampled - scan_alone_ms) / scan_alone_ms * 100, 2),
+                                                  "hist_kernels_ms": round(hist_sampled_ms, 4), "r": r_sampled,
+                                                  "routed_chunk": chunk_sampled}},
         "per_chunk": per_chunk,
         "paper_shape": paper_shape,
         "cpu_baseline": cpu,

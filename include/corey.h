@@ -147,6 +147,18 @@ int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64
                               const corey_policy* p, int32_t* chunks_out, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------
+ * corey_route_device -- corey_entropy_hist followed by corey_select_chunk_device in one call: the statistic of x,
+ * then the chunk rule applied to each r by the kernel that reduces the histogram (one launch fewer on the routed
+ * path; the paper counts scheduler dispatch among the costs of routing).  Arguments as for those two calls; the
+ * sequence length each decision is taken for is seqlens[h] when seqlens is given, else L.  Results are identical to
+ * calling the two one after the other.  Errors: as for both.
+ * ----------------------------------------------------------------------------------------------------- */
+int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
+                       const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
+                       const corey_policy* p, uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
+                       int32_t* chunks_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* -------------------------------------------------------------------------------------------------------
  * selective_scan_fwd -- the recurrence h_t = A_t h_{t-1} + B_t x_t, y_t = C_t h_t + D_t x_t (Method,
  * Preliminaries) in its Mamba-1 form, for every sequence b and channel d independently:
  *

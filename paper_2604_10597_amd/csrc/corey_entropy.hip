@@ -484,9 +484,45 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
     }
 }
 
+// Eq. 2 and the scheduler family around it for one histogram (see corey_select_chunk for the rule); 0 when r is NaN
+// in an entropy mode.
+__device__ __forceinline__ int32_t chunk_rule(double rv, int64_t L, const corey_policy& p)
+{
+    if (L < 1) L = 1;
+    const bool short_seq = L <= p.short_len;
+    int64_t c;
+    if (p.mode == 3) {
+        c = p.static_chunk;
+    } else if (p.mode == 2) {
+        c = short_seq ? p.short_chunk : p.long_chunk;
+    } else if (p.mode == 1 && short_seq) {
+        c = p.short_chunk;
+    } else {
+        if (rv != rv) return 0;
+        double re = rv * p.h_ref_scale;
+        re = re < 0.0 ? 0.0 : (re > 1.0 ? 1.0 : re);
+        const double target = (double)p.c_min + re * (double)(p.c_max - p.c_min);
+        const double k = floor(log2(target) + 0.5);
+        c = (int64_t)1 << (int)k;
+        c = c < p.c_min ? p.c_min : (c > p.c_max ? p.c_max : c);
+        if (p.mode == 4) {
+            int away = (63 - __clzll((long long)c)) - (63 - __clzll((long long)p.safe_chunk));
+            away = away < 0 ? -away : away;
+            if (away < p.guard_buckets) c = p.safe_chunk;
+        }
+        int64_t cap = 1;
+        while (cap < L) cap <<= 1;
+        if (cap < p.c_min) cap = p.c_min;
+        if (c > cap) c = cap;
+    }
+    return (int32_t)c;
+}
+
+// With `chunks_out` the chunk rule is applied to r in the same kernel (routing without a further launch).
 __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* __restrict__ parts, uint32_t* counts, int K, double eps,
                                                                const RangeSlot* __restrict__ slots, double* H_out,
-                                                               double* r_out, float* range_out)
+                                                               double* r_out, float* range_out, int32_t* chunks_out,
+                                                               const int32_t* __restrict__ seqlens, int64_t L_all, corey_policy pol)
 {
     const int h = blockIdx.x;
     uint32_t* c = counts + (int64_t)h * K;
@@ -532,6 +568,7 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
         }
         H_out[h] = H;
         r_out[h] = r;
+        if (chunks_out) chunks_out[h] = chunk_rule(r, seqlens ? (int64_t)seqlens[h] : L_all, pol);
         if (range_out) {
             range_out[2 * h] = (slots[h].lo_key == 0xffffffffu) ? INFINITY : key_value(slots[h].lo_key);
             range_out[2 * h + 1] = (slots[h].hi_key == 0u) ? -INFINITY : key_value(slots[h].hi_key);
@@ -539,42 +576,13 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
     }
 }
 
-// Eq. 2 and the scheduler family around it, one thread per histogram (see corey_select_chunk for the rule).
+// One thread per histogram.
 __global__ void k_select_chunk(const double* __restrict__ r, const int32_t* __restrict__ seqlens, int64_t L_all, int nh,
                                corey_policy p, int32_t* __restrict__ chunks)
 {
     const int h = blockIdx.x * blockDim.x + threadIdx.x;
     if (h >= nh) return;
-    int64_t L = seqlens ? (int64_t)seqlens[h] : L_all;
-    if (L < 1) L = 1;
-    const bool short_seq = L <= p.short_len;
-    int64_t c;
-    if (p.mode == 3) {
-        c = p.static_chunk;
-    } else if (p.mode == 2) {
-        c = short_seq ? p.short_chunk : p.long_chunk;
-    } else if (p.mode == 1 && short_seq) {
-        c = p.short_chunk;
-    } else {
-        const double rv = r[h];
-        if (rv != rv) { chunks[h] = 0; return; }
-        double re = rv * p.h_ref_scale;
-        re = re < 0.0 ? 0.0 : (re > 1.0 ? 1.0 : re);
-        const double target = (double)p.c_min + re * (double)(p.c_max - p.c_min);
-        const double k = floor(log2(target) + 0.5);
-        c = (int64_t)1 << (int)k;
-        c = c < p.c_min ? p.c_min : (c > p.c_max ? p.c_max : c);
-        if (p.mode == 4) {
-            int away = (63 - __clzll((long long)c)) - (63 - __clzll((long long)p.safe_chunk));
-            away = away < 0 ? -away : away;
-            if (away < p.guard_buckets) c = p.safe_chunk;
-        }
-        int64_t cap = 1;
-        while (cap < L) cap <<= 1;
-        if (cap < p.c_min) cap = p.c_min;
-        if (c > cap) c = cap;
-    }
-    chunks[h] = (int32_t)c;
+    chunks[h] = chunk_rule(r[h], seqlens ? (int64_t)seqlens[h] : L_all, p);
 }
 
 size_t slots_bytes(int64_t nh)
@@ -600,7 +608,8 @@ void launch_flat(const word4* x, int64_t nwords, WordMap<SAMPLED> map, int32_t K
 
 template <typename T>
 int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K, double eps, int64_t stride,
-           int64_t block, uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream)
+           int64_t block, uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream,
+           const corey_policy* pol, int32_t* chunks_out)
 {
     const int nh = seqlens ? (int)B : 1;
     uint32_t* parts = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(slots) + slots_bytes(B));
@@ -639,7 +648,9 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         k_entropy_count<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride, block,
                                                                vector_ok ? 1 : 0, K, slots, parts);
     }
-    k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, slots, H_out, r_out, range_out);
+    corey_policy no_policy = {};
+    k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, slots, H_out, r_out, range_out,
+                                                                          pol ? chunks_out : nullptr, seqlens, L, pol ? *pol : no_policy);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "corey_entropy_hist launch");
     return COREY_OK;
@@ -672,30 +683,57 @@ extern "C" size_t corey_entropy_hist_workspace(int64_t B, int32_t K)
     return workspace_bytes(B, K);
 }
 
+namespace {
+
+int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K,
+                      double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
+                      void* workspace, size_t workspace_bytes_given, void* hip_stream, const corey_policy* pol, int32_t* chunks_out)
+{
+    using corey::fail;
+    if (!x || !counts_out || !H_out || !r_out) return fail(COREY_ENULL, "%s: x, counts_out, H_out and r_out are required", who);
+    if (dt != COREY_F32 && dt != COREY_BF16 && dt != COREY_F16) return fail(COREY_EINVAL, "%s: unknown dtype %d", who, (int)dt);
+    if (B < 1 || D < 1 || L < 1) return fail(COREY_ESHAPE, "%s: B, D, L must be >= 1", who);
+    if (B > 65535) return fail(COREY_ESHAPE, "%s: B = %lld exceeds 65535", who, (long long)B);
+    if ((double)B * (double)D * (double)L >= 9.0e18) return fail(COREY_ESHAPE, "%s: B*D*L overflows", who);
+    if ((double)B * (double)D * (double)L >= 4294967296.0 && stride == 1)
+        return fail(COREY_ESHAPE, "%s: more than 2^32-1 samples would overflow the 32-bit counts", who);
+    if (K < 2 || K > COREY_MAX_BINS) return fail(COREY_EINVAL, "%s: K = %d outside [2, %d]", who, K, COREY_MAX_BINS);
+    if (!(eps >= 0.0)) return fail(COREY_EINVAL, "%s: eps must be >= 0", who);
+    if (stride < 1 || block < 1) return fail(COREY_EINVAL, "%s: stride and block must be >= 1", who);
+    const size_t need = workspace_bytes(B, K);
+    if (!workspace || workspace_bytes_given < need) return fail(COREY_EWORKSPACE, "%s: workspace of %zu bytes required", who, need);
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "%s: workspace must be 16-byte aligned", who);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    RangeSlot* slots = static_cast<RangeSlot*>(workspace);
+    if (dt == COREY_F32)
+        return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out);
+    if (dt == COREY_F16)
+        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out);
+    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out);
+}
+
+}  // namespace
+
 extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
                                   int32_t K, double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out,
                                   double* r_out, float* range_out, void* workspace, size_t workspace_bytes_given, void* hip_stream)
 {
+    return entropy_hist_impl("corey_entropy_hist", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
+                             workspace, workspace_bytes_given, hip_stream, nullptr, nullptr);
+}
+
+extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
+                                  int32_t K, double eps, int64_t stride, int64_t block, const corey_policy* p,
+                                  uint32_t* counts_out, double* H_out, double* r_out, float* range_out, int32_t* chunks_out,
+                                  void* workspace, size_t workspace_bytes_given, void* hip_stream)
+{
     using corey::fail;
-    if (!x || !counts_out || !H_out || !r_out) return fail(COREY_ENULL, "corey_entropy_hist: x, counts_out, H_out and r_out are required");
-    if (dt != COREY_F32 && dt != COREY_BF16 && dt != COREY_F16) return fail(COREY_EINVAL, "corey_entropy_hist: unknown dtype %d", (int)dt);
-    if (B < 1 || D < 1 || L < 1) return fail(COREY_ESHAPE, "corey_entropy_hist: B, D, L must be >= 1");
-    if (B > 65535) return fail(COREY_ESHAPE, "corey_entropy_hist: B = %lld exceeds 65535", (long long)B);
-    if ((double)B * (double)D * (double)L >= 9.0e18) return fail(COREY_ESHAPE, "corey_entropy_hist: B*D*L overflows");
-    if ((double)B * (double)D * (double)L >= 4294967296.0 && stride == 1)
-        return fail(COREY_ESHAPE, "corey_entropy_hist: more than 2^32-1 samples would overflow the 32-bit counts");
-    if (K < 2 || K > COREY_MAX_BINS) return fail(COREY_EINVAL, "corey_entropy_hist: K = %d outside [2, %d]", K, COREY_MAX_BINS);
-    if (!(eps >= 0.0)) return fail(COREY_EINVAL, "corey_entropy_hist: eps must be >= 0");
-    if (stride < 1 || block < 1) return fail(COREY_EINVAL, "corey_entropy_hist: stride and block must be >= 1");
-    const size_t need = workspace_bytes(B, K);
-    if (!workspace || workspace_bytes_given < need)
-        return fail(COREY_EWORKSPACE, "corey_entropy_hist: workspace of %zu bytes required", need);
-    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "corey_entropy_hist: workspace must be 16-byte aligned");
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    RangeSlot* slots = static_cast<RangeSlot*>(workspace);
-    if (dt == COREY_F32)
-        return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream);
-    if (dt == COREY_F16)
-        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream);
-    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream);
+    if (!p || !chunks_out) return fail(COREY_ENULL, "corey_route_device: p and chunks_out are required");
+    // validate the policy on the host with the host rule (r = 0.5 is a placeholder that no mode rejects)
+    int32_t probe = 0;
+    const int st = corey_select_chunk(0.5, L < 1 ? 1 : L, p, &probe);
+    if (st != COREY_OK) return st;
+    if (p->mode == 1 && !corey::is_pow2(p->short_chunk)) return fail(COREY_EINVAL, "corey_route_device: short_chunk = %d", p->short_chunk);
+    return entropy_hist_impl("corey_route_device", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
+                             workspace, workspace_bytes_given, hip_stream, p, chunks_out);
 }

@@ -170,6 +170,29 @@ def test_routed_scan_without_host_round_trip():
         assert np.array_equal(yb[b], y[b])
 
 
+def test_route_device_equals_the_two_calls():
+    """corey_route_device = corey_entropy_hist then corey_select_chunk_device, bit for bit, for every mode."""
+    cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], D=32, L=2048, B=3, seqlens=(2048, 40, 700))
+    w = wl.make(cfg)
+    d = upload(w)
+    _say("route_device")
+    for seqlens in (d["seqlens"], None):
+        for mode in (0, 1, 2, 3, 4):
+            for stride, block in ((1, 1), (8, 512)):
+                pol = corey.policy_default()
+                pol.mode = mode
+                ent = corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, stride=stride, block=block)
+                two = corey.corey_select_chunk_device(ent["r"], cfg.L, pol, seqlens=seqlens)
+                one = corey.corey_route_device(d["u"], cfg.K, pol, seqlens=seqlens, stride=stride, block=block)
+                torch.cuda.synchronize()
+                assert torch.equal(one["chunks"], two) and torch.equal(one["counts"], ent["counts"])
+                assert torch.equal(one["r"], ent["r"]) and torch.equal(one["H"], ent["H"])
+    bad = corey.policy_default()
+    bad.c_min = 48
+    with pytest.raises(corey.CoreyError):
+        corey.corey_route_device(d["u"], cfg.K, bad)
+
+
 def test_invariants_on_the_gpu_path():
     cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=32, L=1024)
     w = wl.make(cfg, a_kind="random")
