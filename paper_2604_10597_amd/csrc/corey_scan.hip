@@ -1,6 +1,7 @@
 // selective_scan_fwd: host entry.  Validates the arguments, lays out the launch and hands over to the kernels of
 // the storage type (corey_scan_impl.h, instantiated per type in corey_scan_f32/bf16/f16.hip).
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <cstdlib>
 
 #include "corey_scan_impl.h"
@@ -13,7 +14,13 @@ void launch_scan_f16(const ScanArgs& a, const LaunchPlan& p);
 
 namespace {
 int64_t padded_len(int64_t L) { return (L + corey_scan::kPad + 3) / 4 * 4; }
+std::atomic<int> g_structured{1};
 }  // namespace
+
+extern "C" int corey_scan_structured_path(int enable)
+{
+    return g_structured.exchange(enable ? 1 : 0);
+}
 
 extern "C" size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L)
 {
@@ -59,6 +66,7 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.ws_C = a.ws_B + (size_t)B * a.Np * a.Lpad;
     a.L = L; a.rows_total = B * D; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
+    a.allow_structured = g_structured.load();
     // LDS budget for the per-row arrays (carried state and A): at most 32 rows and 8 KiB each, so that the staging
     // buffers and the rows of a workgroup stay below what a compute unit gives four workgroups (chunks below 64,
     // which would put more than 32 rows into a workgroup, run with idle lanes).

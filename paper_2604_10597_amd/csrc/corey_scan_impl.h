@@ -52,7 +52,10 @@ constexpr int kWaves = kBlock / 64;
 #define COREY_WAVES_K16 4             // waves per SIMD the register allocation of the 16-step kernels leaves room for
 #endif
 #ifndef COREY_WAVES_K8
-#define COREY_WAVES_K8 5
+#define COREY_WAVES_K8 4              // the same for 8 steps per lane (the spare registers hold the tile fetched ahead)
+#endif
+#ifndef COREY_CPREFETCH_MAXK
+#define COREY_CPREFETCH_MAXK 8        // geometries with at most this many steps per lane fetch C before the lane scan
 #endif
 constexpr int kMaxGroup = 4;          // most states staged (and unrolled) per group
 constexpr int kPad = COREY_MAX_CHUNK; // the relaid-out time axis is padded to whole tiles
@@ -330,6 +333,7 @@ struct ScanArgs {
     int32_t chunk;          // host chunk (also the fallback for invalid device entries)
     int32_t rows_cap;       // most rows a workgroup may hold (LDS budget for the carried state)
     int32_t softplus;
+    int32_t allow_structured;   // take the power-chain path when A[d, n] = (n + 1) A[d, 0] (16-bit storage only)
     int32_t vector_ok;      // rows of the [.., L] tensors are 16-byte aligned
 };
 
@@ -424,7 +428,12 @@ __host__ __device__ constexpr int lds_floats(int rows, int N)
 
 // ------------------------------------------------------------------------------------------- the scan
 // The rows d0 .. d0 + rows - 1 of sequence blockIdx.y, start to end.
-template <typename T, int K, int CHUNK>
+//
+// STRUCT: every row of the group has A[d, n] = (n + 1) A[d, 0] (the S4D-real initialisation Mamba starts from, and
+// the benchmark's A = -(n + 1)).  Then exp(dl A[d, n]) = exp(dl A[d, 0])^(n + 1): one exponential per time step
+// instead of one per (time step, state), the decay of state n following from that of state n - 1 by one multiply
+// (likewise the sub-block product P).  The chain adds at most n roundings (about (n + 1) 2^-24 relative) to a decay.
+template <typename T, int K, int CHUNK, bool STRUCT>
 __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, const int rows, const int d0)
 {
     using Gm = Geo<K, CHUNK>;
@@ -485,6 +494,11 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     int buf = 0;                                            // staging buffer holding the group about to be used
     if (len > 0) stage_async<STAGE>(wsB, wsC, s_stage, s_stage + STAGE, wave, lane);
 
+    // Geometries with 8 steps per lane have the registers to fetch the next tile's u / delta / z while the last
+    // group of states of the current tile is computed, which takes the HBM latency out of every tile's start.
+    constexpr bool kTileAhead = K == 8;
+    Raw<T, K> u_nx, d_nx, z_nx;
+    bool have_nx = false;                                   // uniform over the workgroup
     const int64_t ntiles = (len + CHUNK - 1) / CHUNK;
     for (int64_t tau = 0; tau < ntiles; ++tau) {
         const int64_t tile = tau * CHUNK;
@@ -502,13 +516,18 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
         }
         float dl[K], du[K], yv[K];
         Raw<T, K> z_raw;                                    // the gate is fetched with the tile and used after the last state
-        {
+        if (kTileAhead && have_nx) {                        // a full tile fetched one tile ago
+            z_raw = z_nx;
+            widen<T, K>(d_nx, dl);
+            widen<T, K>(u_nx, du);
+        } else {
             const Raw<T, K> u_raw = load_raw<T, K>(u_row + t0, nvalid, vec);
             const Raw<T, K> d_raw = load_raw<T, K>(dl_row + t0, nvalid, vec);
             if (z_row) z_raw = load_raw<T, K>(z_row + t0, nvalid, vec);
             widen<T, K>(d_raw, dl);
             widen<T, K>(u_raw, du);
         }
+        have_nx = false;
         float S = 0.f;
         if (sp) {
 #pragma unroll
@@ -527,6 +546,16 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
             du[i] = dl[i] * du[i];
             S += dl[i];
         }
+        float av_chain[K], P_chain = 1.f, P_base = 1.f;      // STRUCT: decay of the current state, built up state by state
+        if constexpr (STRUCT) {
+            const float A20 = A2_row[0];
+#pragma unroll
+            for (int i = 0; i < K; ++i) {
+                dl[i] = fast_exp2(dl[i] * A20);             // from here on dl holds the decay of state 0
+                av_chain[i] = 1.f;
+            }
+            P_base = fast_exp2(S * A20);
+        }
 
         for (int n0 = 0; n0 < N; n0 += G) {
             const float* s_B = s_stage + buf * 2 * STAGE;
@@ -543,31 +572,65 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                     float* d_B = s_stage + (buf ^ 1) * 2 * STAGE;
                     stage_async<STAGE>(wsB + off, wsC + off, d_B, d_B + STAGE, wave, lane);
                 }
+                if constexpr (kTileAhead) {                 // last group of this tile: fetch the next tile if it is a full one
+                    if (nn0 == 0 && vec && tile + 2 * CHUNK <= len) {
+                        const int64_t t1 = t0 + CHUNK;
+                        u_nx = load_raw<T, K>(u_row + t1, K, true);
+                        d_nx = load_raw<T, K>(dl_row + t1, K, true);
+                        if (z_row) z_nx = load_raw<T, K>(z_row + t1, K, true);
+                        have_nx = true;
+                    }
+                }
             }
             buf ^= 1;
             const float4v* bq0 = reinterpret_cast<const float4v*>(s_B) + j;
             const float4v* cq0 = reinterpret_cast<const float4v*>(s_C) + j;
+            constexpr bool kEarlyC = K <= COREY_CPREFETCH_MAXK;   // C is requested before the lane scan, which covers the LDS latency
             auto one_state = [&](const int nl, const int n) __attribute__((always_inline)) {
-                const float A2 = A2_row[n];
                 const float cin = carry_rd[n];              // carried state for the first lane of the row, 0 elsewhere
                 const float4v* bq = bq0 + nl * KQ * LPR;
                 const float4v* cq = cq0 + nl * KQ * LPR;
+                float A2 = 0.f;
+                if constexpr (!STRUCT) A2 = A2_row[n];
 
-                float av[K], bv[K];
-                float h = 0.f;
+                float av_local[K], bv[K];
+                float (&av)[K] = STRUCT ? av_chain : av_local;
+                float h = 0.f, P;
+                if constexpr (STRUCT) {
 #pragma unroll
-                for (int q = 0; q < KQ; ++q) {
-                    const float4v b4 = bq[q * LPR];
-                    const float be[4] = {b4.x, b4.y, b4.z, b4.w};
+                    for (int q = 0; q < KQ; ++q) {
+                        const float4v b4 = bq[q * LPR];
+                        const float be[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int i = 4 * q + e;
-                        av[i] = fast_exp2(dl[i] * A2);
-                        bv[i] = du[i] * be[e];
-                        h = fmaf(av[i], h, bv[i]);
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = 4 * q + e;
+                            av[i] *= dl[i];                 // decay of state n from that of state n - 1
+                            bv[i] = du[i] * be[e];
+                            h = fmaf(av[i], h, bv[i]);
+                        }
                     }
+                    P_chain *= P_base;
+                    P = P_chain;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < KQ; ++q) {
+                        const float4v b4 = bq[q * LPR];
+                        const float be[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = 4 * q + e;
+                            av[i] = fast_exp2(dl[i] * A2);
+                            bv[i] = du[i] * be[e];
+                            h = fmaf(av[i], h, bv[i]);
+                        }
+                    }
+                    P = fast_exp2(S * A2);
                 }
-                float P = fast_exp2(S * A2);
+                float4v cv[KQ];
+                if constexpr (kEarlyC) {
+#pragma unroll
+                    for (int q = 0; q < KQ; ++q) cv[q] = cq[q * LPR];
+                }
                 h = fmaf(P, cin, h);                        // the row's first lane starts from the carried state
                 scan_inclusive<SEG, (WPR > 1)>(jseg, P, h); // h: state at the end of this lane's sub-block (within the wave)
                 float first = cin;                          // state entering the first lane of this wave's part of the row
@@ -590,7 +653,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 }
 #pragma unroll
                 for (int q = 0; q < KQ; ++q) {
-                    const float4v c4 = cq[q * LPR];
+                    const float4v c4 = kEarlyC ? cv[q] : cq[q * LPR];
                     const float ce[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -655,7 +718,20 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
 {
     const int rows = Geo<K, CHUNK>::ROWS < a.rows_cap ? Geo<K, CHUNK>::ROWS : a.rows_cap;
     for (int64_t d0 = (int64_t)blockIdx.x * rows; d0 < a.D; d0 += (int64_t)gridDim.x * rows) {   // uniform over the workgroup
-        scan_group<T, K, CHUNK>(a, s_mem, rows, (int)d0);
+        bool structured = false;
+        if constexpr (sizeof(T) == 2) {                      // fp32 storage keeps the one-exponential-per-state path
+            if (a.allow_structured) {
+                int ok = 1;
+                for (int i = threadIdx.x; i < rows * a.N; i += kBlock) {
+                    const int r = i / a.N, n = i - r * a.N;
+                    const int64_t dd = d0 + r;
+                    if (dd < a.D) ok &= a.A[dd * a.N + n] == (float)(n + 1) * a.A[dd * a.N];
+                }
+                structured = __syncthreads_and(ok) != 0;
+            }
+        }
+        if (structured) scan_group<T, K, CHUNK, true>(a, s_mem, rows, (int)d0);
+        else scan_group<T, K, CHUNK, false>(a, s_mem, rows, (int)d0);
         __syncthreads();                                     // the LDS arrays are set up afresh for the next group
     }
 }

@@ -193,6 +193,47 @@ def test_route_device_equals_the_two_calls():
         corey.corey_route_device(d["u"], cfg.K, bad)
 
 
+def test_structured_A_fast_path():
+    """A[d, n] = (n + 1) A[d, 0] with 16-bit storage takes the power-chain path: it must meet the same bounds as the
+    general path, differ from it only by the chain's roundings, and leave every other A untouched."""
+    try:
+        for name, dtype in (("c2_mamba370m", wl.BF16), ("paper_w1_fp16", wl.F16)):
+            cfg = wl.scaled(wl.CONFIGS[name], D=40, L=1300, dtype=dtype)
+            w = wl.make(cfg, a_kind="mamba", with_h0=True)
+            d = upload(w)
+            y_ref, s_ref = oracle_scan(w)
+            for chunk in (64, 512, 1024, 2048):
+                _say(f"scan structured A {name} {dtype} chunk={chunk}")
+                corey.corey_scan_structured_path(True)
+                y1, s1 = _run(d, chunk)
+                assert corey.corey_scan_structured_path(False) is True
+                y0, s0 = _run(d, chunk)
+                for y, s in ((y1, s1), (y0, s0)):
+                    assert_close(y, y_ref, y_rtol(cfg), f"y chunk {chunk}", store_bits(cfg))
+                    assert_close(s, s_ref, fp32_rtol(cfg.L), f"state chunk {chunk}")
+                assert not np.array_equal(s1, s0)             # the two paths really are different code
+                assert_close(s1, s0, 2e-6, "structured against general state")
+            # an unstructured A, and a structured one whose first channel is off by one ulp, take the general path
+            wr = wl.make(cfg, a_kind="random")
+            dr = upload(wr)
+            corey.corey_scan_structured_path(True)
+            ya, sa = _run(dr, 512)
+            corey.corey_scan_structured_path(False)
+            yb, sb = _run(dr, 512)
+            assert np.array_equal(ya, yb) and np.array_equal(sa, sb)
+        # fp32 storage never takes it
+        cfg = wl.scaled(wl.CONFIGS["c0_tiny_f32"], D=16, L=512)
+        w = wl.make(cfg)
+        d = upload(w)
+        corey.corey_scan_structured_path(True)
+        ya, sa = _run(d, 256)
+        corey.corey_scan_structured_path(False)
+        yb, sb = _run(d, 256)
+        assert np.array_equal(ya, yb) and np.array_equal(sa, sb)
+    finally:
+        corey.corey_scan_structured_path(True)
+
+
 def test_invariants_on_the_gpu_path():
     cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], D=32, L=1024)
     w = wl.make(cfg, a_kind="random")
