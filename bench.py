@@ -34,7 +34,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
 # HBM bytes per scan launch measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`, scaled by what the same counters
 # read for a 256 MiB device copy (profiles/hot_path_c4_mamba2p8b_counters.txt); not re-measured by this script
-MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 713_100_000}
+MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 787_300_000}
 
 
 def main() -> int:
@@ -294,7 +294,7 @@ def main() -> int:
                    "scan_bytes": scan_bytes, "tokens": tokens},
         "tokens_per_s": round(tokens / ms_step * 1e3, 1),
         "routed_chunk": chunk, "r": [round(float(v), 6) for v in r_pinned],
-        "roofline": {"bound": "hbm", "kernel": "k_selective_scan", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "k_scan_any (selective_scan_fwd, device-routed chunk; the launch also holds k_relayout_bc, ~5 us)", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": round(scan_ms, 4)},
         "alu": {"achieved": round(scan_flop / scan_ms * 1e-9, 2), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
