@@ -57,6 +57,7 @@ typedef enum {
 #define COREY_MAX_STATE 256      /* N (d_state)            */
 #define COREY_MIN_CHUNK 16
 #define COREY_MAX_CHUNK 2048
+#define COREY_CHUNK_SLOTS 12     /* chunk-distribution counters: slot log2(chunk), chunk = 1 .. 2048 */
 
 /* -------------------------------------------------------------------------------------------------------
  * corey_entropy_hist -- Eq. 1 and r = H / log K.
@@ -147,15 +148,32 @@ int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64
                               const corey_policy* p, int32_t* chunks_out, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------
+ * corey_ema_update -- the exponential moving average of the entropy estimate across calls ("Entropy Estimation
+ * Protocol"):  H^_t = lambda * H^_{t-1} + (1 - lambda) * H_t,  0 <= lambda < 1  (the paper's prototype: 0.85, an
+ * effective horizon of about 1 / (1 - lambda) = 6.7 calls).  Host function on a HOST state: *state = NaN means "no
+ * estimate yet" and the first observation is taken as it is (the paper does not state the initial value); a NaN
+ * observation leaves the state unchanged.  Errors: COREY_ENULL, COREY_EINVAL for lambda outside [0, 1).
+ * ----------------------------------------------------------------------------------------------------- */
+int corey_ema_update(double lambda, double* state, double H);
+
+/* -------------------------------------------------------------------------------------------------------
  * corey_route_device -- corey_entropy_hist followed by corey_select_chunk_device in one call: the statistic of x,
  * then the chunk rule applied to each r by the kernel that reduces the histogram (one launch fewer on the routed
  * path; the paper counts scheduler dispatch among the costs of routing).  Arguments as for those two calls; the
- * sequence length each decision is taken for is seqlens[h] when seqlens is given, else L.  Results are identical to
- * calling the two one after the other.  Errors: as for both.
+ * sequence length each decision is taken for is seqlens[h] when seqlens is given, else L.  Without the two optional
+ * arguments below the results are identical to calling the two one after the other.
+ *   ema_lambda, ema_state   ema_state: DEVICE double[nh] or NULL.  With a state, the rule is applied to the smoothed
+ *               entropy: ema_state[h] is updated as in corey_ema_update (NaN = no estimate yet) and r for the rule
+ *               is clamp(ema_state[h] / log K, 0, 1); H_out and r_out still hold the raw values of this call.
+ *   chunk_calls DEVICE uint32[COREY_CHUNK_SLOTS] or NULL: chunk-distribution counters (the paper logs, per run, how
+ *               many scheduler calls chose each chunk); slot log2(chunk) is incremented for every decision taken
+ *               (not for NaN decisions).  The caller clears them.
+ * Errors: as for both calls; COREY_EINVAL for ema_lambda outside [0, 1) when ema_state is given.
  * ----------------------------------------------------------------------------------------------------- */
 int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
                        const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
-                       const corey_policy* p, uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
+                       const corey_policy* p, double ema_lambda, double* ema_state, uint32_t* chunk_calls,
+                       uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
                        int32_t* chunks_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------

@@ -95,6 +95,13 @@ def entropy_hist(x, K, eps=1e-8, stride=1, seqlens=None, block=1):
     return dict(status=st, counts=counts, H=H, r=r, lo=lo, hi=hi)
 
 
+def ema_update(lam, prev, H):
+    """One step of the entropy EMA; prev = NaN means no estimate yet."""
+    f = lib().oracle_ema_update
+    f.restype = ctypes.c_double
+    return f(ctypes.c_double(lam), ctypes.c_double(prev), ctypes.c_double(H))
+
+
 def select_chunk(r, L, pol: Policy | None = None):
     """Returns (status, chunk, margin)."""
     pol = pol or policy()

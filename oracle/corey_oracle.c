@@ -160,6 +160,20 @@ int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const i
 }
 
 /* ------------------------------------------------------------------------------------------------
+ * Exponential moving average of the entropy estimate across calls ("Entropy Estimation Protocol"):
+ *     H^_t = lambda * H^_{t-1} + (1 - lambda) * H_t,   0 <= lambda < 1   (the paper's prototype uses 0.85).
+ * The paper does not say what H^_0 is (it only notes that short runs stay dominated by the initialisation): here a
+ * NaN `prev` means "no estimate yet" and the first observation is taken as it is.  A NaN observation (non-finite
+ * input) leaves the estimate unchanged.
+ * ---------------------------------------------------------------------------------------------- */
+double oracle_ema_update(double lambda, double prev, double H)
+{
+    if (H != H) return prev;
+    if (prev != prev) return H;
+    return lambda * prev + (1.0 - lambda) * H;
+}
+
+/* ------------------------------------------------------------------------------------------------
  * Eq. 2 and the scheduler family around it.
  *
  * mode 0  entropy rule (Eq. 2).

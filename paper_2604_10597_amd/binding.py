@@ -18,7 +18,7 @@ COREY_F32, COREY_BF16, COREY_F16 = 0, 1, 2
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
-           "corey_select_chunk_device", "corey_route_device",
+           "corey_select_chunk_device", "corey_route_device", "corey_ema_update",
            "selective_scan_fwd", "selective_scan_fwd_workspace", "corey_scan_structured_path", "corey_last_error", "corey_version")
 
 
@@ -51,8 +51,10 @@ def lib() -> ctypes.CDLL:
         L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp,
                                          ctypes.c_size_t, vp]
         L.corey_route_device.restype = ctypes.c_int
-        L.corey_route_device.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, ctypes.POINTER(Policy), vp, vp, vp,
-                                         vp, vp, vp, ctypes.c_size_t, vp]
+        L.corey_route_device.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, ctypes.POINTER(Policy), dbl, vp, vp,
+                                         vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.corey_ema_update.restype = ctypes.c_int
+        L.corey_ema_update.argtypes = [dbl, ctypes.POINTER(dbl), dbl]
         L.corey_entropy_hist_workspace.restype = ctypes.c_size_t
         L.corey_entropy_hist_workspace.argtypes = [i64, i32]
         L.corey_policy_default.restype = ctypes.c_int
@@ -140,10 +142,21 @@ def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int =
     return out
 
 
+def corey_ema_update(lam: float, state: float, H: float) -> float:
+    """One step of the entropy EMA on the host; state = NaN means no estimate yet.  Returns the new state."""
+    st = ctypes.c_double(state)
+    _check(lib().corey_ema_update(float(lam), ctypes.byref(st), float(H)))
+    return st.value
+
+
 def corey_route_device(x: torch.Tensor, K: int, policy: Policy | None = None, eps: float = 1e-8, stride: int = 1, block: int = 1,
-                       seqlens: torch.Tensor | None = None, out: dict | None = None, workspace: torch.Tensor | None = None):
+                       seqlens: torch.Tensor | None = None, out: dict | None = None, workspace: torch.Tensor | None = None,
+                       ema_lambda: float = 0.0, ema_state: torch.Tensor | None = None, chunk_calls: torch.Tensor | None = None):
     """corey_entropy_hist and the chunk rule in one call.  Returns the dict of corey_entropy_hist plus `chunks`
-    (int32 GPU tensor [nh], directly usable as `chunks_dev` of selective_scan_fwd); no synchronisation."""
+    (int32 GPU tensor [nh], directly usable as `chunks_dev` of selective_scan_fwd); no synchronisation.
+    ema_state: float64 GPU tensor [nh] (NaN = no estimate yet), updated in place; chunk_calls: int32 GPU tensor
+    [COREY_CHUNK_SLOTS] of counters the caller clears."""
+    _dev(ema_state, "ema_state"), _dev(chunk_calls, "chunk_calls")
     _dev(x, "x"), _dev(seqlens, "seqlens")
     if x.dim() != 3:
         raise ValueError("x must be [B, D, L]")
@@ -161,7 +174,7 @@ def corey_route_device(x: torch.Tensor, K: int, policy: Policy | None = None, ep
     if workspace is None:
         workspace = torch.empty(max(corey_entropy_hist_workspace(B, K), 256), dtype=torch.uint8, device=x.device)
     _check(lib().corey_route_device(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride, block, ctypes.byref(p),
-                                    _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
+                                    float(ema_lambda), _ptr(ema_state), _ptr(chunk_calls), _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
                                     _ptr(out["chunks"]), _ptr(workspace), workspace.numel(), _stream()))
     out["workspace"] = workspace
     return out

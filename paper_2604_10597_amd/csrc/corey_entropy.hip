@@ -522,7 +522,8 @@ __device__ __forceinline__ int32_t chunk_rule(double rv, int64_t L, const corey_
 __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* __restrict__ parts, uint32_t* counts, int K, double eps,
                                                                const RangeSlot* __restrict__ slots, double* H_out,
                                                                double* r_out, float* range_out, int32_t* chunks_out,
-                                                               const int32_t* __restrict__ seqlens, int64_t L_all, corey_policy pol)
+                                                               const int32_t* __restrict__ seqlens, int64_t L_all, corey_policy pol,
+                                                               double ema_lambda, double* ema_state, uint32_t* chunk_calls)
 {
     const int h = blockIdx.x;
     uint32_t* c = counts + (int64_t)h * K;
@@ -568,7 +569,20 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
         }
         H_out[h] = H;
         r_out[h] = r;
-        if (chunks_out) chunks_out[h] = chunk_rule(r, seqlens ? (int64_t)seqlens[h] : L_all, pol);
+        if (chunks_out) {
+            double r_rule = r;
+            if (ema_state) {                                   // the rule sees the entropy smoothed across calls
+                const double prev = ema_state[h];
+                double Hs = prev;
+                if (H == H) Hs = (prev != prev) ? H : ema_lambda * prev + (1.0 - ema_lambda) * H;
+                ema_state[h] = Hs;
+                r_rule = Hs / log((double)K);
+                r_rule = r_rule < 0.0 ? 0.0 : (r_rule > 1.0 ? 1.0 : r_rule);
+            }
+            const int32_t c = chunk_rule(r_rule, seqlens ? (int64_t)seqlens[h] : L_all, pol);
+            chunks_out[h] = c;
+            if (chunk_calls && c > 0) atomicAdd(&chunk_calls[31 - __clz(c)], 1u);
+        }
         if (range_out) {
             range_out[2 * h] = (slots[h].lo_key == 0xffffffffu) ? INFINITY : key_value(slots[h].lo_key);
             range_out[2 * h + 1] = (slots[h].hi_key == 0u) ? -INFINITY : key_value(slots[h].hi_key);
@@ -609,7 +623,7 @@ void launch_flat(const word4* x, int64_t nwords, WordMap<SAMPLED> map, int32_t K
 template <typename T>
 int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K, double eps, int64_t stride,
            int64_t block, uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream,
-           const corey_policy* pol, int32_t* chunks_out)
+           const corey_policy* pol, int32_t* chunks_out, double ema_lambda, double* ema_state, uint32_t* chunk_calls)
 {
     const int nh = seqlens ? (int)B : 1;
     uint32_t* parts = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(slots) + slots_bytes(B));
@@ -650,7 +664,8 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
     }
     corey_policy no_policy = {};
     k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, slots, H_out, r_out, range_out,
-                                                                          pol ? chunks_out : nullptr, seqlens, L, pol ? *pol : no_policy);
+                                                                          pol ? chunks_out : nullptr, seqlens, L, pol ? *pol : no_policy,
+                                                                          ema_lambda, ema_state, chunk_calls);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "corey_entropy_hist launch");
     return COREY_OK;
@@ -687,7 +702,8 @@ namespace {
 
 int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K,
                       double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
-                      void* workspace, size_t workspace_bytes_given, void* hip_stream, const corey_policy* pol, int32_t* chunks_out)
+                      void* workspace, size_t workspace_bytes_given, void* hip_stream, const corey_policy* pol, int32_t* chunks_out,
+                      double ema_lambda = 0.0, double* ema_state = nullptr, uint32_t* chunk_calls = nullptr)
 {
     using corey::fail;
     if (!x || !counts_out || !H_out || !r_out) return fail(COREY_ENULL, "%s: x, counts_out, H_out and r_out are required", who);
@@ -706,10 +722,13 @@ int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B,
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     RangeSlot* slots = static_cast<RangeSlot*>(workspace);
     if (dt == COREY_F32)
-        return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out);
+        return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
+                             ema_state, chunk_calls);
     if (dt == COREY_F16)
-        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out);
-    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out);
+        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
+                             ema_state, chunk_calls);
+    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
+                             ema_state, chunk_calls);
 }
 
 }  // namespace
@@ -724,16 +743,19 @@ extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int6
 
 extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
                                   int32_t K, double eps, int64_t stride, int64_t block, const corey_policy* p,
+                                  double ema_lambda, double* ema_state, uint32_t* chunk_calls,
                                   uint32_t* counts_out, double* H_out, double* r_out, float* range_out, int32_t* chunks_out,
                                   void* workspace, size_t workspace_bytes_given, void* hip_stream)
 {
     using corey::fail;
     if (!p || !chunks_out) return fail(COREY_ENULL, "corey_route_device: p and chunks_out are required");
+    if (ema_state && !(ema_lambda >= 0.0 && ema_lambda < 1.0))
+        return fail(COREY_EINVAL, "corey_route_device: ema_lambda = %g outside [0, 1)", ema_lambda);
     // validate the policy on the host with the host rule (r = 0.5 is a placeholder that no mode rejects)
     int32_t probe = 0;
     const int st = corey_select_chunk(0.5, L < 1 ? 1 : L, p, &probe);
     if (st != COREY_OK) return st;
     if (p->mode == 1 && !corey::is_pow2(p->short_chunk)) return fail(COREY_EINVAL, "corey_route_device: short_chunk = %d", p->short_chunk);
     return entropy_hist_impl("corey_route_device", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
-                             workspace, workspace_bytes_given, hip_stream, p, chunks_out);
+                             workspace, workspace_bytes_given, hip_stream, p, chunks_out, ema_lambda, ema_state, chunk_calls);
 }

@@ -45,6 +45,15 @@ extern "C" int corey_policy_default(corey_policy* p)
     return COREY_OK;
 }
 
+extern "C" int corey_ema_update(double lambda, double* state, double H)
+{
+    if (!state) return fail(COREY_ENULL, "corey_ema_update: state is NULL");
+    if (!(lambda >= 0.0 && lambda < 1.0)) return fail(COREY_EINVAL, "corey_ema_update: lambda = %g outside [0, 1)", lambda);
+    if (std::isnan(H)) return COREY_OK;
+    *state = std::isnan(*state) ? H : lambda * *state + (1.0 - lambda) * H;
+    return COREY_OK;
+}
+
 namespace {
 
 int log2_of_pow2(int64_t v)

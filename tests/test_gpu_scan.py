@@ -193,6 +193,42 @@ def test_route_device_equals_the_two_calls():
         corey.corey_route_device(d["u"], cfg.K, bad)
 
 
+def test_route_device_with_ema_and_chunk_counters():
+    """The smoothed entropy across calls and the chunk-distribution counters, against the oracle's EMA and rule."""
+    import math
+    import oracle
+    K = 256
+    rng = np.random.default_rng(11)
+    pol, opol = corey.policy_default(), oracle.policy()
+    ema = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+    calls = torch.zeros(12, dtype=torch.int32, device="cuda")
+    s_ref = float("nan")
+    expect_calls = np.zeros(12, dtype=np.int64)
+    _say("route_device EMA")
+    for it, scale in enumerate((1.0, 1.0, 30.0, 1.0, 0.2, 1.0, 8.0, 1.0)):
+        x = rng.standard_normal((1, 8, 2048)).astype(np.float32)
+        x[0, 0, :16] *= scale                                  # a few outliers stretch the range: entropy moves call to call
+        store, val = wl.store(x, wl.BF16)
+        out = corey.corey_route_device(upload_one(store), K, pol, ema_lambda=0.85, ema_state=ema, chunk_calls=calls)
+        torch.cuda.synchronize()
+        ref = oracle.entropy_hist(val, K)
+        s_ref = oracle.ema_update(0.85, s_ref, float(ref["H"][0]))
+        assert out["H"].item() == pytest.approx(ref["H"][0], rel=1e-12)          # raw value of this call
+        assert ema.item() == pytest.approx(s_ref, rel=1e-12)
+        r_s = min(max(s_ref / math.log(K), 0.0), 1.0)
+        st, c, margin = oracle.select_chunk(r_s, 2048, opol)
+        assert margin > 1e-9 and out["chunks"].item() == c
+        expect_calls[int(math.log2(c))] += 1
+    assert np.array_equal(calls.cpu().numpy(), expect_calls) and expect_calls.sum() == 8
+    with pytest.raises(corey.CoreyError):
+        corey.corey_route_device(upload_one(store), K, pol, ema_lambda=1.0, ema_state=ema)
+
+
+def upload_one(store):
+    from gpu_util import to_dev
+    return to_dev(store, wl.BF16)
+
+
 def test_structured_A_fast_path():
     """A[d, n] = (n + 1) A[d, 0] with 16-bit storage takes the power-chain path: it must meet the same bounds as the
     general path, differ from it only by the chain's roundings, and leave every other A untouched."""

@@ -86,3 +86,48 @@ def test_cap_by_length_static_and_errors():
     assert oracle.select_chunk(0.5, 0, pol)[0] == oracle.EINVAL
     assert oracle.select_chunk(0.5, 64, oracle.policy(c_min=48))[0] == oracle.EINVAL
     assert oracle.select_chunk(0.5, 64, oracle.policy(mode=9))[0] == oracle.EINVAL
+
+
+# ------------------------------------------------------------------------------------------------ EMA of the entropy
+def test_ema_closed_forms():
+    """H^_t = lambda H^_{t-1} + (1 - lambda) H_t ("Entropy Estimation Protocol").  Pins: a hand-computed three-step run,
+    the fixed point of a constant input, the geometric step response H (1 - lambda^t) + lambda^t H^_0, and the
+    horizon the paper quotes for lambda = 0.85 (about 1 / (1 - lambda) = 6.7 calls; "stable after 6-8 observations")."""
+    nan = float("nan")
+    lam = 0.85
+    # by hand: start 2.0 (first observation taken as is), then 4.0 -> 0.85*2 + 0.15*4 = 2.3, then 1.0 -> 0.85*2.3 + 0.15 = 2.105
+    s = oracle.ema_update(lam, nan, 2.0)
+    assert s == 2.0
+    s = oracle.ema_update(lam, s, 4.0)
+    assert abs(s - 2.3) < 1e-15
+    s = oracle.ema_update(lam, s, 1.0)
+    assert abs(s - 2.105) < 1e-15
+    # constant input is a fixed point
+    s = 3.25
+    for _ in range(50):
+        s = oracle.ema_update(lam, s, 3.25)
+    assert s == 3.25
+    # step response from H^_0 = 1 towards H = 5: closed form
+    s, h0, H = 1.0, 1.0, 5.0
+    for t in range(1, 40):
+        s = oracle.ema_update(lam, s, H)
+        assert abs(s - (H * (1 - lam ** t) + lam ** t * h0)) < 1e-12
+    # the paper's horizon: after 7 observations about a third of the initial value is left, after 14 a tenth
+    assert 0.30 < lam ** 7 < 0.34 and lam ** 14 < 0.11
+    # lambda = 0 follows the input, a NaN observation leaves the estimate alone
+    assert oracle.ema_update(0.0, 7.0, 1.5) == 1.5
+    assert oracle.ema_update(lam, 2.0, nan) == 2.0
+
+
+def test_library_ema_matches_oracle():
+    from paper_2604_10597_amd import binding
+    import numpy as np
+    rng = np.random.default_rng(5)
+    s_lib = s_or = float("nan")
+    for H in rng.uniform(0, 5.5, 200):
+        s_lib = binding.corey_ema_update(0.85, s_lib, float(H))
+        s_or = oracle.ema_update(0.85, s_or, float(H))
+        assert s_lib == s_or
+    for bad in (-0.1, 1.0, float("nan")):
+        with pytest.raises(binding.CoreyError):
+            binding.corey_ema_update(bad, 1.0, 1.0)
