@@ -58,6 +58,8 @@ typedef enum {
 #define COREY_MIN_CHUNK 16
 #define COREY_MAX_CHUNK 2048
 #define COREY_CHUNK_SLOTS 12     /* chunk-distribution counters: slot log2(chunk), chunk = 1 .. 2048 */
+#define COREY_MAX_CONV 4         /* taps of the causal convolution that produces u */
+#define COREY_RANGE_PARTS 1024   /* partial ranges a producer of u hands to corey_entropy_hist (16 bytes each) */
 
 /* -------------------------------------------------------------------------------------------------------
  * corey_entropy_hist -- Eq. 1 and r = H / log K.
@@ -83,6 +85,9 @@ typedef enum {
  *               the sampled runs of memory are fetched, so the statistic costs 1/stride of the traffic.
  *   counts_out  DEVICE uint32[nh * K].   H_out, r_out: DEVICE double[nh].
  *   range_out   DEVICE float[nh * 2] (lo, hi per histogram) or NULL.
+ *   range_parts DEVICE, COREY_RANGE_PARTS * 16 bytes as written by causal_conv1d_silu_fwd for this same tensor, or
+ *               NULL.  With it the range sweep is skipped (the producer of x already saw every value): only the
+ *               count sweep reads x.  Requires seqlens == NULL and stride == 1 (COREY_EINVAL otherwise).
  *   workspace   DEVICE, at least corey_entropy_hist_workspace(B, K) bytes, 256-byte aligned; scratch only,
  *               contents are undefined afterwards.
  * The work is two sweeps over the sampled values of x (range, then counts) plus an O(K) reduction, as the paper's
@@ -92,7 +97,7 @@ typedef enum {
 int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
                        const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
                        uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
-                       void* workspace, size_t workspace_bytes, void* hip_stream);
+                       const void* range_parts, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of workspace corey_entropy_hist needs for batch B and K bins (0 if the arguments are invalid). */
 size_t corey_entropy_hist_workspace(int64_t B, int32_t K);
@@ -173,8 +178,30 @@ int corey_ema_update(double lambda, double* state, double H);
 int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
                        const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
                        const corey_policy* p, double ema_lambda, double* ema_state, uint32_t* chunk_calls,
-                       uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
+                       uint32_t* counts_out, double* H_out, double* r_out, float* range_out, const void* range_parts,
                        int32_t* chunks_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* -------------------------------------------------------------------------------------------------------
+ * causal_conv1d_silu_fwd -- the step before the path: the causal depthwise convolution and SiLU that produce the
+ * scan input u (step (1) of the paper's inline hook, "Active-Mode Overhead Budget": convolution, then the entropy of
+ * the post-convolution tensor, then the rule, then the scan), with the range of u taken in the same pass (the paper
+ * names fusing the statistic more deeply into the layer as the way to make routing cheaper):
+ *
+ *     v[b,d,t] = bias[d] + sum_{k=0}^{W-1} weight[d,k] * x[b,d,t-(W-1)+k]       (x before t = 0: state_in, else 0)
+ *     u[b,d,t] = v * sigmoid(v)                                                   stored in `dt`
+ *
+ * evaluated in binary32 (taps accumulated oldest first with fused multiply-adds).
+ *   x, u        DEVICE [B, D, L] in `dt`; u may not alias x.
+ *   weight      DEVICE float[D, W], 1 <= W <= COREY_MAX_CONV.     bias: DEVICE float[D] or NULL.
+ *   state_in    DEVICE [B, D, W-1] in `dt` or NULL: the W-1 inputs that precede t = 0 (oldest first).
+ *   state_out   DEVICE [B, D, W-1] in `dt` or NULL: the last W-1 inputs (for continuing the sequence).
+ *   range_parts DEVICE, COREY_RANGE_PARTS * 16 bytes, or NULL: partial minima / maxima (and a NaN flag) of the
+ *               values of u *as stored*, for corey_entropy_hist / corey_route_device on this u.
+ * Errors: COREY_ENULL, COREY_EINVAL (dtype, W), COREY_ESHAPE.
+ * ----------------------------------------------------------------------------------------------------- */
+int causal_conv1d_silu_fwd(const void* x, const float* weight, const float* bias, const void* state_in,
+                           void* u, void* state_out, void* range_parts, corey_dtype dt,
+                           int64_t B, int64_t D, int64_t L, int32_t W, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------
  * selective_scan_fwd -- the recurrence h_t = A_t h_{t-1} + B_t x_t, y_t = C_t h_t + D_t x_t (Method,

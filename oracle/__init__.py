@@ -102,6 +102,26 @@ def ema_update(lam, prev, H):
     return f(ctypes.c_double(lam), ctypes.c_double(prev), ctypes.c_double(H))
 
 
+def causal_conv1d_silu(x, weight, bias=None, state_in=None):
+    """x [B, D, L], weight [D, W], bias [D], state_in [B, D, W-1] (float arrays).  Returns (u float64 [B, D, L],
+    state_out float32 [B, D, W-1])."""
+    x = np.asarray(x)
+    B, D, L = x.shape
+    W = np.asarray(weight).shape[1]
+    xk, xp = _f32(x)
+    wk, wp = _f32(weight)
+    bk, bp = _f32(bias)
+    sk, sp = _f32(state_in)
+    u = np.zeros((B, D, L), dtype=np.float64)
+    so = np.zeros((B, D, max(W - 1, 0)), dtype=np.float32)
+    f = lib().oracle_causal_conv1d_silu
+    f.restype = ctypes.c_int
+    st = f(xp, wp, bp, sp, ctypes.c_int64(B), ctypes.c_int64(D), ctypes.c_int64(L), ctypes.c_int32(W),
+           u.ctypes.data_as(ctypes.c_void_p), so.ctypes.data_as(ctypes.c_void_p))
+    assert st == OK
+    return u, so
+
+
 def select_chunk(r, L, pol: Policy | None = None):
     """Returns (status, chunk, margin)."""
     pol = pol or policy()

@@ -319,3 +319,39 @@ int oracle_max_threads(void)
     return 1;
 #endif
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * The step before the path: causal depthwise convolution and SiLU producing the scan input u (step (1) of the
+ * paper's inline hook, "Active-Mode Overhead Budget"), in its Mamba-1 form:
+ *     v[b,d,t] = bias[d] + sum_{k=0}^{W-1} weight[d,k] * x[b,d,t-(W-1)+k],   u = v / (1 + exp(-v)),
+ * inputs before t = 0 taken from state_in[b,d,0..W-2] (oldest first) or zero.  Everything in double; u is returned
+ * unrounded.  state_out (may be NULL) receives the last W-1 inputs of every row.
+ * ---------------------------------------------------------------------------------------------- */
+int oracle_causal_conv1d_silu(const float* x, const float* weight, const float* bias, const float* state_in,
+                              int64_t B, int64_t D, int64_t L, int32_t W, double* u, float* state_out)
+{
+    if (!x || !weight || !u || B < 1 || D < 1 || L < 1 || W < 1) return ORACLE_EINVAL;
+    for (int64_t r = 0; r < B * D; ++r) {
+        const int64_t d = r % D;
+        for (int64_t t = 0; t < L; ++t) {
+            double v = bias ? (double)bias[d] : 0.0;
+            for (int32_t k = 0; k < W; ++k) {
+                const int64_t s = t - (W - 1) + k;
+                double xv = 0.0;
+                if (s >= 0) xv = (double)x[r * L + s];
+                else if (state_in) xv = (double)state_in[r * (W - 1) + (s + (W - 1))];
+                v += (double)weight[d * W + k] * xv;
+            }
+            u[r * L + t] = v / (1.0 + exp(-v));
+        }
+        if (state_out)
+            for (int32_t k = 0; k < W - 1; ++k) {
+                const int64_t s = L - (W - 1) + k;
+                float xv = 0.f;
+                if (s >= 0) xv = x[r * L + s];
+                else if (state_in) xv = state_in[r * (W - 1) + (s + (W - 1))];
+                state_out[r * (W - 1) + k] = xv;
+            }
+    }
+    return ORACLE_OK;
+}

@@ -18,7 +18,7 @@ COREY_F32, COREY_BF16, COREY_F16 = 0, 1, 2
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
-           "corey_select_chunk_device", "corey_route_device", "corey_ema_update",
+           "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd",
            "selective_scan_fwd", "selective_scan_fwd_workspace", "corey_scan_structured_path", "corey_last_error", "corey_version")
 
 
@@ -48,11 +48,13 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         i64, i32, vp, dbl = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_double
         L.corey_entropy_hist.restype = ctypes.c_int
-        L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp,
+        L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp, vp,
                                          ctypes.c_size_t, vp]
+        L.causal_conv1d_silu_fwd.restype = ctypes.c_int
+        L.causal_conv1d_silu_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, i64, i64, i64, i32, vp]
         L.corey_route_device.restype = ctypes.c_int
         L.corey_route_device.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, ctypes.POINTER(Policy), dbl, vp, vp,
-                                         vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+                                         vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.corey_ema_update.restype = ctypes.c_int
         L.corey_ema_update.argtypes = [dbl, ctypes.POINTER(dbl), dbl]
         L.corey_entropy_hist_workspace.restype = ctypes.c_size_t
@@ -118,8 +120,34 @@ def corey_entropy_hist_workspace(B: int, K: int) -> int:
     return int(lib().corey_entropy_hist_workspace(B, K))
 
 
+RANGE_PARTS_BYTES = 1024 * 16      # COREY_RANGE_PARTS records of 16 bytes
+
+
+def causal_conv1d_silu_fwd(x: torch.Tensor, weight: torch.Tensor, bias: torch.Tensor | None = None,
+                           state_in: torch.Tensor | None = None, u: torch.Tensor | None = None, want_state: bool = False,
+                           range_parts: torch.Tensor | None = None):
+    """x [B, D, L] GPU tensor, weight float32 [D, W], bias float32 [D].  Returns (u, state_out or None, range_parts):
+    range_parts (uint8 GPU tensor of RANGE_PARTS_BYTES, allocated here if omitted) can be handed to
+    corey_entropy_hist / corey_route_device on this u, which then skip their range sweep."""
+    for name, t in (("x", x), ("weight", weight), ("bias", bias), ("state_in", state_in), ("u", u), ("range_parts", range_parts)):
+        _dev(t, name)
+    B, D, L = x.shape
+    W = weight.shape[1]
+    if weight.shape[0] != D or weight.dtype != torch.float32 or (bias is not None and bias.dtype != torch.float32):
+        raise TypeError("weight [D, W] and bias [D] must be float32")
+    if u is None:
+        u = torch.empty_like(x)
+    state_out = torch.empty((B, D, W - 1), dtype=x.dtype, device=x.device) if want_state else None
+    if range_parts is None:
+        range_parts = torch.empty(RANGE_PARTS_BYTES, dtype=torch.uint8, device=x.device)
+    _check(lib().causal_conv1d_silu_fwd(_ptr(x), _ptr(weight), _ptr(bias), _ptr(state_in), _ptr(u), _ptr(state_out),
+                                        _ptr(range_parts), _dtype_code(x), B, D, L, W, _stream()))
+    return u, state_out, range_parts
+
+
 def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int = 1, seqlens: torch.Tensor | None = None,
-                       out: dict | None = None, workspace: torch.Tensor | None = None, block: int = 1):
+                       out: dict | None = None, workspace: torch.Tensor | None = None, block: int = 1,
+                       range_parts: torch.Tensor | None = None):
     """x: [B, D, L] GPU tensor (float32 or bfloat16).  Returns dict(counts, H, r, range) of GPU tensors;
     nothing is copied to the host and the call does not synchronise."""
     _dev(x, "x"), _dev(seqlens, "seqlens")
@@ -137,7 +165,7 @@ def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int =
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
     _check(lib().corey_entropy_hist(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride, block,
                                     _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
-                                    _ptr(workspace), workspace.numel(), _stream()))
+                                    _ptr(range_parts), _ptr(workspace), workspace.numel(), _stream()))
     out["workspace"] = workspace
     return out
 
@@ -151,7 +179,8 @@ def corey_ema_update(lam: float, state: float, H: float) -> float:
 
 def corey_route_device(x: torch.Tensor, K: int, policy: Policy | None = None, eps: float = 1e-8, stride: int = 1, block: int = 1,
                        seqlens: torch.Tensor | None = None, out: dict | None = None, workspace: torch.Tensor | None = None,
-                       ema_lambda: float = 0.0, ema_state: torch.Tensor | None = None, chunk_calls: torch.Tensor | None = None):
+                       ema_lambda: float = 0.0, ema_state: torch.Tensor | None = None, chunk_calls: torch.Tensor | None = None,
+                       range_parts: torch.Tensor | None = None):
     """corey_entropy_hist and the chunk rule in one call.  Returns the dict of corey_entropy_hist plus `chunks`
     (int32 GPU tensor [nh], directly usable as `chunks_dev` of selective_scan_fwd); no synchronisation.
     ema_state: float64 GPU tensor [nh] (NaN = no estimate yet), updated in place; chunk_calls: int32 GPU tensor
@@ -175,7 +204,7 @@ def corey_route_device(x: torch.Tensor, K: int, policy: Policy | None = None, ep
         workspace = torch.empty(max(corey_entropy_hist_workspace(B, K), 256), dtype=torch.uint8, device=x.device)
     _check(lib().corey_route_device(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride, block, ctypes.byref(p),
                                     float(ema_lambda), _ptr(ema_state), _ptr(chunk_calls), _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
-                                    _ptr(out["chunks"]), _ptr(workspace), workspace.numel(), _stream()))
+                                    _ptr(range_parts), _ptr(out["chunks"]), _ptr(workspace), workspace.numel(), _stream()))
     out["workspace"] = workspace
     return out
 

@@ -23,15 +23,20 @@
 #include <cmath>
 
 #include "corey_internal.h"
+#include "corey_range.h"
 
 namespace {
 
 using corey::bf16_to_f32;
 
-constexpr int kThreads = 256;
+using corey_range::kThreads;
+using corey_range::key_value;
+using corey_range::order_key;
+using corey_range::RangePart;
+using corey_range::reduce_range_keys;
 constexpr int kVecBytes = 16;
 constexpr int kParts = 16;     // partial histograms per histogram in the workspace
-constexpr int kMaxBlocks = 1024;  // workgroups per sweep (four per compute unit)
+constexpr int kMaxBlocks = COREY_RANGE_PARTS;  // workgroups per sweep (four per compute unit)
 
 struct RangeSlot {        // one per histogram, in the caller's workspace
     uint32_t lo_key;      // order-preserving image of the minimum (0xffffffff: nothing seen)
@@ -39,17 +44,6 @@ struct RangeSlot {        // one per histogram, in the caller's workspace
     uint32_t saw_nan;
     uint32_t pad;
 };
-
-__device__ __forceinline__ uint32_t order_key(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ __forceinline__ float key_value(uint32_t k)
-{
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
-}
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -188,27 +182,6 @@ __global__ void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots
     }
 }
 
-// Workgroup reduction of (lo, hi, nan flag) as order-preserving keys; the result is valid in thread 0.
-__device__ __forceinline__ void reduce_range_keys(uint32_t& klo, uint32_t& khi, uint32_t& knan)
-{
-    for (int off = 32; off > 0; off >>= 1) {
-        klo = min(klo, (uint32_t)__shfl_xor((int)klo, off));
-        khi = max(khi, (uint32_t)__shfl_xor((int)khi, off));
-        knan |= (uint32_t)__shfl_xor((int)knan, off);
-    }
-    __shared__ uint32_t s_lo[kThreads / 64], s_hi[kThreads / 64], s_nan[kThreads / 64];
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { s_lo[wave] = klo; s_hi[wave] = khi; s_nan[wave] = knan; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < kThreads / 64; ++w) {
-            klo = min(klo, s_lo[w]);
-            khi = max(khi, s_hi[w]);
-            knan |= s_nan[w];
-        }
-    }
-}
-
 // ... and the integer atomics that publish it.  The slot is read first and an atomic is issued only if it
 // would change it: extremes only move one way, so a stale read can cost a redundant atomic but never lose an
 // update, and almost all workgroups skip the contended atomics.
@@ -313,10 +286,6 @@ template <bool SAMPLED> struct WordMap {
         const int64_t sb = i >> bw_log2;
         return ((sb * stride) << bw_log2) + (i - (sb << bw_log2));
     }
-};
-
-struct RangePart {        // what one workgroup of the flat range sweep saw
-    uint32_t lo_key, hi_key, saw_nan, pad;
 };
 
 template <typename T, bool SAMPLED>
@@ -609,6 +578,22 @@ size_t parts_bytes(int64_t nh, int32_t K) { return ((size_t)nh * kParts * K * si
 
 size_t workspace_bytes(int64_t nh, int32_t K) { return slots_bytes(nh) + parts_bytes(nh, K) + (size_t)kMaxBlocks * sizeof(RangePart); }
 
+// Fold given partial ranges into the range slot of the (single) histogram.
+__global__ __launch_bounds__(kThreads) void k_entropy_fold_parts(const RangePart* __restrict__ rparts, int nrparts, RangeSlot* slots)
+{
+    uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
+    for (int i = threadIdx.x; i < nrparts; i += kThreads) {
+        const RangePart rp = rparts[i];
+        klo = min(klo, rp.lo_key);
+        khi = max(khi, rp.hi_key);
+        knan |= rp.saw_nan;
+    }
+    reduce_range_keys(klo, khi, knan);
+    if (threadIdx.x == 0) {
+        slots[0].lo_key = klo; slots[0].hi_key = khi; slots[0].saw_nan = knan; slots[0].pad = 0u;
+    }
+}
+
 template <typename T, bool SAMPLED>
 void launch_flat(const word4* x, int64_t nwords, WordMap<SAMPLED> map, int32_t K, RangeSlot* slots, uint32_t* parts,
                  RangePart* rparts, hipStream_t stream)
@@ -623,7 +608,8 @@ void launch_flat(const word4* x, int64_t nwords, WordMap<SAMPLED> map, int32_t K
 template <typename T>
 int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K, double eps, int64_t stride,
            int64_t block, uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream,
-           const corey_policy* pol, int32_t* chunks_out, double ema_lambda, double* ema_state, uint32_t* chunk_calls)
+           const corey_policy* pol, int32_t* chunks_out, double ema_lambda, double* ema_state, uint32_t* chunk_calls,
+           const RangePart* given_parts)
 {
     const int nh = seqlens ? (int)B : 1;
     uint32_t* parts = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(slots) + slots_bytes(B));
@@ -634,7 +620,25 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
     const int64_t E = B * D * L;
     const bool flat_ok = !seqlens && reinterpret_cast<uintptr_t>(x) % kVecBytes == 0 && E % V == 0;
     const int64_t bw = block / V;                              // 16-byte words per sampling block
-    if (flat_ok && stride == 1) {
+    if (given_parts && flat_ok) {
+        // the producer of x left the partial ranges: clear the partial counts and go straight to the count sweep
+        const int64_t nwords = E / V;
+        int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
+        blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
+        k_entropy_count_flat<T, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
+            static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
+    } else if (given_parts) {
+        // unaligned tensor: one workgroup folds the partial ranges into the slot, then the general count sweep
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
+        k_entropy_fold_parts<<<dim3(1), dim3(kThreads), 0, stream>>>(given_parts, COREY_RANGE_PARTS, slots);
+        const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
+        const int64_t seg = (int64_t)kThreads * V * kUnroll;
+        int64_t blocks = B * D * ((L + seg - 1) / seg);
+        blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
+        k_entropy_count<T><<<dim3((unsigned)blocks, 1), dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, nullptr, 1, 1,
+                                                                                   vector_ok ? 1 : 0, K, slots, parts);
+    } else if (flat_ok && stride == 1) {
         // whole tensor, every value, aligned: flat sweeps
         launch_flat<T, false>(static_cast<const word4*>(x), E / V, WordMap<false>{0, 1}, K, slots, parts, rparts, stream);
     } else if (flat_ok && block % V == 0 && corey::is_pow2(bw)) {
@@ -703,7 +707,8 @@ namespace {
 int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K,
                       double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
                       void* workspace, size_t workspace_bytes_given, void* hip_stream, const corey_policy* pol, int32_t* chunks_out,
-                      double ema_lambda = 0.0, double* ema_state = nullptr, uint32_t* chunk_calls = nullptr)
+                      double ema_lambda = 0.0, double* ema_state = nullptr, uint32_t* chunk_calls = nullptr,
+                      const void* range_parts = nullptr)
 {
     using corey::fail;
     if (!x || !counts_out || !H_out || !r_out) return fail(COREY_ENULL, "%s: x, counts_out, H_out and r_out are required", who);
@@ -716,6 +721,9 @@ int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B,
     if (K < 2 || K > COREY_MAX_BINS) return fail(COREY_EINVAL, "%s: K = %d outside [2, %d]", who, K, COREY_MAX_BINS);
     if (!(eps >= 0.0)) return fail(COREY_EINVAL, "%s: eps must be >= 0", who);
     if (stride < 1 || block < 1) return fail(COREY_EINVAL, "%s: stride and block must be >= 1", who);
+    if (range_parts && (seqlens || stride != 1))
+        return fail(COREY_EINVAL, "%s: range_parts needs the whole-tensor statistic (seqlens NULL, stride 1)", who);
+    if (range_parts && reinterpret_cast<uintptr_t>(range_parts) % 16 != 0) return fail(COREY_EINVAL, "%s: range_parts must be 16-byte aligned", who);
     const size_t need = workspace_bytes(B, K);
     if (!workspace || workspace_bytes_given < need) return fail(COREY_EWORKSPACE, "%s: workspace of %zu bytes required", who, need);
     if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "%s: workspace must be 16-byte aligned", who);
@@ -723,29 +731,30 @@ int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B,
     RangeSlot* slots = static_cast<RangeSlot*>(workspace);
     if (dt == COREY_F32)
         return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
-                             ema_state, chunk_calls);
+                             ema_state, chunk_calls, static_cast<const RangePart*>(range_parts));
     if (dt == COREY_F16)
         return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
-                             ema_state, chunk_calls);
+                             ema_state, chunk_calls, static_cast<const RangePart*>(range_parts));
     return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
-                             ema_state, chunk_calls);
+                             ema_state, chunk_calls, static_cast<const RangePart*>(range_parts));
 }
 
 }  // namespace
 
 extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
                                   int32_t K, double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out,
-                                  double* r_out, float* range_out, void* workspace, size_t workspace_bytes_given, void* hip_stream)
+                                  double* r_out, float* range_out, const void* range_parts, void* workspace,
+                                  size_t workspace_bytes_given, void* hip_stream)
 {
     return entropy_hist_impl("corey_entropy_hist", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
-                             workspace, workspace_bytes_given, hip_stream, nullptr, nullptr);
+                             workspace, workspace_bytes_given, hip_stream, nullptr, nullptr, 0.0, nullptr, nullptr, range_parts);
 }
 
 extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
                                   int32_t K, double eps, int64_t stride, int64_t block, const corey_policy* p,
                                   double ema_lambda, double* ema_state, uint32_t* chunk_calls,
-                                  uint32_t* counts_out, double* H_out, double* r_out, float* range_out, int32_t* chunks_out,
-                                  void* workspace, size_t workspace_bytes_given, void* hip_stream)
+                                  uint32_t* counts_out, double* H_out, double* r_out, float* range_out, const void* range_parts,
+                                  int32_t* chunks_out, void* workspace, size_t workspace_bytes_given, void* hip_stream)
 {
     using corey::fail;
     if (!p || !chunks_out) return fail(COREY_ENULL, "corey_route_device: p and chunks_out are required");
@@ -757,5 +766,5 @@ extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int6
     if (st != COREY_OK) return st;
     if (p->mode == 1 && !corey::is_pow2(p->short_chunk)) return fail(COREY_EINVAL, "corey_route_device: short_chunk = %d", p->short_chunk);
     return entropy_hist_impl("corey_route_device", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
-                             workspace, workspace_bytes_given, hip_stream, p, chunks_out, ema_lambda, ema_state, chunk_calls);
+                             workspace, workspace_bytes_given, hip_stream, p, chunks_out, ema_lambda, ema_state, chunk_calls, range_parts);
 }

@@ -155,6 +155,34 @@ def make(cfg: Config, a_kind: str = "mamba", with_z: bool = True, with_h0: bool 
     return w
 
 
+def make_conv(cfg: Config, W: int = 4, with_state: bool = False, seed_offset: int = 7919) -> dict:
+    """Inputs of the convolution that produces u: x [B, D, L] ~ N(0,1) rounded to cfg.dtype, weight [D, W] and bias [D]
+    ~ U(-1/sqrt(W), 1/sqrt(W)) (the default initialisation of a depthwise Conv1d with W taps), optional
+    state_in [B, D, W-1] ~ N(0,1) in the storage type.  Returns {"dev": storage arrays, "val": float32 values}."""
+    rng = np.random.default_rng(cfg.seed + seed_offset)
+    f = np.float32
+    x = rng.standard_normal((cfg.B, cfg.D, cfg.L), dtype=f)
+    k = f(1.0 / np.sqrt(W))
+    weight = rng.uniform(-k, k, size=(cfg.D, W)).astype(f)
+    bias = rng.uniform(-k, k, size=cfg.D).astype(f)
+    out = {"dev": {}, "val": {}}
+    out["dev"]["x"], out["val"]["x"] = store(x, cfg.dtype)
+    if with_state and W > 1:
+        st = rng.standard_normal((cfg.B, cfg.D, W - 1), dtype=f)
+        out["dev"]["state_in"], out["val"]["state_in"] = store(st, cfg.dtype)
+    else:
+        out["dev"]["state_in"] = out["val"]["state_in"] = None
+    for name, arr in (("weight", weight), ("bias", bias)):
+        out["dev"][name] = out["val"][name] = arr
+    return out
+
+
+def conv_bytes(cfg: Config) -> int:
+    """Bytes the convolution must move once: x in, u out (parameters are negligible)."""
+    s = 4 if cfg.dtype == F32 else 2
+    return 2 * cfg.B * cfg.D * cfg.L * s
+
+
 def scan_bytes(cfg: Config, with_z: bool = True, with_h0: bool = False) -> int:
     """Bytes the scan must move once: u, delta, (z) in and y out, B and C once, parameters, final state."""
     s = 4 if cfg.dtype == F32 else 2
