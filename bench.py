@@ -254,6 +254,19 @@ def main() -> int:
                 "route_two_sweeps_ms": round(hist2_ms, 4), "route_given_range_ms": round(hist1_ms, 4)}
     del xc, uc
 
+    # ---- one generated token from the carried state (the recurrence at L = 1), single sequence and batches of 64 and 512
+    # (back-to-back launches from Python: the small cases show the launch rate, about 12 us per call, not the kernel)
+    decode = {"note": "selective_state_update on the benchmark's layer shape; bytes = state read + written, A, per-row scalars"}
+    for Bd in (1, 64, 512):
+        dc = wl.scaled(cfg, B=Bd, L=1, seqlens=None)
+        dd = {k: dev(v) for k, v in wl.make_decode(dc)["dev"].items()}
+        yd = torch.empty_like(dd["x"])
+        ms = time_kernel(lambda: corey.selective_state_update(dd["state"], dd["x"], dd["delta"], dd["A"], dd["Bt"], dd["Ct"], Dv=dd["D"],
+                                                              z=dd["z"], delta_bias=dd["delta_bias"], y=yd), args.steps)
+        decode[f"B{Bd}"] = {"us_per_token_step": round(ms * 1e3, 2), "GBps": round(wl.decode_bytes(dc) / ms * 1e-6, 1),
+                            "hbm_frac": round(wl.decode_bytes(dc) / ms * 1e-6 / HBM_PEAK_GBPS, 4)}
+        del dd, yd
+
     # ---- the paper's own kernel-benchmark shape (batch 1, d 1024, L 4096, d_state 16, FP16), for context only
     paper_shape = None
     if not args.no_sweep:
@@ -343,6 +356,7 @@ def main() -> int:
         "per_chunk": per_chunk,
         "structured_A": structured,
         "producer": producer,
+        "decode": decode,
         "paper_shape": paper_shape,
         "cpu_baseline": cpu,
     }

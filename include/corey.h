@@ -261,6 +261,28 @@ const char* corey_last_error(void);
 /* Library version, "major.minor". */
 const char* corey_version(void);
 
+/* -------------------------------------------------------------------------------------------------------
+ * selective_state_update -- one generated token: the recurrence of selective_scan_fwd (Method, Preliminaries) taken
+ * for a single step from the carried state, as in the greedy-generation steps that follow the prompt in the paper's
+ * quality check ("Output Quality Preservation").  For every sequence b and channel d:
+ *
+ *     dl = delta[b,d] + delta_bias[d];   if delta_softplus: dl = log(1 + exp(dl))
+ *     state[b,d,n] <- exp(dl * A[d,n]) * state[b,d,n] + dl * Bt[b,n] * x[b,d]
+ *     y[b,d] = sum_n Ct[b,n] * state[b,d,n] + Dv[d] * x[b,d];   if z: y *= z * sigmoid(z)
+ *
+ *   state       DEVICE float[B, D, N], read and overwritten in place (the layout of selective_scan_fwd's last_state
+ *               and h0, so a prompt's final state can be carried straight into generation).
+ *   x, delta, z DEVICE [B, D] in `dt` (z may be NULL).   Bt, Ct: DEVICE [B, N] in `dt`.   y: DEVICE [B, D] in `dt`.
+ *   A float[D, N], Dv and delta_bias float[D] or NULL, DEVICE.
+ * Arithmetic in binary32 as in the scan; y is rounded once to `dt`.  Asynchronous on hip_stream; needs no workspace.
+ * Errors: COREY_ENULL, COREY_EINVAL (dtype, misaligned state), COREY_ESHAPE (B, D < 1, N outside
+ * [1, COREY_MAX_STATE], B*D >= 2^25), COREY_EHIP.
+ * ----------------------------------------------------------------------------------------------------- */
+int selective_state_update(void* state, const void* x, const void* delta, const float* A, const void* Bt,
+                           const void* Ct, const float* Dv, const void* z, const float* delta_bias,
+                           int32_t delta_softplus, void* y, corey_dtype dt, int64_t B, int64_t D, int64_t N,
+                           void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -102,6 +102,22 @@ def ema_update(lam, prev, H):
     return f(ctypes.c_double(lam), ctypes.c_double(prev), ctypes.c_double(H))
 
 
+def selective_state_update(state, x, delta, A, Bt, Ct, Dv=None, z=None, delta_bias=None, delta_softplus=True):
+    """One decode step.  state [B, D, N], x/delta/z [B, D], A [D, N], Bt/Ct [B, N].  Returns (state_out float64
+    [B, D, N], y float64 [B, D])."""
+    state = np.asarray(state)
+    B, D, N = state.shape
+    keep = [_f32(a) for a in (state, x, delta, A, Bt, Ct, Dv, z, delta_bias)]
+    so = np.zeros((B, D, N), dtype=np.float64)
+    y = np.zeros((B, D), dtype=np.float64)
+    f = lib().oracle_selective_state_update
+    f.restype = ctypes.c_int
+    st = f(*[k[1] for k in keep], ctypes.c_int(1 if delta_softplus else 0), ctypes.c_int64(B), ctypes.c_int64(D),
+           ctypes.c_int64(N), so.ctypes.data_as(ctypes.c_void_p), y.ctypes.data_as(ctypes.c_void_p))
+    assert st == OK
+    return so, y
+
+
 def causal_conv1d_silu(x, weight, bias=None, state_in=None):
     """x [B, D, L], weight [D, W], bias [D], state_in [B, D, W-1] (float arrays).  Returns (u float64 [B, D, L],
     state_out float32 [B, D, W-1])."""

@@ -355,3 +355,44 @@ int oracle_causal_conv1d_silu(const float* x, const float* weight, const float* 
     }
     return ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * One generated token: the recurrence of oracle_selective_scan taken for a single step from a carried state (what
+ * runs after the prompt in the paper's greedy-generation checks, "Output Quality Preservation").
+ *
+ * state_in      float[B][D][N]  the state after the previous token
+ * x, delta, z   float[B][D]     (z may be NULL)
+ * A float[D][N];  Bt, Ct float[B][N];  Dv, dbias float[D] or NULL
+ * state_out     double[B][D][N];  y double[B][D]
+ *     dl = softplus(delta + dbias);  h'[n] = exp(dl A[d][n]) h[n] + dl Bt[b][n] x;  y = sum_n Ct[b][n] h'[n] + Dv[d] x;
+ *     y *= z / (1 + exp(-z))
+ * ---------------------------------------------------------------------------------------------- */
+int oracle_selective_state_update(const float* state_in, const float* x, const float* delta, const float* A,
+                                  const float* Bt, const float* Ct, const float* Dv, const float* z,
+                                  const float* dbias, int delta_softplus, int64_t B, int64_t D, int64_t N,
+                                  double* state_out, double* y)
+{
+    if (!state_in || !x || !delta || !A || !Bt || !Ct || !state_out || !y) return ORACLE_EINVAL;
+    if (B < 1 || D < 1 || N < 1) return ORACLE_EINVAL;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t d = 0; d < D; ++d) {
+            const int64_t row = b * D + d;
+            double dl = (double)delta[row] + (dbias ? (double)dbias[d] : 0.0);
+            if (delta_softplus) dl = (dl > 0.0 ? dl : 0.0) + log1p(exp(-fabs(dl)));
+            const double xx = (double)x[row];
+            double acc = 0.0;
+            for (int64_t n = 0; n < N; ++n) {
+                const double hn = exp(dl * (double)A[d * N + n]) * (double)state_in[row * N + n]
+                                  + dl * (double)Bt[b * N + n] * xx;
+                state_out[row * N + n] = hn;
+                acc += (double)Ct[b * N + n] * hn;
+            }
+            double yv = acc + (Dv ? (double)Dv[d] * xx : 0.0);
+            if (z) {
+                const double zz = (double)z[row];
+                yv *= zz / (1.0 + exp(-zz));
+            }
+            y[row] = yv;
+        }
+    return ORACLE_OK;
+}

@@ -18,7 +18,7 @@ COREY_F32, COREY_BF16, COREY_F16 = 0, 1, 2
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
-           "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd",
+           "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
            "selective_scan_fwd", "selective_scan_fwd_workspace", "corey_scan_structured_path", "corey_last_error", "corey_version")
 
 
@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.corey_entropy_hist.restype = ctypes.c_int
         L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp, vp,
                                          ctypes.c_size_t, vp]
+        L.selective_state_update.restype = ctypes.c_int
+        L.selective_state_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, i64, i64, i64, vp]
         L.causal_conv1d_silu_fwd.restype = ctypes.c_int
         L.causal_conv1d_silu_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, i64, i64, i64, i32, vp]
         L.corey_route_device.restype = ctypes.c_int
@@ -118,6 +120,29 @@ def corey_version() -> str:
 
 def corey_entropy_hist_workspace(B: int, K: int) -> int:
     return int(lib().corey_entropy_hist_workspace(B, K))
+
+
+def selective_state_update(state: torch.Tensor, x: torch.Tensor, delta: torch.Tensor, A: torch.Tensor, Bt: torch.Tensor,
+                           Ct: torch.Tensor, Dv: torch.Tensor | None = None, z: torch.Tensor | None = None,
+                           delta_bias: torch.Tensor | None = None, delta_softplus: bool = True, y: torch.Tensor | None = None):
+    """One decode step: state float32 [B, D, N] is updated in place; x, delta, z [B, D]; Bt, Ct [B, N]; returns y [B, D]."""
+    for name, t in (("state", state), ("x", x), ("delta", delta), ("A", A), ("Bt", Bt), ("Ct", Ct), ("Dv", Dv), ("z", z),
+                    ("delta_bias", delta_bias), ("y", y)):
+        _dev(t, name)
+    B, D, N = state.shape
+    if state.dtype != torch.float32 or A.dtype != torch.float32 or A.shape != (D, N):
+        raise TypeError("state [B, D, N] and A [D, N] must be float32")
+    for name, t, shape in (("x", x, (B, D)), ("delta", delta, (B, D)), ("z", z, (B, D)), ("Bt", Bt, (B, N)), ("Ct", Ct, (B, N))):
+        if t is not None and (tuple(t.shape) != shape or t.dtype != x.dtype):
+            raise TypeError(f"{name} must be {shape} in the dtype of x")
+    for name, t in (("Dv", Dv), ("delta_bias", delta_bias)):
+        if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != (D,)):
+            raise TypeError(f"{name} must be float32 [D]")
+    if y is None:
+        y = torch.empty_like(x)
+    _check(lib().selective_state_update(_ptr(state), _ptr(x), _ptr(delta), _ptr(A), _ptr(Bt), _ptr(Ct), _ptr(Dv), _ptr(z),
+                                        _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(y), _dtype_code(x), B, D, N, _stream()))
+    return y
 
 
 RANGE_PARTS_BYTES = 1024 * 16      # COREY_RANGE_PARTS records of 16 bytes

@@ -177,6 +177,35 @@ def make_conv(cfg: Config, W: int = 4, with_state: bool = False, seed_offset: in
     return out
 
 
+def make_decode(cfg: Config, a_kind: str = "mamba", seed_offset: int = 104729) -> dict:
+    """Inputs of one generated token for cfg.B sequences (cfg.L is not used): state [B, D, N] float32 ~ N(0,1); x, z
+    [B, D] ~ N(0,1) and delta [B, D] ~ N(0, 0.5) in cfg.dtype; Bt, Ct [B, N] ~ N(0,1) in cfg.dtype; A, D, delta_bias as in
+    make().  Returns {"dev": storage arrays, "val": float32 values}."""
+    rng = np.random.default_rng(cfg.seed + seed_offset)
+    f = np.float32
+    B, D, N = cfg.B, cfg.D, cfg.N
+    out = {"dev": {}, "val": {}}
+    state = rng.standard_normal((B, D, N), dtype=f)
+    for name, arr in (("x", rng.standard_normal((B, D), dtype=f)), ("delta", rng.standard_normal((B, D), dtype=f) * f(0.5)),
+                      ("z", rng.standard_normal((B, D), dtype=f)), ("Bt", rng.standard_normal((B, N), dtype=f)),
+                      ("Ct", rng.standard_normal((B, N), dtype=f))):
+        out["dev"][name], out["val"][name] = store(arr, cfg.dtype)
+    if a_kind == "mamba":
+        A = -np.broadcast_to(np.arange(1, N + 1, dtype=f), (D, N)).copy()
+    else:
+        A = -np.exp(rng.standard_normal((D, N), dtype=f)).astype(f)
+    for name, arr in (("state", state), ("A", A), ("D", rng.standard_normal(D, dtype=f)),
+                      ("delta_bias", rng.uniform(np.log(1e-3), np.log(1e-1), size=D).astype(f))):
+        out["dev"][name] = out["val"][name] = arr
+    return out
+
+
+def decode_bytes(cfg: Config) -> int:
+    """Bytes one decode step must move: the state read and written, A once, the per-row scalars and y."""
+    s = 4 if cfg.dtype == F32 else 2
+    return 8 * cfg.B * cfg.D * cfg.N + 4 * cfg.D * cfg.N + 4 * cfg.B * cfg.D * s + 2 * cfg.B * cfg.N * s + 8 * cfg.D
+
+
 def conv_bytes(cfg: Config) -> int:
     """Bytes the convolution must move once: x in, u out (parameters are negligible)."""
     s = 4 if cfg.dtype == F32 else 2

@@ -15,7 +15,7 @@ from paper_2604_10597_amd import binding
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "corey.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(corey_\w+|selective_scan_fwd\w*|causal_conv1d_silu_fwd)\s*\(", hdr))
+    declared = set(re.findall(r"\b(corey_\w+|selective_scan_fwd\w*|causal_conv1d_silu_fwd|selective_state_update)\s*\(", hdr))
     declared -= {"corey_dtype", "corey_status", "corey_policy"}
     assert declared == set(binding.EXPORTS)
     lib = binding.lib()
@@ -93,6 +93,13 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     assert cv(B=0) == 3 and cv(L=0) == 3
     assert lib.corey_entropy_hist_workspace(0, 16) == 0 and lib.corey_entropy_hist_workspace(3, 1) == 0
     assert lib.corey_entropy_hist_workspace(3, 256) >= 3 * 16
+
+    su = lambda **kw: lib.selective_state_update(
+        kw.get("state", fake), kw.get("x", fake), fake, fake, fake, fake, none, none, none, 1, kw.get("y", fake), kw.get("dt", 1),
+        kw.get("B", 1), kw.get("D", 4), kw.get("N", 16), none)
+    assert su(state=none) == 2 and su(x=none) == 2 and su(y=none) == 2
+    assert su(dt=5) == 1 and su(state=ctypes.c_void_p(0x1002)) == 1
+    assert su(B=0) == 3 and su(N=0) == 3 and su(N=257) == 3 and su(B=1 << 20, D=1 << 10) == 3
 
     ss = lambda **kw: lib.selective_scan_fwd(
         kw.get("u", fake), fake, fake, fake, fake, none, none, none, 1, none, none, kw.get("chunk", 256), none,
