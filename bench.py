@@ -223,6 +223,29 @@ def main() -> int:
     structured["hbm_frac_at_routed_chunk"] = round(structured["GBps"][str(chunk)] / HBM_PEAK_GBPS, 4)
     corey.corey_scan_structured_path(False)
 
+    # ---- ceilings beside the HBM peak: what a plain device copy reaches on this machine, and the time the scan's own
+    # instruction stream needs at the measured issue rates (counts per wave-level state update from the committed
+    # counter summary; cycles per wave instruction from issue-rate probes: plain VALU 2.3 with both pipes of a SIMD fed,
+    # transcendental 8.2, not overlapping)
+    src = torch.empty(scan_bytes // 2, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    ca, cb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ca.record()
+    for _ in range(20):
+        dst.copy_(src)
+    cb.record()
+    torch.cuda.synchronize()
+    copy_ms = ca.elapsed_time(cb) / 20
+    del src, dst
+    wave_updates = state_updates / 64.0
+    issue_cycles = wave_updates / 1024.0 * (8.2 * 2.3 + 1.34 * 8.2)          # per SIMD (256 CUs x 4)
+    ceilings = {"device_copy_GBps": round(scan_bytes / copy_ms * 1e-6, 1), "device_copy_ms_for_scan_bytes": round(copy_ms, 4),
+                "issue_model_ms_at_2p2GHz": round(issue_cycles / 2.2e9 * 1e3, 4),
+                "issue_model": "8.2 VALU x 2.3 cycles + 1.34 transcendental x 8.2 cycles per wave-level state update, 1024 SIMDs"}
+
     # ---- the producer of u (causal convolution + SiLU) with the range of u taken in the same pass: the statistic then
     # needs one sweep over u instead of two
     cv = wl.make_conv(cfg, 4)
@@ -364,6 +387,7 @@ def main() -> int:
                                                   "entropy_routing_pct_of_scan": round((ms_step_sampled - scan_alone_ms) / scan_alone_ms * 100, 2),
                                                   "hist_kernels_ms": round(hist_sampled_ms, 4), "r": r_sampled,
                                                   "routed_chunk": chunk_sampled}},
+        "ceilings": ceilings,
         "per_chunk": per_chunk,
         "structured_A": structured,
         "producer": producer,
