@@ -145,3 +145,33 @@ def test_given_range_is_rejected_for_per_sequence_or_sampled_statistics():
         corey.corey_entropy_hist(u, 16, seqlens=torch.tensor([64, 10], dtype=torch.int32, device="cuda"), range_parts=parts)
     with pytest.raises(corey.CoreyError):
         corey.causal_conv1d_silu_fwd(x, torch.ones(4, 5, device="cuda"))
+
+
+@pytest.mark.parametrize("name", ["c2_mamba370m", "c4_mamba2p8b", "paper_w1_fp16"])
+def test_full_size_sampled_channels_and_whole_range(name):
+    """The benchmark's launch configuration at full size: the oracle recomputes sampled channels, the fused range is
+    checked against a plain reduction of the stored output, and the histogram it feeds against the oracle's."""
+    cfg = wl.scaled(wl.CONFIGS[name], seqlens=None) if wl.CONFIGS[name].seqlens else wl.CONFIGS[name]
+    _say(f"conv full size {name} B{cfg.B} D{cfg.D} L{cfg.L} {cfg.dtype}")
+    c = wl.make_conv(cfg, 4, with_state=True)
+    dev, val = c["dev"], c["val"]
+    xd = to_dev(dev["x"], cfg.dtype)
+    wd, bd = torch.from_numpy(dev["weight"]).cuda(), torch.from_numpy(dev["bias"]).cuda()
+    sd = to_dev(dev["state_in"], cfg.dtype)
+    u, so, parts = corey.causal_conv1d_silu_fwd(xd, wd, bd, sd, want_state=True)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, cfg.D // 2, cfg.D - 1], np.random.default_rng(5).integers(0, cfg.D, 12)]))
+    sub = {"x": val["x"][:, rows, :], "weight": val["weight"][rows], "bias": val["bias"][rows], "state_in": val["state_in"][:, rows, :]}
+    ref_u, ref_so = oracle.causal_conv1d_silu(sub["x"], sub["weight"], sub["bias"], sub["state_in"])
+    got = _widen(u[:, torch.from_numpy(rows).cuda(), :]).astype(np.float64)
+    err, tol = np.abs(got - ref_u), _tolerance(ref_u, sub, 4, cfg.dtype)
+    assert not (err > tol).any(), f"worst {float((err / tol).max()):.2f}x the tolerance"
+    assert np.array_equal(_widen(so)[:, rows, :], ref_so)
+    uf = u.float()
+    lo, hi, nan = _parts_range(parts)
+    assert lo == uf.min().item() and hi == uf.max().item() and not nan
+    fused = corey.corey_entropy_hist(u, cfg.K, range_parts=parts)
+    torch.cuda.synchronize()
+    ref = oracle.entropy_hist(uf.cpu().numpy(), cfg.K)
+    assert np.array_equal(counts_u32(fused["counts"]), ref["counts"])
+    assert fused["H"].item() == pytest.approx(ref["H"][0], rel=1e-12)
