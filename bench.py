@@ -55,8 +55,8 @@ def main() -> int:
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
-              "run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU only: this build has no multi-GPU path (rows are independent and would shard "
+              "over channels); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

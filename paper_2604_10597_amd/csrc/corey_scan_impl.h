@@ -39,7 +39,10 @@ namespace corey_scan {
 using corey::bf16_to_f32;
 using corey::f32_to_bf16;
 
-constexpr int kBlock = 256;           // lanes per workgroup: four waves, one per SIMD of a compute unit
+#ifndef COREY_BLOCK
+#define COREY_BLOCK 256
+#endif
+constexpr int kBlock = COREY_BLOCK;   // lanes per workgroup: four waves, one per SIMD of a compute unit
 constexpr int kWaves = kBlock / 64;
 // Build-time tuning knobs (defaults are the measured best on MI355X).
 #ifndef COREY_STAGE_FLOATS_K16
