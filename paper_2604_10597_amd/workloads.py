@@ -213,10 +213,11 @@ def conv_bytes(cfg: Config) -> int:
 
 
 def scan_bytes(cfg: Config, with_z: bool = True, with_h0: bool = False) -> int:
-    """Bytes the scan must move once: u, delta, (z) in and y out, B and C once, parameters, final state."""
+    """Bytes the scan must move once: u, delta, (z) in over the valid tokens, B and C once over the valid tokens, y out
+    over all B*L positions (padded positions are written as zero), parameters, final state."""
     s = 4 if cfg.dtype == F32 else 2
-    E = cfg.B * cfg.D * cfg.L
-    n = (4 if with_z else 3) * E * s + 2 * cfg.B * cfg.N * cfg.L * s
+    valid = sum(cfg.seqlens) if cfg.seqlens is not None else cfg.B * cfg.L
+    n = ((3 if with_z else 2) * cfg.D * valid + cfg.B * cfg.D * cfg.L) * s + 2 * cfg.N * valid * s
     n += 4 * cfg.D * cfg.N + 8 * cfg.D + 4 * cfg.B * cfg.D * cfg.N * (2 if with_h0 else 1)
     return n
 
