@@ -296,7 +296,30 @@ def main() -> int:
             for _ in range(32):
                 one_token()
         ms_g = time_kernel(graph.replay, 20) / 32
+        # with the convolution's own single step in front (its carried window in, u_t and the new window out)
+        xt = dd["x"].unsqueeze(2).contiguous()
+        ut = torch.empty_like(xt)
+        cw, cb = torch.rand(cfg.D, 4, device="cuda") - 0.5, torch.rand(cfg.D, device="cuda") - 0.5
+        win = [torch.zeros((Bd, cfg.D, 3), dtype=xt.dtype, device="cuda") for _ in range(2)]
+        cparts = torch.empty(corey.binding.RANGE_PARTS_BYTES, dtype=torch.uint8, device="cuda")
+        lib, ptr = corey.binding.lib(), corey.binding._ptr
+
+        def layer_token(i):
+            corey.binding._check(lib.causal_conv1d_silu_fwd(ptr(xt), ptr(cw), ptr(cb), ptr(win[i & 1]), ptr(ut), ptr(win[(i & 1) ^ 1]),
+                                                             ptr(cparts), corey.binding._dtype_code(xt), Bd, cfg.D, 1, 4,
+                                                             corey.binding._stream()))
+            corey.selective_state_update(dd["state"], ut.view(Bd, cfg.D), dd["delta"], dd["A"], dd["Bt"], dd["Ct"], Dv=dd["D"],
+                                         z=dd["z"], delta_bias=dd["delta_bias"], y=yd)
+        layer_token(0)
+        torch.cuda.synchronize()
+        graph2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph2):
+            for i in range(32):
+                layer_token(i)
+        ms_g2 = time_kernel(graph2.replay, 20) / 32
+        del graph2
         decode[f"B{Bd}"] = {"us_per_token_step_eager_calls": round(ms * 1e3, 2), "us_per_token_step_graph": round(ms_g * 1e3, 2),
+                            "us_per_token_conv_plus_state_graph": round(ms_g2 * 1e3, 2),
                             "GBps": round(wl.decode_bytes(dc) / ms_g * 1e-6, 1),
                             "hbm_frac": round(wl.decode_bytes(dc) / ms_g * 1e-6 / HBM_PEAK_GBPS, 4)}
         del graph, dd, yd

@@ -308,6 +308,83 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_silu(const T* __restrict__ 
     }
 }
 
+// Sequences of a few steps (generation: L = 1 with the carried state): one lane per row instead of one workgroup
+// per row segment.  A lane keeps the row's window of W - 1 earlier inputs in registers and walks its L steps.
+constexpr int kShortL = 16;
+
+template <typename T, int W>
+__global__ __launch_bounds__(kThreads) void k_conv1d_silu_short(const T* __restrict__ x, const float* __restrict__ weight,
+                                                                const float* __restrict__ bias, const T* __restrict__ state_in,
+                                                                T* __restrict__ u, T* __restrict__ state_out,
+                                                                RangePart* __restrict__ rparts, int64_t rows, int64_t D, int L)
+{
+    float lo = INFINITY, hi = -INFINITY;
+    bool nan = false;
+    for (int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x; r < rows; r += (int64_t)gridDim.x * kThreads) {
+        const int64_t d = r % D;
+        float w[W], win[W];                                   // win[k]: the input the tap w[k] multiplies at the current step
+#pragma unroll
+        for (int k = 0; k < W; ++k) w[k] = weight[d * W + k];
+#pragma unroll
+        for (int k = 0; k < W - 1; ++k) win[k + 1] = state_in ? St<T>::widen(state_in[r * (W - 1) + k]) : 0.f;
+        const float bs = bias ? bias[d] : 0.f;
+        T raw[W > 1 ? W - 1 : 1];                             // the stored form of the window, for state_out
+#pragma unroll
+        for (int k = 0; k < W - 1; ++k) raw[k] = state_in ? state_in[r * (W - 1) + k] : T(0);
+        for (int t = 0; t < L; ++t) {
+#pragma unroll
+            for (int k = 0; k < W - 1; ++k) win[k] = win[k + 1];
+#pragma unroll
+            for (int k = 0; k + 1 < W - 1; ++k) raw[k] = raw[k + 1];
+            const T xt = x[r * L + t];
+            win[W - 1] = St<T>::widen(xt);
+            if constexpr (W > 1) raw[W - 2] = xt;
+            float acc = bs;
+#pragma unroll
+            for (int k = 0; k < W; ++k) acc = fmaf(w[k], win[k], acc);
+            const float val = acc * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-acc * kLog2e));
+            nan |= (val != val);
+            lo = vmin(lo, val);
+            hi = vmax(hi, val);
+            float one[St<T>::kVec];
+            T st[St<T>::kVec];
+#pragma unroll
+            for (int e = 0; e < St<T>::kVec; ++e) one[e] = val;
+            St<T>::narrow(one, st);
+            u[r * L + t] = st[0];
+        }
+        if (state_out)
+#pragma unroll
+            for (int k = 0; k < W - 1; ++k) state_out[r * (W - 1) + k] = raw[k];
+    }
+    if (lo <= hi) {                                           // the stored extremes: one rounding each
+        float pad[St<T>::kVec];
+        T st[St<T>::kVec];
+#pragma unroll
+        for (int e = 0; e < St<T>::kVec; ++e) pad[e] = (e == 0) ? lo : hi;
+        St<T>::narrow(pad, st);
+        lo = St<T>::widen(st[0]);
+        hi = St<T>::widen(st[1]);
+    }
+    if (rparts) {
+        uint32_t klo = (lo <= hi) ? order_key(lo) : 0xffffffffu;
+        uint32_t khi = (lo <= hi) ? order_key(hi) : 0u;
+        uint32_t knan = nan ? 1u : 0u;
+        reduce_range_keys(klo, khi, knan);
+        if (threadIdx.x == 0) {
+            RangePart rp;
+            rp.lo_key = klo; rp.hi_key = khi; rp.saw_nan = knan; rp.pad = 0u;
+            rparts[blockIdx.x] = rp;
+        }
+        if (blockIdx.x == 0)                                  // entries no workgroup owns say "nothing seen"
+            for (int i = gridDim.x + threadIdx.x; i < COREY_RANGE_PARTS; i += kThreads) {
+                RangePart rp;
+                rp.lo_key = 0xffffffffu; rp.hi_key = 0u; rp.saw_nan = 0u; rp.pad = 0u;
+                rparts[i] = rp;
+            }
+    }
+}
+
 template <typename T>
 void launch(const void* x, const float* weight, const float* bias, const void* state_in, void* u, void* state_out, void* rparts,
             int64_t B, int64_t D, int64_t L, int W, hipStream_t stream)
@@ -317,6 +394,22 @@ void launch(const void* x, const float* weight, const float* bias, const void* s
     for (const void* p : {x, (const void*)u})
         if (reinterpret_cast<uintptr_t>(p) % 16 != 0) vector_ok = false;
     const int64_t rows = B * D;
+    if (L <= kShortL) {
+        int64_t nb = (rows + kThreads - 1) / kThreads;
+        nb = nb > COREY_RANGE_PARTS ? COREY_RANGE_PARTS : nb;
+        auto go_short = [&](auto kernel) {
+            kernel<<<dim3((unsigned)nb), dim3(kThreads), 0, stream>>>(
+                static_cast<const T*>(x), weight, bias, static_cast<const T*>(state_in), static_cast<T*>(u), static_cast<T*>(state_out),
+                static_cast<RangePart*>(rparts), rows, D, (int)L);
+        };
+        switch (W) {
+        case 1: go_short(k_conv1d_silu_short<T, 1>); break;
+        case 2: go_short(k_conv1d_silu_short<T, 2>); break;
+        case 3: go_short(k_conv1d_silu_short<T, 3>); break;
+        default: go_short(k_conv1d_silu_short<T, 4>); break;
+        }
+        return;
+    }
     const int64_t seg = (int64_t)kThreads * V;
     int64_t blocks = rows * ((L + seg - 1) / seg);
     blocks = blocks < 1 ? 1 : (blocks > COREY_RANGE_PARTS ? COREY_RANGE_PARTS : blocks);

@@ -175,3 +175,27 @@ def test_full_size_sampled_channels_and_whole_range(name):
     ref = oracle.entropy_hist(uf.cpu().numpy(), cfg.K)
     assert np.array_equal(counts_u32(fused["counts"]), ref["counts"])
     assert fused["H"].item() == pytest.approx(ref["H"][0], rel=1e-12)
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F32])
+def test_generation_steps_continue_the_prompt_bit_for_bit(dtype):
+    """A prompt through the vector path, then single steps from the carried state (the one-lane-per-row path): the same
+    bits as one call over the whole sequence, and the same carried state."""
+    P, T = 4096, 5
+    cfg = wl.Config(name="conv_gen", B=2, D=70, N=16, L=P + T, dtype=dtype, K=16, chunks=(64,), seed=21)
+    _say(f"conv prompt {P} + {T} steps {dtype}")
+    c = wl.make_conv(cfg, 4)
+    xd = to_dev(c["dev"]["x"], cfg.dtype)
+    wd, bd = torch.from_numpy(c["dev"]["weight"]).cuda(), torch.from_numpy(c["dev"]["bias"]).cuda()
+    whole, s_whole, _ = corey.causal_conv1d_silu_fwd(xd, wd, bd, want_state=True)
+    u0, state, _ = corey.causal_conv1d_silu_fwd(xd[:, :, :P].contiguous(), wd, bd, want_state=True)
+    outs = [u0]
+    for t in range(P, P + T):
+        ut, state, parts = corey.causal_conv1d_silu_fwd(xd[:, :, t:t + 1].contiguous(), wd, bd, state_in=state, want_state=True)
+        outs.append(ut)
+        lo, hi, nan = _parts_range(parts)
+        assert lo == ut.float().min().item() and hi == ut.float().max().item() and not nan
+    torch.cuda.synchronize()
+    view = torch.int16 if dtype == wl.BF16 else torch.int32
+    assert torch.equal(torch.cat(outs, dim=2).view(view), whole.view(view))
+    assert torch.equal(state.view(view), s_whole.view(view))
