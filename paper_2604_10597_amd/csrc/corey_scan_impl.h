@@ -83,14 +83,15 @@ template <int K, int CHUNK> struct Geo {
     static constexpr int STAGE = G * CHUNK;                     // floats per operand per staging buffer
 };
 
-// Time steps per lane.  16 halves the lane-scan work per value; 8 doubles the lanes and needs fewer registers (five
-// waves per SIMD instead of four), which pays when 16 would leave the chip short of waves: fewer than four per SIMD
-// (256 CUs x 4 SIMDs x 4 waves x 64 lanes = 262144 lanes), as long as a row still fits one wave (chunk <= 512).
-// Measured on the five benchmark layers and the paper's shape: the rule picks the faster of the two everywhere.
+// Time steps per lane.  16 halves the lane-scan work per value and doubles the rows that share a workgroup's staged
+// B / C; 8 doubles the lanes and needs fewer registers, which pays when 16 would leave the chip short of waves.
+// Measured on channel counts from 1024 to 16384 at chunks 128 ... 512 (several machines): 8 wins while 16 would give
+// fewer than about 2.6 waves per SIMD (256 CUs x 4 SIMDs x 64 lanes x 2.625 = 172032 lanes), as long as a row still
+// fits one wave (chunk <= 512); beyond that 16 is faster by 7 - 15 %.
 // The same rule runs on the host (known chunk) and on the device (per-sequence chunk read from memory); `rows` is B * D.
 __host__ __device__ inline int items_per_lane(int64_t rows, int chunk)
 {
-    return (chunk <= 512 && rows * (chunk / 16) < 262144) ? 8 : 16;
+    return (chunk <= 512 && rows * (chunk / 16) < 172032) ? 8 : 16;
 }
 
 // ------------------------------------------------------------------------------------------- storage types
