@@ -227,7 +227,8 @@ int causal_conv1d_silu_fwd(const void* x, const float* weight, const float* bias
  *                    without a host round trip; out-of-range or non-power-of-two entries fall back to `chunk`.
  *   last_state       DEVICE float[B, D, N], required.
  *   workspace        DEVICE, at least selective_scan_fwd_workspace(B, N, L) bytes, 16-byte aligned; scratch only
- *                    (the call first rewrites B and C there as fp32 in the order the scan reads them).
+ *                    (the call first rewrites B and C there as fp32 in the order, or the two orders, the scan reads
+ *                    them in).
  *   1 <= N <= COREY_MAX_STATE;  B*D*L and B*N*L must fit in int64 and B*D in int32.
  * y and last_state may not alias any input.  Accuracy against a double-precision evaluation of the same
  * bits: about 1e-6 relative to the row's scale for fp32 storage; for bf16 storage y carries one bf16
@@ -251,8 +252,10 @@ int selective_scan_fwd(const void* u, const void* delta, const float* A, const v
  * ----------------------------------------------------------------------------------------------------- */
 int corey_scan_structured_path(int enable);
 
-/* Bytes of workspace selective_scan_fwd needs (0 if the arguments are invalid): room for B and C as fp32,
- * padded along L to whole tiles and in N to a multiple of 4:  2 * B * roundup(N, 4) * roundup(L + 2048, 4) * 4. */
+/* Bytes of workspace selective_scan_fwd needs (0 if the arguments are invalid): room for B and C as fp32, padded
+ * along L to whole tiles and in N to a multiple of 4, in the two orders a launch may read them in (one launch can run
+ * some channels with 16 and the others with 8 time steps per lane):
+ * 4 * B * roundup(N, 4) * roundup(L + 2048, 4) * 4. */
 size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L);
 
 /* Message for the most recent failing call on this thread ("" if none).  Static storage; do not free. */

@@ -25,7 +25,7 @@ extern "C" int corey_scan_structured_path(int enable)
 extern "C" size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L)
 {
     if (B < 1 || N < 1 || N > COREY_MAX_STATE || L < 1) return 0;
-    return (size_t)2 * B * corey_scan::a_np(N) * padded_len(L) * sizeof(float);
+    return (size_t)4 * B * corey_scan::a_np(N) * padded_len(L) * sizeof(float);     // B and C, in two orders
 }
 
 extern "C" int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
@@ -64,6 +64,8 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.ws_B = static_cast<float*>(workspace);
     a.Np = corey_scan::a_np(N);
     a.ws_C = a.ws_B + (size_t)B * a.Np * a.Lpad;
+    a.ws_B8 = a.ws_C + (size_t)B * a.Np * a.Lpad;
+    a.ws_C8 = a.ws_B8 + (size_t)B * a.Np * a.Lpad;
     a.L = L; a.rows_total = B * D; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
     a.allow_structured = g_structured.load();
@@ -74,9 +76,10 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.rows_cap = rows_cap < 1 ? 1 : (rows_cap > 32 ? 32 : rows_cap);
 
     corey_scan::LaunchPlan p;
-    p.items = corey_scan::items_per_lane(B * D, chunk);
+    a.d16 = corey_scan::plan_d16(B, D, chunk, a.rows_cap);
 #ifdef COREY_DEV_KNOBS
-    if (const char* e = getenv("COREY_ITEMS")) p.items = atoi(e) == 8 ? 8 : 16;
+    if (const char* e = getenv("COREY_ITEMS")) a.d16 = (atoi(e) == 8 && chunk <= 512) ? 0 : D;
+    if (const char* e = getenv("COREY_D16")) a.d16 = chunk <= 512 ? (atoi(e) >= D ? D : atoi(e) / 32 * 32) : D;
 #endif
     p.chunk = chunk;
     p.routed = chunks_dev != nullptr;

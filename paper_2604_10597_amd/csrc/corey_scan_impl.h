@@ -83,15 +83,27 @@ template <int K, int CHUNK> struct Geo {
     static constexpr int STAGE = G * CHUNK;                     // floats per operand per staging buffer
 };
 
-// Time steps per lane.  16 halves the lane-scan work per value and doubles the rows that share a workgroup's staged
-// B / C; 8 doubles the lanes and needs fewer registers, which pays when 16 would leave the chip short of waves.
-// Measured on channel counts from 1024 to 16384 at chunks 128 ... 512 (several machines): 8 wins while 16 would give
-// fewer than about 2.6 waves per SIMD (256 CUs x 4 SIMDs x 64 lanes x 2.625 = 172032 lanes), as long as a row still
-// fits one wave (chunk <= 512); beyond that 16 is faster by 7 - 15 %.
-// The same rule runs on the host (known chunk) and on the device (per-sequence chunk read from memory); `rows` is B * D.
-__host__ __device__ inline int items_per_lane(int64_t rows, int chunk)
+// Time steps per lane, chosen per channel range.  16 steps halve the lane-scan work per value and stage B / C once for
+// twice as many rows of a workgroup; 8 steps double the waves per row and need fewer registers.  Measured on channel
+// counts 1024 ... 16384 at chunks 128 ... 512: while every row can have a wave of its own with all of them resident
+// (four waves per SIMD: 4096 waves), 8 steps win.  Beyond that the fastest launch gives the channels below d16 sixteen
+// steps, in whole layers of one workgroup per compute unit, and the remaining channels (less than one such layer)
+// eight: the two kinds of workgroups then fill the SIMDs evenly (e.g. 5120 rows at chunk 512: 4096 rows as two
+// 16-step waves per SIMD plus 1024 rows as one 8-step wave, 10 % faster than either geometry alone).
+// plan_d16 returns d16: channels [0, d16) of every sequence take 16 steps per lane, [d16, D) take 8; 0 and D are the
+// pure launches.  It runs on the host (known chunk) and on the device (chunk read from memory) with the same inputs.
+__host__ __device__ inline int64_t plan_d16(int64_t B, int64_t D, int chunk, int rows_cap)
 {
-    return (chunk <= 512 && rows * (chunk / 16) < 172032) ? 8 : 16;
+    if (chunk > 512) return D;                                   // a row of 8-step lanes would no longer fit one wave
+    if (chunk < 128)                                             // 16-step rows would leave workgroup lanes idle here
+        return (B * D * (chunk / 16) < 172032) ? 0 : D;
+    const int64_t waves8 = B * D * (chunk / 8) / 64;
+    if (waves8 <= 4096) return 0;
+    int rows16 = kBlock * 16 / chunk;                            // rows of a 16-step workgroup
+    rows16 = rows16 < rows_cap ? rows16 : rows_cap;
+    const int64_t layer = (int64_t)256 * rows16 / B / 32 * 32;   // channels per sequence in one workgroup per compute unit
+    if (layer < 32) return D;
+    return D / layer * layer;
 }
 
 // ------------------------------------------------------------------------------------------- storage types
@@ -330,6 +342,9 @@ struct ScanArgs {
     float* last_state;
     float* ws_B;            // relaid-out fp32 B, [B][N * Lpad]
     float* ws_C;
+    float* ws_B8;           // the same operands in the order of the 8-step geometries (ws_B / ws_C: the 16-step ones)
+    float* ws_C8;
+    int64_t d16;            // channels below d16 take 16 steps per lane, the others 8 (host chunk; see plan_d16)
     int64_t L, Lpad;
     int64_t rows_total;     // B * D (input of the items-per-lane rule)
     int32_t D, N;
@@ -359,49 +374,55 @@ __device__ __forceinline__ int resolve_chunk(const ScanArgs& a, int b)
 // are the padding states N..Np-1 (N here is the padded count Np): with B = C = 0 they contribute nothing.
 template <typename T>
 __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, const T* __restrict__ Cm, float* __restrict__ ws_B,
-                                                     float* __restrict__ ws_C, const int32_t* __restrict__ seqlens,
-                                                     const int32_t* __restrict__ chunks_dev, int chunk_host, int items_host,
-                                                     int64_t rows_total, int Nreal, int N, int64_t L, int64_t Lpad)
+                                                     float* __restrict__ ws_C, float* __restrict__ ws_B8, float* __restrict__ ws_C8,
+                                                     const int32_t* __restrict__ seqlens, const int32_t* __restrict__ chunks_dev,
+                                                     int chunk_host, int64_t d16_host, int64_t Bn, int64_t D, int rows_cap, int Nreal,
+                                                     int N, int64_t L, int64_t Lpad)
 {
     const int b = blockIdx.y;
     int chunk = chunk_host;
-    int K = items_host;
+    int64_t d16 = d16_host;
     if (chunks_dev) {
         const int c = chunks_dev[b];
         if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
-        K = items_per_lane(rows_total, chunk);
+        d16 = plan_d16(Bn, D, chunk, rows_cap);
     }
     int64_t len = L;
     if (seqlens) {
         const int64_t sl = seqlens[b];
         len = sl < 0 ? 0 : (sl > L ? L : sl);
     }
-    const int lpr = chunk / K;
     const int slots_log2 = __ffs(chunk / 4) - 1;                 // 16-byte slots per (tile, state)
-    const int lpr_log2 = __ffs(lpr) - 1;
     const int64_t ntiles = (len + chunk - 1) / chunk;            // tiles the scan will actually visit
     const int64_t total = (ntiles * N) << slots_log2;
     const T* Bs = Bm + (int64_t)b * Nreal * L;
     const T* Cs = Cm + (int64_t)b * Nreal * L;
-    float4v* oB = reinterpret_cast<float4v*>(ws_B + (int64_t)b * N * Lpad);
-    float4v* oC = reinterpret_cast<float4v*>(ws_C + (int64_t)b * N * Lpad);
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-        const int slot = (int)(i & ((1 << slots_log2) - 1));
-        const int64_t tn = i >> slots_log2;                      // tau * N + n
-        const int64_t tau = tn / N;
-        const int n = (int)(tn - tau * N);
-        const int j = slot & (lpr - 1);
-        const int q = slot >> lpr_log2;
-        const int64_t t = n < Nreal ? tau * chunk + (int64_t)j * K + q * 4 : len;     // padding states read nothing
-        const T* pb = Bs + (int64_t)n * L + t;
-        const T* pc = Cs + (int64_t)n * L + t;
-        float4v vb, vc;
-        vb.x = (t + 0 < len) ? Io<T>::ld(pb + 0) : 0.f; vb.y = (t + 1 < len) ? Io<T>::ld(pb + 1) : 0.f;
-        vb.z = (t + 2 < len) ? Io<T>::ld(pb + 2) : 0.f; vb.w = (t + 3 < len) ? Io<T>::ld(pb + 3) : 0.f;
-        vc.x = (t + 0 < len) ? Io<T>::ld(pc + 0) : 0.f; vc.y = (t + 1 < len) ? Io<T>::ld(pc + 1) : 0.f;
-        vc.z = (t + 2 < len) ? Io<T>::ld(pc + 2) : 0.f; vc.w = (t + 3 < len) ? Io<T>::ld(pc + 3) : 0.f;
-        oB[i] = vb;
-        oC[i] = vc;
+    for (int pass = 0; pass < 2; ++pass) {                       // the order of the 16-step rows, then that of the 8-step rows
+        const int K = pass == 0 ? 16 : 8;
+        if (pass == 0 ? d16 <= 0 : d16 >= D) continue;           // no channel of this sequence uses it
+        if (chunk < K) continue;
+        const int lpr = chunk / K;
+        const int lpr_log2 = __ffs(lpr) - 1;
+        float4v* oB = reinterpret_cast<float4v*>((pass == 0 ? ws_B : ws_B8) + (int64_t)b * N * Lpad);
+        float4v* oC = reinterpret_cast<float4v*>((pass == 0 ? ws_C : ws_C8) + (int64_t)b * N * Lpad);
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+            const int slot = (int)(i & ((1 << slots_log2) - 1));
+            const int64_t tn = i >> slots_log2;                  // tau * N + n
+            const int64_t tau = tn / N;
+            const int n = (int)(tn - tau * N);
+            const int j = slot & (lpr - 1);
+            const int q = slot >> lpr_log2;
+            const int64_t t = n < Nreal ? tau * chunk + (int64_t)j * K + q * 4 : len;     // padding states read nothing
+            const T* pb = Bs + (int64_t)n * L + t;
+            const T* pc = Cs + (int64_t)n * L + t;
+            float4v vb, vc;
+            vb.x = (t + 0 < len) ? Io<T>::ld(pb + 0) : 0.f; vb.y = (t + 1 < len) ? Io<T>::ld(pb + 1) : 0.f;
+            vb.z = (t + 2 < len) ? Io<T>::ld(pb + 2) : 0.f; vb.w = (t + 3 < len) ? Io<T>::ld(pb + 3) : 0.f;
+            vc.x = (t + 0 < len) ? Io<T>::ld(pc + 0) : 0.f; vc.y = (t + 1 < len) ? Io<T>::ld(pc + 1) : 0.f;
+            vc.z = (t + 2 < len) ? Io<T>::ld(pc + 2) : 0.f; vc.w = (t + 3 < len) ? Io<T>::ld(pc + 3) : 0.f;
+            oB[i] = vb;
+            oC[i] = vc;
+        }
     }
 }
 
@@ -479,8 +500,8 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     const T* dl_row = static_cast<const T*>(a.delta) + row * L;
     const T* z_row = a.z ? static_cast<const T*>(a.z) + row * L : nullptr;
     T* y_row = static_cast<T*>(a.y) + row * L;
-    const float* wsB = a.ws_B + (int64_t)b * N * a.Lpad;
-    const float* wsC = a.ws_C + (int64_t)b * N * a.Lpad;
+    const float* wsB = (K == 8 ? a.ws_B8 : a.ws_B) + (int64_t)b * N * a.Lpad;    // each geometry has its own order of B / C
+    const float* wsC = (K == 8 ? a.ws_C8 : a.ws_C) + (int64_t)b * N * a.Lpad;
     const float bias = (a.dbias && active) ? a.dbias[d] : 0.f;
     const float Dd = (a.Dv && active) ? a.Dv[d] : 0.f;
     const bool vec = a.vector_ok != 0;
@@ -718,10 +739,11 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
 // its grid from the host's hint and is correct for any chunk (more groups than workgroups: some take several in
 // turn; fewer: the surplus leaves at once).
 template <typename T, int K, int CHUNK>
-__device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem)
+__device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem, const int64_t d_first, const int64_t d_end,
+                                          const int64_t wg, const int64_t nwg)
 {
     const int rows = Geo<K, CHUNK>::ROWS < a.rows_cap ? Geo<K, CHUNK>::ROWS : a.rows_cap;
-    for (int64_t d0 = (int64_t)blockIdx.x * rows; d0 < a.D; d0 += (int64_t)gridDim.x * rows) {   // uniform over the workgroup
+    for (int64_t d0 = d_first + wg * rows; d0 < d_end; d0 += nwg * rows) {   // uniform over the workgroup
         bool structured = false;
         if constexpr (sizeof(T) == 2) {                      // fp32 storage keeps the one-exponential-per-state path
             if (a.allow_structured) {
@@ -749,7 +771,43 @@ template <typename T, int K, int CHUNK>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_target<K>()))) void k_scan(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
-    scan_rows<T, K, CHUNK>(a, s_mem);
+    scan_rows<T, K, CHUNK>(a, s_mem, 0, a.D, blockIdx.x, gridDim.x);
+}
+
+// Workgroup `wg` of `nwg` takes its share of one sequence's channels: those below d16 with 16 steps per lane (the first
+// g16 workgroups), the others with 8.  With a grid sized for exactly this split every workgroup has one row group;
+// any other grid is still correct (row groups are taken grid-stride within each kind).
+template <typename T, int CHUNK>
+__device__ __forceinline__ void scan_split(const ScanArgs& a, float* s_mem, const int64_t d16)
+{
+    const int rows16 = Geo<16, CHUNK>::ROWS < a.rows_cap ? Geo<16, CHUNK>::ROWS : a.rows_cap;
+    const int64_t n16 = (d16 + rows16 - 1) / rows16;
+    const int64_t nwg = gridDim.x;
+    if constexpr (CHUNK >= 8 && CHUNK <= 512) {
+        const int rows8 = Geo<8, CHUNK>::ROWS < a.rows_cap ? Geo<8, CHUNK>::ROWS : a.rows_cap;
+        const int64_t n8 = (a.D - d16 + rows8 - 1) / rows8;
+        int64_t g16 = n16;                                       // workgroups of the 16-step kind
+        if (n16 + n8 != nwg) {                                   // a grid sized for another chunk: share it in proportion
+            g16 = n8 == 0 ? nwg : (n16 == 0 ? 0 : (nwg * n16 + (n16 + n8) / 2) / (n16 + n8));
+            if (n16 > 0 && g16 < 1) g16 = 1;
+            if (n8 > 0 && g16 > nwg - 1) g16 = nwg - 1;
+        }
+        if ((int64_t)blockIdx.x < g16) {
+            if constexpr (CHUNK >= 16) scan_rows<T, 16, CHUNK>(a, s_mem, 0, d16, blockIdx.x, g16);
+        } else {
+            scan_rows<T, 8, CHUNK>(a, s_mem, d16, a.D, (int64_t)blockIdx.x - g16, nwg - g16);
+        }
+    } else {
+        scan_rows<T, 16, CHUNK>(a, s_mem, 0, a.D, blockIdx.x, nwg);
+    }
+}
+
+// Both kinds of workgroups in one launch (host chunk, 0 < d16 < D).
+template <typename T, int CHUNK>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WAVES_K16))) void k_scan_mix(const ScanArgs a)
+{
+    extern __shared__ float s_mem[];
+    scan_split<T, CHUNK>(a, s_mem, a.d16);
 }
 
 // Per-sequence chunk read from device memory: every geometry in one kernel, selected per workgroup (register budget
@@ -759,11 +817,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WA
 {
     extern __shared__ float s_mem[];
     const int chunk = resolve_chunk(a, blockIdx.y);
-    const int K = items_per_lane(a.rows_total, chunk);
+    const int64_t d16 = plan_d16(gridDim.y, a.D, chunk, a.rows_cap);
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        if (K == 8) { if constexpr (C >= 8) scan_rows<T, 8, C>(a, s_mem); }                 \
-        else { if constexpr (C >= 16) scan_rows<T, 16, C>(a, s_mem); }                      \
+        scan_split<T, C>(a, s_mem, d16);                                                    \
         break;
     switch (chunk) {
         COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
@@ -775,7 +832,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WA
 
 // ------------------------------------------------------------------------------------------- launch
 struct LaunchPlan {
-    int items;              // K when the chunk is known on the host
     int chunk;              // host chunk
     bool routed;            // per-sequence device chunks
     int64_t B, D, N;
@@ -785,20 +841,33 @@ struct LaunchPlan {
 inline int a_np(int64_t N) { return (int)((N + kMaxGroup - 1) / kMaxGroup * kMaxGroup); }
 
 template <int K, int CHUNK>
-inline void geometry(const LaunchPlan& p, int rows_cap, int64_t& gx, size_t& lds)
+inline void geometry(int64_t nrows, int64_t N, int rows_cap, int64_t& gx, size_t& lds)
 {
     int rows = Geo<K, CHUNK>::ROWS < rows_cap ? Geo<K, CHUNK>::ROWS : rows_cap;
-    gx = (p.D + rows - 1) / rows;
-    lds = (size_t)lds_floats<K, CHUNK>(rows, a_np(p.N)) * sizeof(float);
+    gx = (nrows + rows - 1) / rows;
+    lds = (size_t)lds_floats<K, CHUNK>(rows, a_np(N)) * sizeof(float);
 }
 
-template <typename T, int K, int CHUNK>
-inline void launch_one(const ScanArgs& a, const LaunchPlan& p)
+// Grid and LDS of a launch whose channels below d16 take 16 steps per lane and the others 8.
+template <int CHUNK>
+inline void split_geometry(const LaunchPlan& p, int rows_cap, int64_t d16, int64_t& gx, size_t& lds)
 {
-    int64_t gx;
-    size_t lds;
-    geometry<K, CHUNK>(p, a.rows_cap, gx, lds);
-    k_scan<T, K, CHUNK><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
+    gx = 0;
+    lds = 0;
+    int64_t g;
+    size_t l;
+    if (d16 > 0) {
+        geometry<16, CHUNK>(d16, p.N, rows_cap, g, l);
+        gx += g;
+        lds = l > lds ? l : lds;
+    }
+    if constexpr (CHUNK <= 512) {
+        if (d16 < p.D) {
+            geometry<8, CHUNK>(p.D - d16, p.N, rows_cap, g, l);
+            gx += g;
+            lds = l > lds ? l : lds;
+        }
+    }
 }
 
 template <typename T>
@@ -808,15 +877,15 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
     int64_t rb = (a.Np * a.Lpad / 4 + 255) / 256;
     rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
     k_relayout_bc<T><<<dim3((unsigned)rb, (unsigned)p.B), dim3(256), 0, p.stream>>>(
-        static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.seqlens, a.chunks_dev, p.chunk, p.items,
-        a.rows_total, (int)p.N, a.Np, a.L, a.Lpad);
+        static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.ws_B8, a.ws_C8, a.seqlens, a.chunks_dev,
+        p.chunk, a.d16, p.B, p.D, a.rows_cap, (int)p.N, a.Np, a.L, a.Lpad);
+    int64_t gx = 0, g;
+    size_t lds = 0, l;
     if (p.routed) {
         // grid from the host's chunk (the caller's hint: workgroups take row groups grid-stride, so any grid is correct),
-        // LDS for the largest need of any geometry the rule can pick
-        int64_t gx = 0, g;
-        size_t lds = 0, l;
+        // LDS for the largest need of any geometry the device-side plan can pick
 #define COREY_GEO(C)                                                                        \
-        if (items_per_lane(a.rows_total, C) == 8) geometry<8, C>(p, a.rows_cap, g, l); else geometry<16, C>(p, a.rows_cap, g, l); \
+        split_geometry<C>(p, a.rows_cap, plan_d16(p.B, p.D, C, a.rows_cap), g, l);          \
         lds = l > lds ? l : lds;                                                            \
         if (C == p.chunk) gx = g;
         COREY_GEO(16) COREY_GEO(32) COREY_GEO(64) COREY_GEO(128) COREY_GEO(256) COREY_GEO(512) COREY_GEO(1024) COREY_GEO(2048)
@@ -826,7 +895,12 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
     }
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        if (p.items == 8) launch_one<T, 8, C>(a, p); else launch_one<T, 16, C>(a, p);       \
+        split_geometry<C>(p, a.rows_cap, a.d16, gx, lds);                                   \
+        if (a.d16 >= p.D) k_scan<T, 16, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                  \
+        else if constexpr (C <= 512) {                                                      \
+            if (a.d16 <= 0) k_scan<T, 8, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                 \
+            else k_scan_mix<T, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                           \
+        }                                                                                   \
         break;
     switch (p.chunk) {
         COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)

@@ -111,5 +111,5 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
         assert ss(chunk=bad) == 1
     assert ss(N=0) == 3 and ss(N=257) == 3 and ss(B=0) == 3 and ss(L=0) == 3 and ss(B=70000) == 3
     assert ss(ws=none) == 7 and ss(wsb=64) == 7
-    assert lib.selective_scan_fwd_workspace(1, 16, 64) == 2 * 16 * (64 + 2048) * 4
+    assert lib.selective_scan_fwd_workspace(1, 16, 64) == 4 * 16 * (64 + 2048) * 4
     assert lib.selective_scan_fwd_workspace(0, 16, 64) == 0 and lib.selective_scan_fwd_workspace(1, 300, 64) == 0

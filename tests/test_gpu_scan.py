@@ -315,6 +315,32 @@ def test_closed_form_on_gpu_without_softplus():
     assert_close(last.cpu().numpy()[0, 0], h[-1], fp32_rtol(L), "geometric series state")
 
 
+@pytest.mark.parametrize("B,D,chunk", [(1, 4160, 512), (1, 6200, 512), (2, 2100, 512), (1, 8300, 256), (3, 1500, 512)])
+def test_launches_that_mix_both_lane_geometries(B, D, chunk):
+    """Channel counts beyond one resident wave per row: most channels run with 16 steps per lane, the remainder with 8, in
+    one launch (host chunk and device chunk).  Sampled channels from both parts and around the split against the oracle."""
+    cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], B=B, D=D, L=1536, seqlens=None)
+    _say(f"mixed geometries B{B} D{D} chunk {chunk}")
+    w = wl.make(cfg, a_kind="random")
+    d = upload(w)
+    layer = 256 * (4096 // chunk) // B // 32 * 32
+    split = D // layer * layer
+    assert 0 < split < D
+    rows = np.unique(np.clip(np.concatenate([[0, 1, split - 2, split - 1, split, split + 1, D - 1],
+                                             np.random.default_rng(D).integers(0, D, 10)]), 0, D - 1))
+    y_ref, s_ref = oracle_scan(w, rows=rows)
+    chunks_dev = torch.full((B,), chunk, dtype=torch.int32, device="cuda")
+    for routed in (False, True):
+        y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
+                                           delta_bias=d["delta_bias"], chunk=chunk if not routed else 64,
+                                           chunks_dev=chunks_dev if routed else None)
+        torch.cuda.synchronize()
+        ys = y[:, torch.from_numpy(rows).cuda(), :]
+        assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"y routed={routed}", store_bits(cfg))
+        assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"state routed={routed}")
+        assert torch.isfinite(y.float()).all()
+
+
 @pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b", "paper_w1_fp16"])
 def test_full_size_sampled_rows(name):
     """The benchmark's launch configuration at full size; the oracle recomputes sampled channels one by one."""
