@@ -19,7 +19,7 @@ STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
            "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
-           "selective_scan_fwd", "selective_scan_fwd_workspace", "corey_scan_structured_path", "corey_last_error", "corey_version")
+           "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "corey_scan_structured_path", "corey_last_error", "corey_version")
 
 
 class CoreyError(RuntimeError):
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_int, i64, i64, i64, i64, vp, ctypes.c_size_t, vp]
         L.corey_scan_structured_path.restype = ctypes.c_int
         L.corey_scan_structured_path.argtypes = [ctypes.c_int]
+        L.selective_scan_fwd_plan.restype = ctypes.c_int64
+        L.selective_scan_fwd_plan.argtypes = [i64, i64, i64, i32]
         L.selective_scan_fwd_workspace.restype = ctypes.c_size_t
         L.selective_scan_fwd_workspace.argtypes = [i64, i64, i64]
         L.corey_last_error.restype = ctypes.c_char_p
@@ -258,6 +260,10 @@ def corey_select_chunk_device(r_dev: torch.Tensor, L: int, policy: Policy | None
 def corey_scan_structured_path(enable: bool) -> bool:
     """Switch the structured-A fast path of selective_scan_fwd on or off; returns the previous setting."""
     return bool(lib().corey_scan_structured_path(1 if enable else 0))
+
+
+def selective_scan_fwd_plan(B: int, D: int, N: int, chunk: int) -> int:
+    return int(lib().selective_scan_fwd_plan(B, D, N, chunk))
 
 
 def selective_scan_fwd_workspace(B: int, N: int, L: int) -> int:

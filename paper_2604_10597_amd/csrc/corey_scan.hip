@@ -28,6 +28,15 @@ extern "C" size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L)
     return (size_t)4 * B * corey_scan::a_np(N) * padded_len(L) * sizeof(float);     // B and C, in two orders
 }
 
+extern "C" int64_t selective_scan_fwd_plan(int64_t B, int64_t D, int64_t N, int32_t chunk)
+{
+    if (B < 1 || D < 1 || N < 1 || N > COREY_MAX_STATE || chunk < COREY_MIN_CHUNK || chunk > COREY_MAX_CHUNK || !corey::is_pow2(chunk))
+        return -1;
+    int rows_cap = (int)(2048 / corey_scan::a_np(N));
+    rows_cap = rows_cap < 1 ? 1 : (rows_cap > 32 ? 32 : rows_cap);
+    return corey_scan::plan_d16(B, D, chunk, rows_cap);
+}
+
 extern "C" int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
                                   const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
                                   const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,

@@ -113,3 +113,22 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     assert ss(ws=none) == 7 and ss(wsb=64) == 7
     assert lib.selective_scan_fwd_workspace(1, 16, 64) == 4 * 16 * (64 + 2048) * 4
     assert lib.selective_scan_fwd_workspace(0, 16, 64) == 0 and lib.selective_scan_fwd_workspace(1, 300, 64) == 0
+
+
+def test_launch_plan_of_the_scan():
+    """Host logic of the scan's launch shape: which leading channels take 16 time steps per lane."""
+    plan = binding.selective_scan_fwd_plan
+    assert plan(0, 64, 16, 256) == -1 and plan(1, 64, 16, 100) == -1 and plan(1, 64, 300, 256) == -1
+    # every row can have a resident wave of its own: all rows with 8 steps per lane
+    assert plan(1, 64, 16, 256) == 0 and plan(1, 4096, 16, 512) == 0 and plan(1, 5120, 16, 256) == 0
+    # beyond that: whole layers of one workgroup per compute unit with 16 steps, the remainder with 8
+    assert plan(1, 5120, 16, 512) == 4096 and plan(1, 7168, 16, 512) == 6144 and plan(1, 6144, 16, 512) == 6144
+    assert plan(2, 2100, 16, 512) == 2048 and plan(1, 12288, 16, 256) == 12288 and plan(1, 10240, 16, 256) == 8192
+    # a row of 8-step lanes no longer fits a wave above chunk 512
+    assert plan(1, 64, 16, 1024) == 64 and plan(4, 2048, 16, 2048) == 2048
+    for B in (1, 2, 3, 5, 8):
+        for D in (1, 31, 32, 100, 1536, 4097, 5120, 9000, 40000):
+            for N in (1, 16, 64, 256):
+                for chunk in (16, 64, 128, 256, 512, 1024, 2048):
+                    d16 = plan(B, D, N, chunk)
+                    assert 0 <= d16 <= D and (d16 == D or d16 % 32 == 0), (B, D, N, chunk, d16)
