@@ -191,10 +191,11 @@ int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int6
  *     u[b,d,t] = v * sigmoid(v)                                                   stored in `dt`
  *
  * evaluated in binary32 (taps accumulated oldest first with fused multiply-adds).
- *   x, u        DEVICE [B, D, L] in `dt`; u may not alias x.
+ *   x, u        DEVICE [B, D, L] in `dt`; u may not overlap x (only u == x is detected: COREY_EINVAL).
  *   weight      DEVICE float[D, W], 1 <= W <= COREY_MAX_CONV.     bias: DEVICE float[D] or NULL.
  *   state_in    DEVICE [B, D, W-1] in `dt` or NULL: the W-1 inputs that precede t = 0 (oldest first).
- *   state_out   DEVICE [B, D, W-1] in `dt` or NULL: the last W-1 inputs (for continuing the sequence).
+ *   state_out   DEVICE [B, D, W-1] in `dt` or NULL: the last W-1 inputs (for continuing the sequence); may not
+ *               overlap state_in.
  *   range_parts DEVICE, COREY_RANGE_PARTS * 16 bytes, or NULL: partial minima / maxima (and a NaN flag) of the
  *               values of u *as stored*, for corey_entropy_hist / corey_route_device on this u.
  * Errors: COREY_ENULL, COREY_EINVAL (dtype, W), COREY_ESHAPE.
@@ -283,6 +284,7 @@ const char* corey_version(void);
  *               and h0, so a prompt's final state can be carried straight into generation).
  *   x, delta, z DEVICE [B, D] in `dt` (z may be NULL).   Bt, Ct: DEVICE [B, N] in `dt`.   y: DEVICE [B, D] in `dt`.
  *   A float[D, N], Dv and delta_bias float[D] or NULL, DEVICE.
+ * y may not alias an input; state is the only tensor that is both read and written.
  * Arithmetic in binary32 as in the scan; y is rounded once to `dt`.  Asynchronous on hip_stream; needs no workspace.
  * Errors: COREY_ENULL, COREY_EINVAL (dtype, misaligned state), COREY_ESHAPE (B, D < 1, N outside
  * [1, COREY_MAX_STATE], B*D >= 2^25), COREY_EHIP.
