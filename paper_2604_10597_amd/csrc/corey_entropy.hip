@@ -157,14 +157,24 @@ __device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, in
                         if (ph.take_and_advance()) f(Elem<T>::widen(v[e]));
                 }
             }
-        } else {
+        } else {                                               // the ragged end of a row: whole vectors where they fit
+#pragma unroll
             for (int k = 0; k < kUnroll; ++k) {
                 const int64_t t0 = seg0 + ((int64_t)k * kThreads + threadIdx.x) * V;
                 if (t0 >= g.len) break;
                 const int nvalid = (g.len - t0 < V) ? (int)(g.len - t0) : V;
                 SamplePhase ph(all ? 0 : r * g.len + t0, block, stride);
-                for (int e = 0; e < nvalid; ++e)
-                    if (all || ph.take_and_advance()) f(Elem<T>::widen(row[t0 + e]));
+                if (vector_ok && nvalid == V) {
+                    const vec4 raw = *reinterpret_cast<const vec4*>(row + t0);
+                    T v[V];
+                    __builtin_memcpy(v, &raw, kVecBytes);
+#pragma unroll
+                    for (int e = 0; e < V; ++e)
+                        if (all || ph.take_and_advance()) f(Elem<T>::widen(v[e]));
+                } else {
+                    for (int e = 0; e < nvalid; ++e)
+                        if (all || ph.take_and_advance()) f(Elem<T>::widen(row[t0 + e]));
+                }
             }
         }
     }
