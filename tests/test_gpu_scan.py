@@ -341,6 +341,27 @@ def test_launches_that_mix_both_lane_geometries(B, D, chunk):
         assert torch.isfinite(y.float()).all()
 
 
+def test_mixed_launch_with_padded_sequences_and_a_chunk_per_sequence():
+    """Two padded sequences routed to different chunks on the device: one of them splits its channels between both lane
+    geometries, the other does not; the grid comes from a third chunk given as the host's hint."""
+    B, D = 2, 2100
+    cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], B=B, D=D, L=1536, seqlens=(1536, 700))
+    _say(f"mixed geometries, padded, per-sequence chunks B{B} D{D}")
+    assert corey.selective_scan_fwd_plan(B, D, cfg.N, 512) == 2048 and corey.selective_scan_fwd_plan(B, D, cfg.N, 256) == 0
+    w = wl.make(cfg, a_kind="random")
+    d = upload(w)
+    rows = np.unique(np.concatenate([[0, 1, 2046, 2047, 2048, 2049, D - 1], np.random.default_rng(8).integers(0, D, 10)]))
+    y_ref, s_ref = oracle_scan(w, rows=rows)
+    chunks_dev = torch.tensor([512, 256], dtype=torch.int32, device="cuda")
+    y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
+                                       seqlens=d["seqlens"], chunk=128, chunks_dev=chunks_dev)
+    torch.cuda.synchronize()
+    ys = y[:, torch.from_numpy(rows).cuda(), :]
+    assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), "y", store_bits(cfg))
+    assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), "state")
+    assert (y[1, :, 700:] == 0).all()
+
+
 @pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b", "paper_w1_fp16"])
 def test_full_size_sampled_rows(name):
     """The benchmark's launch configuration at full size; the oracle recomputes sampled channels one by one."""
