@@ -224,9 +224,9 @@ def main() -> int:
     corey.corey_scan_structured_path(False)
 
     # ---- ceilings beside the HBM peak: what a plain device copy reaches on this machine, and the time the scan's own
-    # instruction stream needs at the measured issue rates (counts per wave-level state update from the committed
-    # counter summary; cycles per wave instruction from issue-rate probes: plain VALU 2.3 with both pipes of a SIMD fed,
-    # transcendental 8.2, not overlapping)
+    # instruction stream needs when every SIMD issues without a gap (counts per wave-level state update from the
+    # committed counter summary; a SIMD issues one plain wave64 fp32 instruction per 4 cycles and one transcendental per
+    # 8 -- packed fp32 instructions are not used -- as the same counters and register-only probes show)
     src = torch.empty(scan_bytes // 2, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
     for _ in range(3):
@@ -241,10 +241,12 @@ def main() -> int:
     copy_ms = ca.elapsed_time(cb) / 20
     del src, dst
     wave_updates = state_updates / 64.0
-    issue_cycles = wave_updates / 1024.0 * (7.8 * 2.3 + 1.32 * 8.2)          # per SIMD (256 CUs x 4)
+    issue_cycles = wave_updates / 1024.0 * (7.8 * 4.0 + 1.32 * 8.0)          # per SIMD (256 CUs x 4)
     ceilings = {"device_copy_GBps": round(scan_bytes / copy_ms * 1e-6, 1), "device_copy_ms_for_scan_bytes": round(copy_ms, 4),
                 "issue_model_ms_at_2p2GHz": round(issue_cycles / 2.2e9 * 1e3, 4),
-                "issue_model": "7.8 VALU x 2.3 cycles + 1.32 transcendental x 8.2 cycles per wave-level state update, 1024 SIMDs"}
+                "issue_model_ms_at_2p4GHz": round(issue_cycles / 2.4e9 * 1e3, 4),
+                "issue_model": "7.8 plain VALU x 4 cycles + 1.32 transcendental x 8 cycles per wave-level state update on 1024 SIMDs; "
+                               "the kernel is bound by this instruction count"}
 
     # ---- the producer of u (causal convolution + SiLU) with the range of u taken in the same pass: the statistic then
     # needs one sweep over u instead of two
@@ -400,6 +402,9 @@ def main() -> int:
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": round(scan_ms, 4)},
         "alu": {"achieved": round(scan_flop / scan_ms * 1e-9, 2), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(scan_flop / scan_ms * 1e-9 / FP32_VECTOR_PEAK_TFLOPS, 4),
+                "peak_plain_instructions": FP32_VECTOR_PEAK_TFLOPS / 2,      # 16 lanes per SIMD and cycle: packed fp32 is not used
+                "frac_plain_instructions": round(scan_flop / scan_ms * 1e-9 / (FP32_VECTOR_PEAK_TFLOPS / 2), 4),
+                "issue_utilisation_at_2p2GHz": round(issue_cycles / 2.2e9 * 1e3 / scan_ms, 4),
                 "flop_per_state_update": 7, "state_updates": state_updates},
         "overhead": {"entropy_routing_pct_of_scan": round((ms_step - scan_alone_ms) / scan_alone_ms * 100, 2),
                      "host_routed_ms_per_step": round(ms_step_host, 4),
