@@ -397,7 +397,7 @@ def main() -> int:
                    "scan_bytes": scan_bytes, "tokens": tokens},
         "tokens_per_s": round(tokens / ms_step * 1e3, 1),
         "routed_chunk": chunk, "r": [round(float(v), 6) for v in r_pinned],
-        "roofline": {"bound": "hbm", "kernel": "k_scan_any (selective_scan_fwd, device-routed chunk; the launch also holds k_relayout_bc, ~5 us)", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "k_scan_any (selective_scan_fwd, device-routed chunk; the launch also holds k_relayout_bc, ~6 us)", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "avg_launch_ms": round(scan_ms, 4)},
         "alu": {"achieved": round(scan_flop / scan_ms * 1e-9, 2), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
