@@ -381,3 +381,12 @@ def test_full_size_sampled_rows(name):
         assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y chunk {c}", store_bits(cfg))
         assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state chunk {c}")
         assert torch.isfinite(y.to(torch.float32)).all()
+    # the launch the benchmark times: statistic and rule on the GPU, the scan reading the chunk from device memory
+    _say(f"scan full size {name} device-routed")
+    route = corey.corey_route_device(d["u"], cfg.K, corey.policy_default(), seqlens=d["seqlens"])
+    y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
+                                       seqlens=d["seqlens"], chunk=chunk, chunks_dev=route["chunks"])
+    torch.cuda.synchronize()
+    ys = y[:, torch.from_numpy(rows).cuda(), :]
+    assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y device-routed", store_bits(cfg))
+    assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state device-routed")
