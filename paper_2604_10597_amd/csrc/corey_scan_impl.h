@@ -507,7 +507,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     const bool vec = a.vector_ok != 0;
     const bool sp = a.softplus != 0;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // uniform: addresses built from it stay in scalar registers
     const int jseg = lane & (SEG - 1);
     const int wpos = wave & (WPR - 1);                      // this wave's position inside its row
     const float* A2_row = s_A2 + rl * N;
