@@ -742,8 +742,9 @@ template <typename T, int K, int CHUNK>
 __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem, const int64_t d_first, const int64_t d_end,
                                           const int64_t wg, const int64_t nwg)
 {
-    const int rows = Geo<K, CHUNK>::ROWS < a.rows_cap ? Geo<K, CHUNK>::ROWS : a.rows_cap;
-    for (int64_t d0 = d_first + wg * rows; d0 < d_end; d0 += nwg * rows) {   // uniform over the workgroup
+    const int rows_full = Geo<K, CHUNK>::ROWS < a.rows_cap ? Geo<K, CHUNK>::ROWS : a.rows_cap;
+    for (int64_t d0 = d_first + wg * rows_full; d0 < d_end; d0 += nwg * rows_full) {   // uniform over the workgroup
+        const int rows = d_end - d0 < rows_full ? (int)(d_end - d0) : rows_full;     // the range's last group may be short
         bool structured = false;
         if constexpr (sizeof(T) == 2) {                      // fp32 storage keeps the one-exponential-per-state path
             if (a.allow_structured) {

@@ -315,16 +315,19 @@ def test_closed_form_on_gpu_without_softplus():
     assert_close(last.cpu().numpy()[0, 0], h[-1], fp32_rtol(L), "geometric series state")
 
 
-@pytest.mark.parametrize("B,D,chunk", [(1, 4160, 512), (1, 6200, 512), (2, 2100, 512), (1, 8300, 256), (3, 1500, 512)])
-def test_launches_that_mix_both_lane_geometries(B, D, chunk):
+@pytest.mark.parametrize("B,D,chunk,N", [(1, 4160, 512, 16), (1, 6200, 512, 16), (2, 2100, 512, 16), (1, 8300, 256, 16),
+                                          (3, 1500, 512, 16), (1, 4200, 512, 128), (3, 3000, 256, 200)])
+def test_launches_that_mix_both_lane_geometries(B, D, chunk, N):
     """Channel counts beyond one resident wave per row: most channels run with 16 steps per lane, the remainder with 8, in
     one launch (host chunk and device chunk).  Sampled channels from both parts and around the split against the oracle."""
-    cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], B=B, D=D, L=1536, seqlens=None)
-    _say(f"mixed geometries B{B} D{D} chunk {chunk}")
+    cfg = wl.scaled(wl.CONFIGS["c2_mamba370m"], B=B, D=D, L=1536 if N == 16 else 600, seqlens=None, N=N)
+    _say(f"mixed geometries B{B} D{D} N{N} chunk {chunk}")
     w = wl.make(cfg, a_kind="random")
     d = upload(w)
-    layer = 256 * (4096 // chunk) // B // 32 * 32
-    split = D // layer * layer
+    split = corey.selective_scan_fwd_plan(B, D, N, chunk)
+    if N == 16:
+        layer = 256 * (4096 // chunk) // B // 32 * 32
+        assert split == D // layer * layer
     assert 0 < split < D
     rows = np.unique(np.clip(np.concatenate([[0, 1, split - 2, split - 1, split, split + 1, D - 1],
                                              np.random.default_rng(D).integers(0, D, 10)]), 0, D - 1))
