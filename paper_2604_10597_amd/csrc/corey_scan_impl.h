@@ -891,6 +891,7 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
         if (C == p.chunk) gx = g;
         COREY_GEO(16) COREY_GEO(32) COREY_GEO(64) COREY_GEO(128) COREY_GEO(256) COREY_GEO(512) COREY_GEO(1024) COREY_GEO(2048)
 #undef COREY_GEO
+        if (gx < 2) gx = 2;     // a split decided on the device needs a workgroup for each kind (a surplus one leaves at once)
         k_scan_any<T><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
         return;
     }
