@@ -34,7 +34,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
 # HBM bytes per scan launch measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`, scaled by what the same counters
 # read for a 256 MiB device copy (profiles/hot_path_c4_mamba2p8b_counters.txt); not re-measured by this script
-MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 773_900_000}
+MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 769_300_000}
 
 
 def main() -> int:
@@ -241,11 +241,11 @@ def main() -> int:
     copy_ms = ca.elapsed_time(cb) / 20
     del src, dst
     wave_updates = state_updates / 64.0
-    issue_cycles = wave_updates / 1024.0 * (7.8 * 4.0 + 1.32 * 8.0)          # per SIMD (256 CUs x 4)
+    issue_cycles = wave_updates / 1024.0 * (7.6 * 4.0 + 1.32 * 8.0)          # per SIMD (256 CUs x 4)
     ceilings = {"device_copy_GBps": round(scan_bytes / copy_ms * 1e-6, 1), "device_copy_ms_for_scan_bytes": round(copy_ms, 4),
                 "issue_model_ms_at_2p2GHz": round(issue_cycles / 2.2e9 * 1e3, 4),
                 "issue_model_ms_at_2p4GHz": round(issue_cycles / 2.4e9 * 1e3, 4),
-                "issue_model": "7.8 plain VALU x 4 cycles + 1.32 transcendental x 8 cycles per wave-level state update on 1024 SIMDs; "
+                "issue_model": "7.6 plain VALU x 4 cycles + 1.32 transcendental x 8 cycles per wave-level state update on 1024 SIMDs; "
                                "the kernel is bound by this instruction count"}
 
     # ---- the producer of u (causal convolution + SiLU) with the range of u taken in the same pass: the statistic then
