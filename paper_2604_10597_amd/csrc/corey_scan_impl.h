@@ -438,8 +438,10 @@ __device__ __forceinline__ void stage_async(const float* __restrict__ srcB, cons
     for (int s0 = 0; s0 < SLOTS; s0 += kBlock) {
         const int s = s0 + wave * 64;
         if (SLOTS % kBlock == 0 || s + lane < SLOTS) {
-            __builtin_amdgcn_global_load_lds(srcB + (size_t)(s + lane) * 4, dstB + (size_t)s * 4, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(srcC + (size_t)(s + lane) * 4, dstC + (size_t)s * 4, 16, 0, 0);
+            // uniform base + 32-bit lane offset: the address needs no 64-bit vector arithmetic
+            const uint32_t voff = (uint32_t)(s + lane) * 4u;
+            __builtin_amdgcn_global_load_lds(srcB + voff, dstB + (size_t)s * 4, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(srcC + voff, dstC + (size_t)s * 4, 16, 0, 0);
         }
     }
 }
