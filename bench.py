@@ -9,7 +9,11 @@ memory (no host round trip inside a step).  Prints ONE JSON line.
   roofline   for the dominant kernel (the scan): algorithmic bytes / its own launch duration, measured with
              events on the launch stream inside the timed region, against the 8 TB/s HBM peak; the `alu` block
              beside it prices the same launches against the fp32 vector peak, which is the bound that binds
+  ceilings   a plain device copy of the same bytes on this machine, and the time the scan's own instruction count needs
+             at one plain wave64 instruction per 4 cycles and one transcendental per 8 on each SIMD
   per_chunk  scan-only latency, GB/s and tokens/s for every chunk of the sweep
+  producer   the causal convolution + SiLU that writes u and its range, and the statistic with and without that range
+  decode     one generated token (selective_state_update), eager calls and replayed from a HIP graph
   overhead   entropy + routing cost relative to the scan alone at the routed chunk, for the exact statistic (the
              timed step) and for the sampled one (every 8th block of 512 values, the paper's stride-8 variant at
              cache-line granularity), and with the chunk rule on the host instead
