@@ -21,6 +21,9 @@ memory (no host round trip inside a step).  Prints ONE JSON line.
              layers have that A; trained weights in general do not, so every other figure here is measured with the
              fast path switched off, i.e. one exponential per (channel, state, step))
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload on this host's cores
+  parity     this run's own outputs against what the oracle computed in that leg: histogram counts and routed chunk
+             equal (when the sample was the whole workload), worst error of y and of the final state over the
+             tolerance the parity tests use (below 1 passes)
 """
 from __future__ import annotations
 
@@ -376,9 +379,10 @@ def main() -> int:
             h = oracle.entropy_hist(p3(w.val["u"]), cfg.K, seqlens=w.seqlens)
             Ls = w.seqlens if w.seqlens is not None else [cfg.L]
             c = max(oracle.select_chunk(float(h["r"][i]), int(Ls[i]), oracle.policy())[1] for i in range(len(h["r"])))
-            oracle.selective_scan(p3(w.val["u"]), p3(w.val["delta"]), w.val["A"][sel], w.val["B"], w.val["C"],
-                                  Dv=w.val["D"][sel], z=p3(w.val["z"]), delta_bias=w.val["delta_bias"][sel],
-                                  seqlens=w.seqlens, chunk=c, threads=cores)
+            _, y_ref, s_ref = oracle.selective_scan(p3(w.val["u"]), p3(w.val["delta"]), w.val["A"][sel], w.val["B"], w.val["C"],
+                                                    Dv=w.val["D"][sel], z=p3(w.val["z"]), delta_bias=w.val["delta_bias"][sel],
+                                                    seqlens=w.seqlens, chunk=c, threads=cores)
+            oracle_pass.last = (sel, h, c, y_ref, s_ref)
             return time.perf_counter() - t
 
         probe_rows = min(cfg.D, 2 * cores)
@@ -390,6 +394,26 @@ def main() -> int:
                "tokens_per_s": round(tokens * frac / t_cpu, 1), "seconds": round(t_cpu, 2),
                "sample": f"{nrows} of {cfg.D} channels of {cfg.name} (all {tokens} tokens), histogram + chunk rule + scan, "
                          f"double precision, OpenMP over channels"}
+
+    # ---- parity of this very run against what the oracle just computed (the tests hold the full checks)
+    parity = None
+    if cpu is not None:
+        sel, h_ref, c_ref, y_ref, s_ref = oracle_pass.last
+        scan_routed()                                         # general path, exact statistic, device-routed chunk
+        torch.cuda.synchronize()
+        idx = torch.from_numpy(sel).cuda()
+        yg = y[:, idx, :].float().cpu().numpy().astype(np.float64)
+        sg = last[:, idx, :].cpu().numpy().astype(np.float64)
+        store = {"f32": 0.0, "bf16": 2.0 ** -8, "f16": 2.0 ** -11}[cfg.dtype]
+        rt = 1e-5 * max(1.0, (cfg.L / 256.0) ** 0.5)
+        yb = (3e-3 if cfg.dtype != "f32" else rt) * (np.abs(y_ref) + np.sqrt((y_ref ** 2).mean(-1, keepdims=True))) + store * np.abs(y_ref) + 1e-30
+        sb = rt * (np.abs(s_ref) + np.sqrt((s_ref ** 2).mean(-1, keepdims=True))) + 1e-30
+        parity = {"channels_checked": int(len(sel)),
+                  "counts_equal": bool(np.array_equal(ent["counts"].cpu().numpy().view(np.uint32).reshape(h_ref["counts"].shape),
+                                                      h_ref["counts"])) if len(sel) == cfg.D else None,
+                  "chunk_equal": bool(int(chunks_dev.max().item()) == c_ref) if len(sel) == cfg.D else None,
+                  "y_worst_error_over_tolerance": round(float((np.abs(yg - y_ref) / yb).max()), 3),
+                  "state_worst_error_over_tolerance": round(float((np.abs(sg - s_ref) / sb).max()), 3)}
 
     gbps = scan_bytes / scan_ms * 1e-6
     out = {
@@ -426,6 +450,7 @@ def main() -> int:
         "decode": decode,
         "paper_shape": paper_shape,
         "cpu_baseline": cpu,
+        "parity": parity,
     }
     print(json.dumps(out))
     return 0
