@@ -259,11 +259,14 @@ int corey_scan_structured_path(int enable);
  * 4 * B * roundup(N, 4) * roundup(L + 2048, 4) * 4. */
 size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L);
 
-/* How selective_scan_fwd shapes its launch for these sizes (host function, no GPU work; for inspection and tests): the
- * number d16 of leading channels of every sequence that are processed with 16 time steps per lane; the remaining
- * D - d16 channels take 8.  0 and D mean one lane geometry for all channels.  The split never changes results beyond
- * floating-point reassociation (each channel is an independent recurrence).  -1 if the arguments are invalid. */
+/* How selective_scan_fwd shapes its launch for these sizes (host functions, no GPU work; for inspection and tests).
+ * selective_scan_fwd_plan: the number d16 of leading channels of every sequence that are processed with 16 time steps
+ * per lane; the remaining D - d16 channels take selective_scan_fwd_plan_steps time steps per lane: 8, or 4 when the
+ * launch would otherwise leave most of the GPU without a wave (short tiles, few channels).  d16 = 0 or D means one lane
+ * geometry for all channels.  The shape never changes results beyond floating-point reassociation (each channel is an
+ * independent recurrence; the steps of a tile are combined by an associative scan).  -1 if the arguments are invalid. */
 int64_t selective_scan_fwd_plan(int64_t B, int64_t D, int64_t N, int32_t chunk);
+int32_t selective_scan_fwd_plan_steps(int64_t B, int64_t D, int64_t N, int32_t chunk);
 
 /* Message for the most recent failing call on this thread ("" if none).  Static storage; do not free. */
 const char* corey_last_error(void);

@@ -19,7 +19,7 @@ STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
            "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
-           "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "corey_scan_structured_path", "corey_last_error", "corey_version")
+           "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "corey_scan_structured_path", "corey_last_error", "corey_version")
 
 
 class CoreyError(RuntimeError):
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.corey_scan_structured_path.argtypes = [ctypes.c_int]
         L.selective_scan_fwd_plan.restype = ctypes.c_int64
         L.selective_scan_fwd_plan.argtypes = [i64, i64, i64, i32]
+        L.selective_scan_fwd_plan_steps.restype = i32
+        L.selective_scan_fwd_plan_steps.argtypes = [i64, i64, i64, i32]
         L.selective_scan_fwd_workspace.restype = ctypes.c_size_t
         L.selective_scan_fwd_workspace.argtypes = [i64, i64, i64]
         L.corey_last_error.restype = ctypes.c_char_p
@@ -264,6 +266,10 @@ def corey_scan_structured_path(enable: bool) -> bool:
 
 def selective_scan_fwd_plan(B: int, D: int, N: int, chunk: int) -> int:
     return int(lib().selective_scan_fwd_plan(B, D, N, chunk))
+
+
+def selective_scan_fwd_plan_steps(B: int, D: int, N: int, chunk: int) -> int:
+    return int(lib().selective_scan_fwd_plan_steps(B, D, N, chunk))
 
 
 def selective_scan_fwd_workspace(B: int, N: int, L: int) -> int:

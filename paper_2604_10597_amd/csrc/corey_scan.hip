@@ -37,6 +37,13 @@ extern "C" int64_t selective_scan_fwd_plan(int64_t B, int64_t D, int64_t N, int3
     return corey_scan::plan_d16(B, D, chunk, rows_cap);
 }
 
+extern "C" int32_t selective_scan_fwd_plan_steps(int64_t B, int64_t D, int64_t N, int32_t chunk)
+{
+    const int64_t d16 = selective_scan_fwd_plan(B, D, N, chunk);
+    if (d16 < 0) return -1;
+    return corey_scan::plan_klo(B, D, chunk, d16);
+}
+
 extern "C" int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
                                   const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
                                   const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
@@ -86,9 +93,17 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
 
     corey_scan::LaunchPlan p;
     a.d16 = corey_scan::plan_d16(B, D, chunk, a.rows_cap);
+    a.klo = corey_scan::plan_klo(B, D, chunk, a.d16);
 #ifdef COREY_DEV_KNOBS
-    if (const char* e = getenv("COREY_ITEMS")) a.d16 = (atoi(e) == 8 && chunk <= 512) ? 0 : D;
-    if (const char* e = getenv("COREY_D16")) a.d16 = chunk <= 512 ? (atoi(e) >= D ? D : atoi(e) / 32 * 32) : D;
+    if (const char* e = getenv("COREY_ITEMS")) {
+        const int k = atoi(e);
+        a.d16 = ((k == 8 && chunk <= 512) || (k == 4 && chunk <= 256)) ? 0 : D;
+        a.klo = a.d16 == 0 ? k : 8;
+    }
+    if (const char* e = getenv("COREY_D16")) {
+        a.d16 = chunk <= 512 ? (atoi(e) >= D ? D : atoi(e) / 32 * 32) : D;
+        a.klo = 8;
+    }
 #endif
     p.chunk = chunk;
     p.routed = chunks_dev != nullptr;

@@ -12,9 +12,9 @@
 // k_scan          A workgroup of 256 lanes owns ROWS channels of one sequence and walks the time axis in tiles of
 //                 CHUNK steps.  The tile geometry is a compile-time constant (one instantiation per chunk, chosen at
 //                 launch from the run-time chunk), so every LDS address in the inner loop is an immediate offset.
-//                 Inside a tile a row is spread over LPR = CHUNK / K consecutive lanes, each lane owning K (16 or 8)
-//                 consecutive time steps: loads of u / delta / z and the store of y are 16-byte vectors per lane,
-//                 contiguous along L.  The fp32 B / C values of a few states at a time are copied from the
+//                 Inside a tile a row is spread over LPR = CHUNK / K consecutive lanes, each lane owning K (16, 8 or
+//                 4) consecutive time steps: loads of u / delta / z and the store of y are one vector per lane (16 bytes
+//                 or more; 8 for four 16-bit values), contiguous along L.  The fp32 B / C values of a few states at a time are copied from the
 //                 workspace straight into LDS (global_load_lds, no registers), double buffered.  For every state
 //                 index n a lane
 //   1. discretises its K steps (a_i = exp2(dl_i A log2e), b_i = dl_i B_i u_i) and folds them, from a zero state,
@@ -68,6 +68,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef float float2v __attribute__((ext_vector_type(2)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // Geometry of one (K, CHUNK) instantiation.
@@ -77,7 +78,7 @@ template <int K, int CHUNK> struct Geo {
     static constexpr int SEG = LPR < 64 ? LPR : 64;             // lanes of a row inside one wave
     static constexpr int WPR = LPR > 64 ? LPR / 64 : 1;         // waves per row
     static constexpr int ROWS = kBlock / LPR;                   // rows per workgroup
-    static constexpr int kStageFloats = K == 8 ? COREY_STAGE_FLOATS_K8 : COREY_STAGE_FLOATS_K16;
+    static constexpr int kStageFloats = K < 16 ? COREY_STAGE_FLOATS_K8 : COREY_STAGE_FLOATS_K16;
     static constexpr int G = kStageFloats / CHUNK < 1 ? 1 : (kStageFloats / CHUNK > kMaxGroup ? kMaxGroup : kStageFloats / CHUNK);
     static_assert(kMaxGroup % G == 0, "the padded state count must be whole groups");
     static constexpr int STAGE = G * CHUNK;                     // floats per operand per staging buffer
@@ -104,6 +105,18 @@ __host__ __device__ inline int64_t plan_d16(int64_t B, int64_t D, int chunk, int
     const int64_t layer = (int64_t)256 * rows16 / B / 32 * 32;   // channels per sequence in one workgroup per compute unit
     if (layer < 32) return D;
     return D / layer * layer;
+}
+
+// Steps per lane of the channels that do not take 16 (all of them when d16 = 0): 8, or 4 when even 8-step rows leave
+// most SIMDs without a wave (short tiles or few channels: a row is only chunk / 8 lanes wide).  Halving the steps doubles
+// the lanes at the price of a longer lane scan per value.  Measured on 1024 ... 8192 channels at chunks 16 ... 512:
+// 4 steps win by 10 ... 35 % while the 8-step launch has at most about 1500 waves (1.5 per SIMD) and a 4-step row still
+// fits one wave (chunk <= 256); with 2 steps the lane scan costs more than the extra waves bring at chunks of 64 and up.
+constexpr int64_t kFewWaves = 1536;
+__host__ __device__ inline int plan_klo(int64_t B, int64_t D, int chunk, int64_t d16)
+{
+    if (d16 != 0 || chunk > 256) return 8;
+    return B * D * (chunk / 8) / 64 <= kFewWaves ? 4 : 8;
 }
 
 // ------------------------------------------------------------------------------------------- storage types
@@ -189,8 +202,9 @@ template <> struct Io<_Float16> {                         // IEEE binary16 stora
 };
 
 template <typename T, int K> struct Raw {
-    static constexpr int kWords = K / Io<T>::kVec;
-    uint4v w[kWords];
+    static constexpr int kBytes = K * (int)sizeof(T);           // 4 or 8 (short runs: one load), else whole 16-byte words
+    static constexpr int kWords = kBytes / 16 > 0 ? kBytes / 16 : 1;
+    uint4v w[kWords];                                          // a short run uses the first kBytes of w[0]
 };
 
 // K consecutive stored values starting at p (the first nvalid exist); missing ones read as zero bits.
@@ -199,7 +213,23 @@ __device__ __forceinline__ Raw<T, K> load_raw(const T* p, int nvalid, bool vecto
 {
     constexpr int V = Io<T>::kVec;
     Raw<T, K> r;
-    if (vector_ok && nvalid == K) {
+    if constexpr (Raw<T, K>::kBytes < 16) {                    // 2 or 4 values of a 16-bit type, 2 of binary32
+        r.w[0] = uint4v{0u, 0u, 0u, 0u};
+        if (vector_ok && nvalid == K) {
+            if constexpr (Raw<T, K>::kBytes == 8) {
+                const uint2v q = *reinterpret_cast<const uint2v*>(p);
+                r.w[0].x = q.x;
+                r.w[0].y = q.y;
+            } else {
+                r.w[0].x = *reinterpret_cast<const uint32_t*>(p);
+            }
+        } else {
+            T tmp[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) tmp[i] = (i < K && i < nvalid) ? p[i < K ? i : 0] : T(0);
+            __builtin_memcpy(&r.w[0], tmp, 16);
+        }
+    } else if (vector_ok && nvalid == K) {
         const uint4v* pv = reinterpret_cast<const uint4v*>(p);
 #pragma unroll
         for (int v = 0; v < Raw<T, K>::kWords; ++v) r.w[v] = pv[v];
@@ -216,15 +246,41 @@ __device__ __forceinline__ Raw<T, K> load_raw(const T* p, int nvalid, bool vecto
 template <typename T, int K>
 __device__ __forceinline__ void widen(const Raw<T, K>& r, float (&out)[K])
 {
+    if constexpr (Raw<T, K>::kBytes < 16) {
+        float all[Io<T>::kVec];
+        Io<T>::unpack(r.w[0], all);
 #pragma unroll
-    for (int v = 0; v < Raw<T, K>::kWords; ++v) Io<T>::unpack(r.w[v], &out[v * Io<T>::kVec]);
+        for (int i = 0; i < K; ++i) out[i] = all[i];
+    } else {
+#pragma unroll
+        for (int v = 0; v < Raw<T, K>::kWords; ++v) Io<T>::unpack(r.w[v], &out[v * Io<T>::kVec]);
+    }
 }
 
 template <typename T, int K>
 __device__ __forceinline__ void store_items(T* p, int nstore, bool vector_ok, const float (&v)[K])
 {
     constexpr int V = Io<T>::kVec;
-    if (vector_ok && nstore == K) {
+    if constexpr (Raw<T, K>::kBytes < 16) {
+        if (vector_ok && nstore == K) {
+            float all[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) all[i] = i < K ? v[i < K ? i : 0] : 0.f;
+            const uint4v q = Io<T>::pack(all);
+            if constexpr (Raw<T, K>::kBytes == 8) {
+                uint2v o;
+                o.x = q.x;
+                o.y = q.y;
+                *reinterpret_cast<uint2v*>(p) = o;
+            } else {
+                *reinterpret_cast<uint32_t*>(p) = q.x;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < K; ++i)
+                if (i < nstore) Io<T>::st(p + i, v[i]);
+        }
+    } else if (vector_ok && nstore == K) {
         uint4v* pv = reinterpret_cast<uint4v*>(p);
 #pragma unroll
         for (int k = 0; k < K / V; ++k) pv[k] = Io<T>::pack(&v[k * V]);
@@ -342,9 +398,10 @@ struct ScanArgs {
     float* last_state;
     float* ws_B;            // relaid-out fp32 B, [B][N * Lpad]
     float* ws_C;
-    float* ws_B8;           // the same operands in the order of the 8-step geometries (ws_B / ws_C: the 16-step ones)
+    float* ws_B8;           // the same operands in the order of the 8- or 4-step rows of this launch (ws_B / ws_C: the 16-step ones)
     float* ws_C8;
-    int64_t d16;            // channels below d16 take 16 steps per lane, the others 8 (host chunk; see plan_d16)
+    int64_t d16;            // channels below d16 take 16 steps per lane, the others klo (host chunk; see plan_d16)
+    int32_t klo;            // 8 or 4 (host chunk; see plan_klo)
     int64_t L, Lpad;
     int64_t rows_total;     // B * D (input of the items-per-lane rule)
     int32_t D, N;
@@ -376,16 +433,18 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, const T* __restrict__ Cm, float* __restrict__ ws_B,
                                                      float* __restrict__ ws_C, float* __restrict__ ws_B8, float* __restrict__ ws_C8,
                                                      const int32_t* __restrict__ seqlens, const int32_t* __restrict__ chunks_dev,
-                                                     int chunk_host, int64_t d16_host, int64_t Bn, int64_t D, int rows_cap, int Nreal,
-                                                     int N, int64_t L, int64_t Lpad)
+                                                     int chunk_host, int64_t d16_host, int klo_host, int64_t Bn, int64_t D, int rows_cap,
+                                                     int Nreal, int N, int64_t L, int64_t Lpad)
 {
     const int b = blockIdx.y;
     int chunk = chunk_host;
     int64_t d16 = d16_host;
+    int klo = klo_host;
     if (chunks_dev) {
         const int c = chunks_dev[b];
         if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
         d16 = plan_d16(Bn, D, chunk, rows_cap);
+        klo = plan_klo(Bn, D, chunk, d16);
     }
     int64_t len = L;
     if (seqlens) {
@@ -397,8 +456,8 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
     const int64_t total = (ntiles * N) << slots_log2;
     const T* Bs = Bm + (int64_t)b * Nreal * L;
     const T* Cs = Cm + (int64_t)b * Nreal * L;
-    for (int pass = 0; pass < 2; ++pass) {                       // the order of the 16-step rows, then that of the 8-step rows
-        const int K = pass == 0 ? 16 : 8;
+    for (int pass = 0; pass < 2; ++pass) {                       // the order of the 16-step rows, then that of the others
+        const int K = pass == 0 ? 16 : (klo == 8 ? 8 : 4);       // 4 or fewer steps per lane read B / C in time order
         if (pass == 0 ? d16 <= 0 : d16 >= D) continue;           // no channel of this sequence uses it
         if (chunk < K) continue;
         const int lpr = chunk / K;
@@ -464,7 +523,10 @@ template <typename T, int K, int CHUNK, bool STRUCT>
 __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, const int rows, const int d0)
 {
     using Gm = Geo<K, CHUNK>;
-    constexpr int LPR = Gm::LPR, SEG = Gm::SEG, WPR = Gm::WPR, G = Gm::G, STAGE = Gm::STAGE, KQ = K / 4;
+    constexpr int LPR = Gm::LPR, SEG = Gm::SEG, WPR = Gm::WPR, G = Gm::G, STAGE = Gm::STAGE;
+    constexpr int E = K < 4 ? K : 4;                        // staged B / C values a lane reads per LDS instruction
+    constexpr int KQ = K / E;
+    typedef float BCv __attribute__((ext_vector_type(E)));
 
     const int b = blockIdx.y;
     const int tid = threadIdx.x;
@@ -496,14 +558,15 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
         s_A2[i] = ok ? a.A[(int64_t)dd * Nreal + n] * kLog2e : 0.f;
     }
     for (int i = tid; i < N; i += kBlock) s_zero[i] = 0.f;
+    __syncthreads();                                        // the first tile reads A before any other barrier (STRUCT)
 
     const int64_t row = (int64_t)b * a.D + (active ? d : d0);
     const T* u_row = static_cast<const T*>(a.u) + row * L;
     const T* dl_row = static_cast<const T*>(a.delta) + row * L;
     const T* z_row = a.z ? static_cast<const T*>(a.z) + row * L : nullptr;
     T* y_row = static_cast<T*>(a.y) + row * L;
-    const float* wsB = (K == 8 ? a.ws_B8 : a.ws_B) + (int64_t)b * N * a.Lpad;    // each geometry has its own order of B / C
-    const float* wsC = (K == 8 ? a.ws_C8 : a.ws_C) + (int64_t)b * N * a.Lpad;
+    const float* wsB = (K < 16 ? a.ws_B8 : a.ws_B) + (int64_t)b * N * a.Lpad;    // each kind of row has its own order of B / C
+    const float* wsC = (K < 16 ? a.ws_C8 : a.ws_C) + (int64_t)b * N * a.Lpad;
     const float bias = (a.dbias && active) ? a.dbias[d] : 0.f;
     const float Dd = (a.Dv && active) ? a.Dv[d] : 0.f;
     const bool vec = a.vector_ok != 0;
@@ -521,9 +584,9 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     int buf = 0;                                            // staging buffer holding the group about to be used
     if (len > 0) stage_async<STAGE>(wsB, wsC, s_stage, s_stage + STAGE, wave, lane);
 
-    // Geometries with 8 steps per lane have the registers to fetch the next tile's u / delta / z while the last
+    // Geometries with at most 8 steps per lane have the registers to fetch the next tile's u / delta / z while the last
     // group of states of the current tile is computed, which takes the HBM latency out of every tile's start.
-    constexpr bool kTileAhead = K == 8;
+    constexpr bool kTileAhead = K <= 8;
     Raw<T, K> u_nx, d_nx, z_nx;
     bool have_nx = false;                                   // uniform over the workgroup
     const int64_t ntiles = (len + CHUNK - 1) / CHUNK;
@@ -610,13 +673,13 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 }
             }
             buf ^= 1;
-            const float4v* bq0 = reinterpret_cast<const float4v*>(s_B) + j;
-            const float4v* cq0 = reinterpret_cast<const float4v*>(s_C) + j;
+            const BCv* bq0 = reinterpret_cast<const BCv*>(s_B) + j;
+            const BCv* cq0 = reinterpret_cast<const BCv*>(s_C) + j;
             constexpr bool kEarlyC = K <= COREY_CPREFETCH_MAXK;   // C is requested before the lane scan, which covers the LDS latency
             auto one_state = [&](const int nl, const int n) __attribute__((always_inline)) {
                 const float cin = carry_rd[n];              // carried state for the first lane of the row, 0 elsewhere
-                const float4v* bq = bq0 + nl * KQ * LPR;
-                const float4v* cq = cq0 + nl * KQ * LPR;
+                const BCv* bq = bq0 + nl * KQ * LPR;
+                const BCv* cq = cq0 + nl * KQ * LPR;
                 float A2 = 0.f;
                 if constexpr (!STRUCT) A2 = A2_row[n];
 
@@ -626,13 +689,12 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 if constexpr (STRUCT) {
 #pragma unroll
                     for (int q = 0; q < KQ; ++q) {
-                        const float4v b4 = bq[q * LPR];
-                        const float be[4] = {b4.x, b4.y, b4.z, b4.w};
+                        const BCv b4 = bq[q * LPR];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int i = 4 * q + e;
+                        for (int e = 0; e < E; ++e) {
+                            const int i = E * q + e;
                             av[i] *= dl[i];                 // decay of state n from that of state n - 1
-                            bv[i] = du[i] * be[e];
+                            bv[i] = du[i] * b4[e];
                             h = fmaf(av[i], h, bv[i]);
                         }
                     }
@@ -641,19 +703,18 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 } else {
 #pragma unroll
                     for (int q = 0; q < KQ; ++q) {
-                        const float4v b4 = bq[q * LPR];
-                        const float be[4] = {b4.x, b4.y, b4.z, b4.w};
+                        const BCv b4 = bq[q * LPR];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int i = 4 * q + e;
+                        for (int e = 0; e < E; ++e) {
+                            const int i = E * q + e;
                             av[i] = fast_exp2(dl[i] * A2);
-                            bv[i] = du[i] * be[e];
+                            bv[i] = du[i] * b4[e];
                             h = fmaf(av[i], h, bv[i]);
                         }
                     }
                     P = fast_exp2(S * A2);
                 }
-                float4v cv[KQ];
+                BCv cv[KQ];
                 if constexpr (kEarlyC) {
 #pragma unroll
                     for (int q = 0; q < KQ; ++q) cv[q] = cq[q * LPR];
@@ -680,13 +741,12 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 }
 #pragma unroll
                 for (int q = 0; q < KQ; ++q) {
-                    const float4v c4 = kEarlyC ? cv[q] : cq[q * LPR];
-                    const float ce[4] = {c4.x, c4.y, c4.z, c4.w};
+                    const BCv c4 = kEarlyC ? cv[q] : cq[q * LPR];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int i = 4 * q + e;
+                    for (int e = 0; e < E; ++e) {
+                        const int i = E * q + e;
                         hh = fmaf(av[i], hh, bv[i]);
-                        yv[i] = fmaf(ce[e], hh, yv[i]);
+                        yv[i] = fmaf(c4[e], hh, yv[i]);
                     }
                 }
             };
@@ -765,9 +825,9 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem, const
     }
 }
 
-// Register budget: K = 16 keeps 16 x (dl, du, y, a, b) per lane and is built for four waves per SIMD (128 VGPRs);
-// K = 8 for five.
-template <int K> constexpr int waves_target() { return K == 8 ? COREY_WAVES_K8 : COREY_WAVES_K16; }
+// Register budget: K = 16 keeps 16 x (dl, du, y, a, b) per lane and is built for four waves per SIMD (128 VGPRs), and
+// so are the shorter lanes (their spare registers hold the tile fetched ahead).
+template <int K> constexpr int waves_target() { return K < 16 ? COREY_WAVES_K8 : COREY_WAVES_K16; }
 
 // One geometry, chosen on the host from the run-time chunk.
 template <typename T, int K, int CHUNK>
@@ -780,14 +840,26 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_ta
 // Workgroup `wg` of `nwg` takes its share of one sequence's channels: those below d16 with 16 steps per lane (the first
 // g16 workgroups), the others with 8.  With a grid sized for exactly this split every workgroup has one row group;
 // any other grid is still correct (row groups are taken grid-stride within each kind).
-template <typename T, int CHUNK>
-__device__ __forceinline__ void scan_split(const ScanArgs& a, float* s_mem, const int64_t d16)
+template <int K, int CHUNK> constexpr bool geometry_exists()
 {
-    const int rows16 = Geo<16, CHUNK>::ROWS < a.rows_cap ? Geo<16, CHUNK>::ROWS : a.rows_cap;
+    return CHUNK >= K && (K == 16 || (K == 8 && CHUNK <= 512) || (K == 4 && CHUNK <= 256));
+}
+
+template <int CHUNK> __host__ __device__ inline int rows_of(int K, int rows_cap)
+{
+    const int lpr = CHUNK / K < 1 ? 1 : CHUNK / K;
+    const int rows = kBlock / lpr;
+    return rows < rows_cap ? rows : rows_cap;
+}
+
+template <typename T, int CHUNK>
+__device__ __forceinline__ void scan_split(const ScanArgs& a, float* s_mem, const int64_t d16, const int klo)
+{
+    const int rows16 = rows_of<CHUNK>(16, a.rows_cap);
     const int64_t n16 = (d16 + rows16 - 1) / rows16;
     const int64_t nwg = gridDim.x;
-    if constexpr (CHUNK >= 8 && CHUNK <= 512) {
-        const int rows8 = Geo<8, CHUNK>::ROWS < a.rows_cap ? Geo<8, CHUNK>::ROWS : a.rows_cap;
+    if constexpr (CHUNK <= 512) {
+        const int rows8 = rows_of<CHUNK>(klo, a.rows_cap);
         const int64_t n8 = (a.D - d16 + rows8 - 1) / rows8;
         int64_t g16 = n16;                                       // workgroups of the 16-step kind
         if (n16 + n8 != nwg) {                                   // a grid sized for another chunk: share it in proportion
@@ -795,10 +867,13 @@ __device__ __forceinline__ void scan_split(const ScanArgs& a, float* s_mem, cons
             if (n16 > 0 && g16 < 1) g16 = 1;
             if (n8 > 0 && g16 > nwg - 1) g16 = nwg - 1;
         }
+        const int64_t wg = (int64_t)blockIdx.x - g16;
         if ((int64_t)blockIdx.x < g16) {
-            if constexpr (CHUNK >= 16) scan_rows<T, 16, CHUNK>(a, s_mem, 0, d16, blockIdx.x, g16);
+            if constexpr (geometry_exists<16, CHUNK>()) scan_rows<T, 16, CHUNK>(a, s_mem, 0, d16, blockIdx.x, g16);
+        } else if (klo == 8) {
+            if constexpr (geometry_exists<8, CHUNK>()) scan_rows<T, 8, CHUNK>(a, s_mem, d16, a.D, wg, nwg - g16);
         } else {
-            scan_rows<T, 8, CHUNK>(a, s_mem, d16, a.D, (int64_t)blockIdx.x - g16, nwg - g16);
+            if constexpr (geometry_exists<4, CHUNK>()) scan_rows<T, 4, CHUNK>(a, s_mem, d16, a.D, wg, nwg - g16);
         }
     } else {
         scan_rows<T, 16, CHUNK>(a, s_mem, 0, a.D, blockIdx.x, nwg);
@@ -810,7 +885,7 @@ template <typename T, int CHUNK>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WAVES_K16))) void k_scan_mix(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
-    scan_split<T, CHUNK>(a, s_mem, a.d16);
+    scan_split<T, CHUNK>(a, s_mem, a.d16, a.klo);
 }
 
 // Per-sequence chunk read from device memory: every geometry in one kernel, selected per workgroup (register budget
@@ -821,9 +896,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WA
     extern __shared__ float s_mem[];
     const int chunk = resolve_chunk(a, blockIdx.y);
     const int64_t d16 = plan_d16(gridDim.y, a.D, chunk, a.rows_cap);
+    const int klo = plan_klo(gridDim.y, a.D, chunk, d16);
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        scan_split<T, C>(a, s_mem, d16);                                                    \
+        scan_split<T, C>(a, s_mem, d16, klo);                                               \
         break;
     switch (chunk) {
         COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
@@ -846,30 +922,33 @@ inline int a_np(int64_t N) { return (int)((N + kMaxGroup - 1) / kMaxGroup * kMax
 template <int K, int CHUNK>
 inline void geometry(int64_t nrows, int64_t N, int rows_cap, int64_t& gx, size_t& lds)
 {
-    int rows = Geo<K, CHUNK>::ROWS < rows_cap ? Geo<K, CHUNK>::ROWS : rows_cap;
-    gx = (nrows + rows - 1) / rows;
-    lds = (size_t)lds_floats<K, CHUNK>(rows, a_np(N)) * sizeof(float);
+    gx = 0;
+    lds = 0;
+    if constexpr (geometry_exists<K, CHUNK>()) {
+        int rows = Geo<K, CHUNK>::ROWS < rows_cap ? Geo<K, CHUNK>::ROWS : rows_cap;
+        gx = (nrows + rows - 1) / rows;
+        lds = (size_t)lds_floats<K, CHUNK>(rows, a_np(N)) * sizeof(float);
+    }
 }
 
-// Grid and LDS of a launch whose channels below d16 take 16 steps per lane and the others 8.
+// Grid and LDS of a launch whose channels below d16 take 16 steps per lane and the others klo.
 template <int CHUNK>
-inline void split_geometry(const LaunchPlan& p, int rows_cap, int64_t d16, int64_t& gx, size_t& lds)
+inline void split_geometry(const LaunchPlan& p, int rows_cap, int64_t d16, int klo, int64_t& gx, size_t& lds)
 {
     gx = 0;
     lds = 0;
-    int64_t g;
-    size_t l;
+    int64_t g = 0;
+    size_t l = 0;
     if (d16 > 0) {
         geometry<16, CHUNK>(d16, p.N, rows_cap, g, l);
         gx += g;
         lds = l > lds ? l : lds;
     }
-    if constexpr (CHUNK <= 512) {
-        if (d16 < p.D) {
-            geometry<8, CHUNK>(p.D - d16, p.N, rows_cap, g, l);
-            gx += g;
-            lds = l > lds ? l : lds;
-        }
+    if (d16 < p.D) {
+        if (klo == 8) geometry<8, CHUNK>(p.D - d16, p.N, rows_cap, g, l);
+        else geometry<4, CHUNK>(p.D - d16, p.N, rows_cap, g, l);
+        gx += g;
+        lds = l > lds ? l : lds;
     }
 }
 
@@ -881,14 +960,17 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
     rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
     k_relayout_bc<T><<<dim3((unsigned)rb, (unsigned)p.B), dim3(256), 0, p.stream>>>(
         static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.ws_B8, a.ws_C8, a.seqlens, a.chunks_dev,
-        p.chunk, a.d16, p.B, p.D, a.rows_cap, (int)p.N, a.Np, a.L, a.Lpad);
+        p.chunk, a.d16, a.klo, p.B, p.D, a.rows_cap, (int)p.N, a.Np, a.L, a.Lpad);
     int64_t gx = 0, g;
     size_t lds = 0, l;
     if (p.routed) {
         // grid from the host's chunk (the caller's hint: workgroups take row groups grid-stride, so any grid is correct),
         // LDS for the largest need of any geometry the device-side plan can pick
 #define COREY_GEO(C)                                                                        \
-        split_geometry<C>(p, a.rows_cap, plan_d16(p.B, p.D, C, a.rows_cap), g, l);          \
+        {                                                                                   \
+            const int64_t d16_c = plan_d16(p.B, p.D, C, a.rows_cap);                        \
+            split_geometry<C>(p, a.rows_cap, d16_c, plan_klo(p.B, p.D, C, d16_c), g, l);    \
+        }                                                                                   \
         lds = l > lds ? l : lds;                                                            \
         if (C == p.chunk) gx = g;
         COREY_GEO(16) COREY_GEO(32) COREY_GEO(64) COREY_GEO(128) COREY_GEO(256) COREY_GEO(512) COREY_GEO(1024) COREY_GEO(2048)
@@ -897,13 +979,17 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
         k_scan_any<T><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
         return;
     }
+#define COREY_LAUNCH(K, C)                                                                  \
+    if constexpr (geometry_exists<K, C>())                                                  \
+        k_scan<T, K, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a)
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        split_geometry<C>(p, a.rows_cap, a.d16, gx, lds);                                   \
-        if (a.d16 >= p.D) k_scan<T, 16, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                  \
+        split_geometry<C>(p, a.rows_cap, a.d16, a.klo, gx, lds);                            \
+        if (a.d16 >= p.D) { COREY_LAUNCH(16, C); }                                          \
         else if constexpr (C <= 512) {                                                      \
-            if (a.d16 <= 0) k_scan<T, 8, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                 \
-            else k_scan_mix<T, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                           \
+            if (a.d16 > 0) k_scan_mix<T, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                 \
+            else if (a.klo == 8) { COREY_LAUNCH(8, C); }                                    \
+            else { COREY_LAUNCH(4, C); }                                                    \
         }                                                                                   \
         break;
     switch (p.chunk) {
@@ -912,6 +998,7 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
     default: break;
     }
 #undef COREY_CASE
+#undef COREY_LAUNCH
 }
 
 }  // namespace corey_scan

@@ -132,3 +132,11 @@ def test_launch_plan_of_the_scan():
                 for chunk in (16, 64, 128, 256, 512, 1024, 2048):
                     d16 = plan(B, D, N, chunk)
                     assert 0 <= d16 <= D and (d16 == D or d16 % 32 == 0), (B, D, N, chunk, d16)
+                    steps = binding.selective_scan_fwd_plan_steps(B, D, N, chunk)
+                    assert steps in (4, 8) and (steps == 8 or (d16 == 0 and chunk <= 256)), (B, D, N, chunk, d16, steps)
+    # short of waves (few channels or short tiles, a 4-step row still inside one wave): 4 steps per lane
+    steps = binding.selective_scan_fwd_plan_steps
+    assert steps(0, 64, 16, 256) == -1 and steps(1, 64, 16, 100) == -1
+    assert steps(1, 1536, 16, 256) == 4 and steps(1, 1536, 16, 512) == 8 and steps(1, 5120, 16, 128) == 4
+    assert steps(1, 5120, 16, 256) == 8 and steps(4, 2048, 16, 64) == 4 and steps(4, 2048, 16, 128) == 8
+    assert steps(1, 13000, 16, 64) == 8 and plan(1, 13000, 16, 64) == 0 and steps(1, 50000, 16, 16) == 8
