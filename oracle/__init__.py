@@ -72,8 +72,9 @@ def _i32(a):
     return a, a.ctypes.data_as(ctypes.c_void_p)
 
 
-def entropy_hist(x, K, eps=1e-8, stride=1, seqlens=None, block=1):
-    """x: float array [B, D, L] (already widened).  Returns dict(status, counts, H, r, lo, hi)."""
+def entropy_hist(x, K, eps=1e-8, stride=1, seqlens=None, block=1, range_all=False):
+    """x: float array [B, D, L] (already widened).  Returns dict(status, counts, H, r, lo, hi).
+    range_all: bins bounded by the minimum / maximum of all values rather than of the sampled ones."""
     x = np.asarray(x)
     if x.ndim != 3:
         raise ValueError("x must be [B, D, L]")
@@ -88,7 +89,7 @@ def entropy_hist(x, K, eps=1e-8, stride=1, seqlens=None, block=1):
     hi = np.zeros(nh, dtype=np.float32)
     st = lib().oracle_entropy_hist(
         xp, ctypes.c_int64(B), ctypes.c_int64(D), ctypes.c_int64(L), sp, ctypes.c_int32(K),
-        ctypes.c_double(eps), ctypes.c_int64(stride), ctypes.c_int64(block),
+        ctypes.c_double(eps), ctypes.c_int64(stride), ctypes.c_int64(block), ctypes.c_int32(1 if range_all else 0),
         counts.ctypes.data_as(ctypes.c_void_p), H.ctypes.data_as(ctypes.c_void_p),
         r.ctypes.data_as(ctypes.c_void_p), lo.ctypes.data_as(ctypes.c_void_p),
         hi.ctypes.data_as(ctypes.c_void_p))

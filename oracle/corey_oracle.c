@@ -78,10 +78,15 @@ enum {
  *          stride 1 is the exact statistic; stride 8 with block 1 is the paper's sampled variant ("sampled
  *          histogram (stride 8)" of the routed ablation, which does not say along which axis it strides: memory
  *          order is the reading taken); block > 1 samples whole runs of memory instead of single elements.
+ * range_all  0: lo and hi are the minimum and maximum of the sampled values.  1: of all valid values of the
+ *          histogram, sampled or not (the paper does not say which values bound the bins of its sampled
+ *          variant; this second reading is what a producer that tracks min / max while it writes the tensor
+ *          hands over).  A NaN among the values the range is taken over makes the statistic non-finite.
+ *          With stride 1 the two are the same.
  * counts   uint32[nh][K] out.   H, r: double[nh] out.   lo, hi: float[nh] out (may be NULL).
  * ---------------------------------------------------------------------------------------------- */
 int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
-                        int32_t K, double eps, int64_t stride, int64_t block,
+                        int32_t K, double eps, int64_t stride, int64_t block, int32_t range_all,
                         uint32_t* counts, double* H, double* r, float* lo_out, float* hi_out)
 {
     if (!x || !counts || !H || !r) return ORACLE_EINVAL;
@@ -95,7 +100,7 @@ int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const i
         const int64_t b0 = seqlens ? hsel : 0;
         const int64_t b1 = seqlens ? hsel + 1 : B;
 
-        /* pass 1: range of the sampled values */
+        /* pass 1: range of the sampled values (of all values with range_all) */
         float lo = INFINITY, hi = -INFINITY;
         int seen_nan = 0;
         int64_t j = 0, nsamp = 0;
@@ -104,12 +109,13 @@ int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const i
             if (len < 0 || len > L) return ORACLE_EINVAL;
             for (int64_t d = 0; d < D; ++d)
                 for (int64_t t = 0; t < len; ++t, ++j) {
-                    if ((j / block) % stride) continue;
+                    const int sampled = (j / block) % stride == 0;
+                    if (!sampled && !range_all) continue;
                     float v = x[(b * D + d) * L + t];
                     if (v != v) seen_nan = 1;
                     if (v < lo) lo = v;
                     if (v > hi) hi = v;
-                    ++nsamp;
+                    if (sampled) ++nsamp;
                 }
         }
         if (lo_out) lo_out[hsel] = lo;

@@ -211,3 +211,51 @@ def test_doubling_K_adds_log_two_for_smooth_densities():
     H = [oracle.entropy_hist(x, K)["H"][0] for K in (64, 128, 256, 512)]
     for a, b in zip(H, H[1:]):
         assert abs((b - a) - math.log(2.0)) < 0.01
+
+
+def test_sampled_counts_on_the_range_of_all_values():
+    """range_all: bins bounded by the extremes of every value, counts over the sampled blocks only."""
+    rng = np.random.default_rng(21)
+    K, w = 29, 0.5
+    # numpy's histogram with an explicit range, on samples in the middle half of their bins
+    k = rng.integers(3, K - 3, size=6000)
+    x = ((k + rng.uniform(0.25, 0.75, size=k.size)) * w).astype(np.float32)
+    x[5] = 0.0                                                  # the extremes sit in blocks that are NOT sampled
+    x[6] = K * w
+    stride, block = 4, 4
+    j = np.arange(x.size)
+    used = (j // block) % stride == 0
+    assert not used[5] and not used[6]
+    res = oracle.entropy_hist(_x(x), K, eps=1e-8, stride=stride, block=block, range_all=True)
+    ref, _ = np.histogram(x[used].astype(np.float64), bins=K, range=(0.0, K * w))
+    assert res["counts"][0].tolist() == ref.tolist() and res["counts"].sum() == used.sum()
+    assert res["lo"][0] == 0.0 and res["hi"][0] == np.float32(K * w)
+    p = ref / ref.sum()                                         # the end bins are empty: 0 log(eps) = 0
+    assert res["H"][0] == pytest.approx(float(-(p * np.log(p + 1e-8)).sum()), rel=1e-12)
+    # the plain sampled statistic takes the narrower range of the sampled values: different bins
+    plain = oracle.entropy_hist(_x(x), K, eps=0.0, stride=stride, block=block)
+    assert plain["lo"][0] > 0.0 and plain["counts"][0].tolist() != ref.tolist()
+    # same thing as appending the two extremes to the sample and taking them out of their (end) bins again
+    ext = np.concatenate([x[used], [0.0, K * w]]).astype(np.float32)
+    e = oracle.entropy_hist(_x(ext), K, eps=0.0)["counts"][0].astype(np.int64)
+    e[0] -= 1
+    e[K - 1] -= 1
+    assert e.tolist() == ref.tolist()
+    # stride 1: both readings coincide; extremes inside sampled blocks: both readings coincide
+    y = rng.standard_normal((2, 3, 50)).astype(np.float32)
+    a, b = oracle.entropy_hist(y, 16), oracle.entropy_hist(y, 16, range_all=True)
+    assert (a["counts"] == b["counts"]).all() and a["H"][0] == b["H"][0]
+    y.reshape(-1)[0], y.reshape(-1)[1] = -9.0, 9.0
+    a, b = oracle.entropy_hist(y, 16, stride=5, block=2), oracle.entropy_hist(y, 16, stride=5, block=2, range_all=True)
+    assert (a["counts"] == b["counts"]).all() and a["lo"][0] == b["lo"][0] == -9.0
+    # a NaN outside the sample still makes the statistic non-finite; per-sequence histograms number their own values
+    z = y.copy()
+    z.reshape(-1)[3] = np.nan                                   # block 1 of stride 5: not sampled
+    assert oracle.entropy_hist(z, 16, stride=5, block=2)["status"] == oracle.OK
+    assert oracle.entropy_hist(z, 16, stride=5, block=2, range_all=True)["status"] == oracle.ENONFINITE
+    lens = np.array([50, 20], dtype=np.int32)
+    per = oracle.entropy_hist(y, 16, seqlens=lens, stride=3, block=2, range_all=True)
+    for bb in range(2):
+        v = np.ascontiguousarray(y[bb:bb + 1, :, :lens[bb]])
+        one = oracle.entropy_hist(v, 16, stride=3, block=2, range_all=True)
+        assert (per["counts"][bb] == one["counts"][0]).all() and per["hi"][bb] == v.max()
