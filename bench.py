@@ -13,6 +13,7 @@ memory (no host round trip inside a step).  Prints ONE JSON line.
              at one plain wave64 instruction per 4 cycles and one transcendental per 8 on each SIMD
   per_chunk  scan-only latency, GB/s and tokens/s for every chunk of the sweep
   producer   the causal convolution + SiLU that writes u and its range, and the statistic with and without that range
+             (two sweeps, one sweep, one sweep over every 8th block), each also as a percentage of the scan
   decode     one generated token (selective_state_update), eager calls and replayed from a HIP graph
   overhead   entropy + routing cost relative to the scan alone at the routed chunk, for the exact statistic (the
              timed step) and for the sampled one (every 8th block of 512 values, the paper's stride-8 variant at
@@ -198,6 +199,8 @@ def main() -> int:
 
     # ---- scan alone at the routed chunk (for the overhead figure) and the chunk sweep
     scan_alone_ms = time_scan(chunk, 3, args.steps)
+    # the sampled statistic can route to another chunk: its overhead is taken against the scan at that chunk
+    scan_alone_sampled_ms = scan_alone_ms if chunk_sampled == chunk else time_scan(chunk_sampled, 3, args.steps)
     hist_a, hist_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     hist_a.record()
     for _ in range(args.steps):
@@ -278,12 +281,17 @@ def main() -> int:
     entc = corey.corey_route_device(uc, cfg.K, pol)
     hist2_ms = time_kernel(lambda: corey.corey_route_device(uc, cfg.K, pol, out=entc), args.steps)
     hist1_ms = time_kernel(lambda: corey.corey_route_device(uc, cfg.K, pol, out=entc, range_parts=parts), args.steps)
+    hist18_ms = time_kernel(lambda: corey.corey_route_device(uc, cfg.K, pol, out=entc, range_parts=parts, stride=8, block=512), args.steps)
     conv_bytes = wl.conv_bytes(cfg)
     producer = {"note": "causal depthwise convolution (4 taps) + SiLU writing u and the partial ranges of u; "
                         "corey_route_device given those ranges skips its range sweep (whole-tensor statistic)",
                 "conv_ms": round(conv_ms, 4), "conv_GBps": round(conv_bytes / conv_ms * 1e-6, 1),
                 "conv_hbm_frac": round(conv_bytes / conv_ms * 1e-6 / HBM_PEAK_GBPS, 4),
-                "route_two_sweeps_ms": round(hist2_ms, 4), "route_given_range_ms": round(hist1_ms, 4)}
+                "route_two_sweeps_ms": round(hist2_ms, 4), "route_given_range_ms": round(hist1_ms, 4),
+                "route_given_range_sampled_stride8_block512_ms": round(hist18_ms, 4),
+                "pct_of_scan": {"two_sweeps": round(hist2_ms / scan_alone_ms * 100, 2),
+                                "given_range": round(hist1_ms / scan_alone_ms * 100, 2),
+                                "given_range_sampled": round(hist18_ms / scan_alone_ms * 100, 2)}}
     del xc, uc
 
     # ---- one generated token from the carried state (the recurrence at L = 1), single sequence and batches of 64 and 512
@@ -440,7 +448,8 @@ def main() -> int:
                      "hist_kernels_ms": round(hist_ms, 4), "scan_alone_ms": round(scan_alone_ms, 4),
                      "hist_pct_of_scan": round(hist_ms / scan_alone_ms * 100, 2),
                      "sampled_stride8_block512": {"ms_per_step": round(ms_step_sampled, 4),
-                                                  "entropy_routing_pct_of_scan": round((ms_step_sampled - scan_alone_ms) / scan_alone_ms * 100, 2),
+                                                  "entropy_routing_pct_of_scan": round((ms_step_sampled - scan_alone_sampled_ms) / scan_alone_sampled_ms * 100, 2),
+                                                  "scan_alone_ms_at_its_chunk": round(scan_alone_sampled_ms, 4),
                                                   "hist_kernels_ms": round(hist_sampled_ms, 4), "r": r_sampled,
                                                   "routed_chunk": chunk_sampled}},
         "ceilings": ceilings,

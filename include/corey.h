@@ -87,7 +87,11 @@ typedef enum {
  *   range_out   DEVICE float[nh * 2] (lo, hi per histogram) or NULL.
  *   range_parts DEVICE, COREY_RANGE_PARTS * 16 bytes as written by causal_conv1d_silu_fwd for this same tensor, or
  *               NULL.  With it the range sweep is skipped (the producer of x already saw every value): only the
- *               count sweep reads x.  Requires seqlens == NULL and stride == 1 (COREY_EINVAL otherwise).
+ *               count sweep reads x.  Requires seqlens == NULL (COREY_EINVAL otherwise).  With stride > 1 the bins are
+ *               then bounded by the minimum and maximum of ALL values while the counts are those of the sampled
+ *               blocks (without range_parts a sampled statistic takes the range of the sampled values; the paper
+ *               does not say which its sampled variant uses): the cheapest statistic the library offers, one read
+ *               of 1/stride of x.
  *   workspace   DEVICE, at least corey_entropy_hist_workspace(B, K) bytes, 256-byte aligned; scratch only,
  *               contents are undefined afterwards.
  * The work is two sweeps over the sampled values of x (range, then counts) plus an O(K) reduction, as the paper's

@@ -630,14 +630,29 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
     const int64_t E = B * D * L;
     const bool flat_ok = !seqlens && reinterpret_cast<uintptr_t>(x) % kVecBytes == 0 && E % V == 0;
     const int64_t bw = block / V;                              // 16-byte words per sampling block
-    if (given_parts && flat_ok) {
+    const bool flat_blocks = flat_ok && block % V == 0 && corey::is_pow2(bw);    // sampled runs are whole 16-byte words
+    if (given_parts && flat_ok && (stride == 1 || flat_blocks)) {
         // the producer of x left the partial ranges: clear the partial counts and go straight to the count sweep
-        const int64_t nwords = E / V;
+        // (over every word, or over the words of every stride-th block)
+        int64_t nwords = E / V;
+        int bw_log2 = 0;
+        if (stride > 1) {
+            const int64_t nb = (nwords + bw - 1) / bw;
+            const int64_t ns = (nb + stride - 1) / stride;
+            const int64_t last_first = (ns - 1) * stride * bw;
+            const int64_t last_words = nwords - last_first < bw ? nwords - last_first : bw;
+            while (((int64_t)1 << bw_log2) < bw) ++bw_log2;
+            nwords = (ns - 1) * bw + last_words;
+        }
         int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
         blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
         k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
-        k_entropy_count_flat<T, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
-            static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
+        if (stride == 1)
+            k_entropy_count_flat<T, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
+                static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
+        else
+            k_entropy_count_flat<T, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
+                static_cast<const word4*>(x), nwords, WordMap<true>{bw_log2, stride}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
     } else if (given_parts) {
         // unaligned tensor: one workgroup folds the partial ranges into the slot, then the general count sweep
         k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
@@ -646,12 +661,12 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
         int64_t blocks = B * D * ((L + seg - 1) / seg);
         blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
-        k_entropy_count<T><<<dim3((unsigned)blocks, 1), dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, nullptr, 1, 1,
-                                                                                   vector_ok ? 1 : 0, K, slots, parts);
+        k_entropy_count<T><<<dim3((unsigned)blocks, 1), dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, nullptr, stride,
+                                                                                   block, vector_ok ? 1 : 0, K, slots, parts);
     } else if (flat_ok && stride == 1) {
         // whole tensor, every value, aligned: flat sweeps
         launch_flat<T, false>(static_cast<const word4*>(x), E / V, WordMap<false>{0, 1}, K, slots, parts, rparts, stream);
-    } else if (flat_ok && block % V == 0 && corey::is_pow2(bw)) {
+    } else if (flat_blocks) {
         // whole tensor, every stride-th block of a power-of-two number of words: flat sweeps over the sampled words only
         const int64_t nwords_all = E / V;
         const int64_t nb = (nwords_all + bw - 1) / bw;          // blocks in the tensor (the last may be short)
@@ -731,8 +746,8 @@ int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B,
     if (K < 2 || K > COREY_MAX_BINS) return fail(COREY_EINVAL, "%s: K = %d outside [2, %d]", who, K, COREY_MAX_BINS);
     if (!(eps >= 0.0)) return fail(COREY_EINVAL, "%s: eps must be >= 0", who);
     if (stride < 1 || block < 1) return fail(COREY_EINVAL, "%s: stride and block must be >= 1", who);
-    if (range_parts && (seqlens || stride != 1))
-        return fail(COREY_EINVAL, "%s: range_parts needs the whole-tensor statistic (seqlens NULL, stride 1)", who);
+    if (range_parts && seqlens)
+        return fail(COREY_EINVAL, "%s: range_parts needs the whole-tensor statistic (seqlens NULL)", who);
     if (range_parts && reinterpret_cast<uintptr_t>(range_parts) % 16 != 0) return fail(COREY_EINVAL, "%s: range_parts must be 16-byte aligned", who);
     const size_t need = workspace_bytes(B, K);
     if (!workspace || workspace_bytes_given < need) return fail(COREY_EWORKSPACE, "%s: workspace of %zu bytes required", who, need);

@@ -76,14 +76,14 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     fake = ctypes.c_void_p(0x1000)          # never dereferenced: every call below fails validation first
     none = ctypes.c_void_p(0)
     eh = lambda **kw: lib.corey_entropy_hist(
-        kw.get("x", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("L", 8), none, kw.get("K", 16),
+        kw.get("x", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("L", 8), kw.get("seqlens", none), kw.get("K", 16),
         kw.get("eps", 1e-8), kw.get("stride", 1), kw.get("block", 1), kw.get("counts", fake), fake, fake, none, kw.get("rp", none),
         kw.get("ws", fake), kw.get("wsb", 256), none)
     assert eh(x=none) == 2 and eh(counts=none) == 2
     assert eh(dt=7) == 1 and eh(K=1) == 1 and eh(K=5000) == 1 and eh(stride=0) == 1 and eh(block=0) == 1 and eh(eps=-1.0) == 1
     assert eh(B=0) == 3 and eh(L=0) == 3
     assert eh(ws=none) == 7 and eh(wsb=8) == 7
-    assert eh(rp=fake, stride=2) == 1 and eh(rp=ctypes.c_void_p(0x1004)) == 1     # given range: whole tensor only, aligned
+    assert eh(rp=fake, seqlens=fake) == 1 and eh(rp=ctypes.c_void_p(0x1004)) == 1     # given range: whole tensor only, aligned
 
     cv = lambda **kw: lib.causal_conv1d_silu_fwd(
         kw.get("x", fake), kw.get("w", fake), none, none, kw.get("u", ctypes.c_void_p(0x2000)), none, kw.get("rp", none),

@@ -135,12 +135,34 @@ def test_unaligned_views_and_nan_inputs():
     assert torch.equal(fused["H"].isnan(), plain["H"].isnan())
 
 
-def test_given_range_is_rejected_for_per_sequence_or_sampled_statistics():
+@pytest.mark.parametrize("name,D,L,stride,block", [("c1_mamba130m", 96, 2048, 8, 512), ("c4_mamba2p8b", 300, 512, 8, 1),
+                                                    ("c2_mamba370m", 64, 1000, 3, 64), ("paper_w1_fp16", 40, 4096, 8, 512),
+                                                    ("c0_tiny_f32", 33, 1001, 5, 24), ("c1_mamba130m", 7, 333, 4, 40)])
+def test_fused_range_with_the_sampled_count(name, D, L, stride, block):
+    """Range from the producer (all values), counts over every stride-th block: the oracle's range_all reading."""
+    cfg = wl.scaled(wl.CONFIGS[name], D=D, L=L, seqlens=None)
+    _say(f"conv + sampled hist {cfg.name} D{D} L{L} stride {stride} block {block}")
+    u, parts, *_ = _run(cfg, 4)
+    uf = u.float()
+    got = corey.corey_entropy_hist(u, cfg.K, stride=stride, block=block, range_parts=parts)
+    routed = corey.corey_route_device(u, cfg.K, stride=stride, block=block, range_parts=parts)
+    torch.cuda.synchronize()
+    ref = oracle.entropy_hist(uf.cpu().numpy(), cfg.K, stride=stride, block=block, range_all=True)
+    assert np.array_equal(counts_u32(got["counts"]), ref["counts"]) and np.array_equal(counts_u32(routed["counts"]), ref["counts"])
+    assert got["H"].item() == pytest.approx(ref["H"][0], rel=1e-12) and got["r"].item() == pytest.approx(ref["r"][0], rel=1e-12)
+    assert got["range"].cpu().reshape(-1).tolist() == [uf.min().item(), uf.max().item()]
+    st, c_ref, margin = oracle.select_chunk(float(ref["r"][0]), cfg.L, oracle.policy())
+    if margin > 1e-9:
+        assert routed["chunks"].item() == c_ref
+    # the sampled statistic on its own range is a different (narrower-binned) histogram of the same values
+    plain = oracle.entropy_hist(uf.cpu().numpy(), cfg.K, stride=stride, block=block)
+    assert plain["counts"].sum() == ref["counts"].sum()
+
+
+def test_given_range_is_rejected_for_per_sequence_statistics():
     x = torch.randn(2, 4, 64, device="cuda")
     w = torch.ones(4, 2, device="cuda")
     u, _, parts = corey.causal_conv1d_silu_fwd(x, w)
-    with pytest.raises(corey.CoreyError):
-        corey.corey_entropy_hist(u, 16, stride=8, range_parts=parts)
     with pytest.raises(corey.CoreyError):
         corey.corey_entropy_hist(u, 16, seqlens=torch.tensor([64, 10], dtype=torch.int32, device="cuda"), range_parts=parts)
     with pytest.raises(corey.CoreyError):
