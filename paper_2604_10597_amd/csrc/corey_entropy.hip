@@ -103,9 +103,15 @@ struct SamplePhase {
     int64_t pos, bph, block, stride;
     __device__ __forceinline__ SamplePhase(int64_t idx, int64_t block_, int64_t stride_) : block(block_), stride(stride_)
     {
-        const int64_t blk = idx / block;
-        pos = idx - blk * block;
-        bph = blk % stride;
+        if (((block & (block - 1)) | (stride & (stride - 1))) == 0) {   // powers of two (uniform): no division
+            const int lb = 63 - __clzll((long long)block);
+            pos = idx & (block - 1);
+            bph = (idx >> lb) & (stride - 1);
+        } else {
+            const int64_t blk = idx / block;
+            pos = idx - blk * block;
+            bph = blk % stride;
+        }
     }
     __device__ __forceinline__ bool take_and_advance()
     {
@@ -118,78 +124,177 @@ struct SamplePhase {
     }
 };
 
-// Visit every sampled value of histogram `h` once: f(value).  A workgroup takes (row, segment) units
-// grid-stride; inside a unit every thread owns kUnroll 16-byte vectors, kThreads vectors apart, all loaded
-// before any is consumed so that enough bytes are in flight to cover HBM latency.  `vector_ok` says rows are
-// 16-byte aligned (pointer and L); otherwise, and in the ragged last segment of a row, values are fetched
-// one by one.
+// Visit every sampled value of histogram `h` once: f(value).  A row is cut into slabs of kThreads 16-byte vectors
+// (one vector per thread); a workgroup takes kUnroll consecutive slabs at a time, grid-stride, whichever rows they
+// fall in (short rows: several rows per turn), and loads all of them before any is consumed so that enough bytes
+// are in flight to cover HBM latency.  The (row, slab) cursor is stepped, never divided, inside the loop.
+// `vector_ok` says rows are 16-byte aligned (pointer and L); otherwise, and in the ragged last slab of a row,
+// values are fetched one by one where no whole vector fits.
+// Apply a per-value function to the values of one 16-byte vector.
 template <typename T, typename F>
-__device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, int64_t stride, int64_t block, bool vector_ok, F&& f)
+__device__ __forceinline__ void each_of_vector(const uint32_t __attribute__((ext_vector_type(4)))& raw, F&& f)
+{
+    T v[Elem<T>::kVec];
+    __builtin_memcpy(v, &raw, kVecBytes);
+#pragma unroll
+    for (int e = 0; e < Elem<T>::kVec; ++e) f(Elem<T>::widen(v[e]));
+}
+
+// The grid is sized on the host from L; the valid lengths are only known here.  active_groups says how many of the
+// launched workgroups a histogram keeps busy (about kTurns turns each): the others leave at once instead of paying a
+// workgroup's fixed costs (clearing and merging the LDS counters) for a sliver of data.
+constexpr int kTurns = 2;
+template <typename T>
+__device__ __forceinline__ int64_t active_groups(const Geometry& g)
+{
+    constexpr int64_t kSlab = (int64_t)kThreads * Elem<T>::kVec;
+    const int64_t nslab = g.rows * ((g.len + kSlab - 1) / kSlab);
+    const int64_t n = (nslab + kUnroll * kTurns - 1) / (kUnroll * kTurns);
+    return n < 1 ? 1 : (n > (int64_t)gridDim.x ? (int64_t)gridDim.x : n);
+}
+
+// `fv` takes a whole 16-byte vector of values that are all used (stride 1); `f` one value.
+template <typename T, typename F, typename FV>
+__device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, int64_t stride, int64_t block, bool vector_ok,
+                                               int64_t nwg, F&& f, FV&& fv)
 {
     constexpr int V = Elem<T>::kVec;
-    constexpr int64_t kSeg = (int64_t)kThreads * V * kUnroll;
+    constexpr int64_t kSlab = (int64_t)kThreads * V;
     typedef uint32_t vec4 __attribute__((ext_vector_type(4)));
     if (g.len == 0) return;
     const bool all = stride == 1;
-    const int64_t nseg = (g.len + kSeg - 1) / kSeg;
-    const int64_t units = g.rows * nseg;
-    for (int64_t unit = blockIdx.x; unit < units; unit += gridDim.x) {
-        const int64_t r = unit / nseg;
-        const int64_t seg0 = (unit - r * nseg) * kSeg;
-        const T* row = x + g.base + r * g.row_stride;
-        if (vector_ok && seg0 + kSeg <= g.len) {               // uniform: the whole unit is in range
+    const int64_t spr = (g.len + kSlab - 1) / kSlab;           // slabs per row
+    const int64_t nslab = g.rows * spr;
+    const int64_t step = nwg * kUnroll;                         // nwg workgroups (blockIdx.x < nwg) share the histogram
+    const int64_t step_r = step / spr, step_o = step - step_r * spr;
+    int64_t s = (int64_t)blockIdx.x * kUnroll;
+    int64_t r = s / spr, o = s - r * spr;                       // row and slab within the row of slab s
+    const int64_t tid_off = (int64_t)threadIdx.x * V;
+    // sampling in power-of-two blocks of whole vectors, every power-of-two-th block, rows of whole vectors
+    const bool vec_blocks = !all && ((block & (block - 1)) | (stride & (stride - 1))) == 0 && block % V == 0 && g.len % V == 0;
+    const int block_log2 = 63 - __clzll((long long)block);
+    for (; s < nslab; s += step) {                              // everything about the cursor is uniform
+        int64_t row_k[kUnroll], t0_k[kUnroll];
+        int nk = 0;
+        bool fast = vector_ok;
+        {
+            int64_t rk = r, ok = o;
+#pragma unroll
+            for (int k = 0; k < kUnroll; ++k) {
+                row_k[k] = rk;
+                t0_k[k] = ok * kSlab;
+                if (s + k < nslab) {
+                    ++nk;
+                    fast = fast && (t0_k[k] + kSlab <= g.len);
+                }
+                if (++ok == spr) {
+                    ok = 0;
+                    ++rk;
+                }
+            }
+        }
+        if (fast && nk == kUnroll && vec_blocks) {              // whole slabs, sampled in blocks of whole vectors:
+            vec4 raw[kUnroll];                                  // a vector is used or skipped (not even fetched) as one
+            bool take[kUnroll];
+#pragma unroll
+            for (int k = 0; k < kUnroll; ++k) {
+                const int64_t idx = row_k[k] * g.len + t0_k[k] + tid_off;
+                take[k] = ((idx >> block_log2) & (stride - 1)) == 0;
+                if (take[k]) raw[k] = *reinterpret_cast<const vec4*>(x + g.base + row_k[k] * g.row_stride + t0_k[k] + tid_off);
+            }
+#pragma unroll
+            for (int k = 0; k < kUnroll; ++k)
+                if (take[k]) fv(raw[k]);
+        } else if (fast && nk == kUnroll) {                     // kUnroll whole slabs
             vec4 raw[kUnroll];
 #pragma unroll
             for (int k = 0; k < kUnroll; ++k)
-                raw[k] = *reinterpret_cast<const vec4*>(row + seg0 + ((int64_t)k * kThreads + threadIdx.x) * V);
+                raw[k] = *reinterpret_cast<const vec4*>(x + g.base + row_k[k] * g.row_stride + t0_k[k] + tid_off);
 #pragma unroll
             for (int k = 0; k < kUnroll; ++k) {
+                if (all) {
+                    fv(raw[k]);
+                    continue;
+                }
                 T v[V];
                 __builtin_memcpy(v, &raw[k], kVecBytes);
-                if (all) {
-#pragma unroll
-                    for (int e = 0; e < V; ++e) f(Elem<T>::widen(v[e]));
-                } else {
-                    const int64_t t0 = seg0 + ((int64_t)k * kThreads + threadIdx.x) * V;
-                    SamplePhase ph(r * g.len + t0, block, stride);     // index of v[0] in memory order
+                {
+                    SamplePhase ph(row_k[k] * g.len + t0_k[k] + tid_off, block, stride);   // index of v[0] in memory order
 #pragma unroll
                     for (int e = 0; e < V; ++e)
                         if (ph.take_and_advance()) f(Elem<T>::widen(v[e]));
                 }
             }
-        } else {                                               // the ragged end of a row: whole vectors where they fit
+        } else if (vector_ok) {                                 // a ragged slab among them, or the last turn: every thread
+            vec4 raw[kUnroll];                                  // still fetches its whole vectors before it uses any
+            int nvalid[kUnroll];
 #pragma unroll
             for (int k = 0; k < kUnroll; ++k) {
-                const int64_t t0 = seg0 + ((int64_t)k * kThreads + threadIdx.x) * V;
-                if (t0 >= g.len) break;
-                const int nvalid = (g.len - t0 < V) ? (int)(g.len - t0) : V;
-                SamplePhase ph(all ? 0 : r * g.len + t0, block, stride);
-                if (vector_ok && nvalid == V) {
-                    const vec4 raw = *reinterpret_cast<const vec4*>(row + t0);
-                    T v[V];
-                    __builtin_memcpy(v, &raw, kVecBytes);
+                const int64_t left = g.len - (t0_k[k] + tid_off);
+                nvalid[k] = (k < nk && left > 0) ? (left < V ? (int)left : V) : 0;
+                if (nvalid[k] == V)
+                    raw[k] = *reinterpret_cast<const vec4*>(x + g.base + row_k[k] * g.row_stride + t0_k[k] + tid_off);
+            }
 #pragma unroll
-                    for (int e = 0; e < V; ++e)
-                        if (all || ph.take_and_advance()) f(Elem<T>::widen(v[e]));
+            for (int k = 0; k < kUnroll; ++k) {
+                if (nvalid[k] == 0) continue;
+                const int64_t t0 = t0_k[k] + tid_off;
+                const T* row = x + g.base + row_k[k] * g.row_stride;
+                if (nvalid[k] == V) {
+                    if (all) {
+                        fv(raw[k]);
+                    } else {
+                        T v[V];
+                        __builtin_memcpy(v, &raw[k], kVecBytes);
+                        SamplePhase ph(row_k[k] * g.len + t0, block, stride);
+#pragma unroll
+                        for (int e = 0; e < V; ++e)
+                            if (ph.take_and_advance()) f(Elem<T>::widen(v[e]));
+                    }
+                } else if (all) {                              // the thread that straddles the end of the row
+                    for (int e = 0; e < nvalid[k]; ++e) f(Elem<T>::widen(row[t0 + e]));
                 } else {
-                    for (int e = 0; e < nvalid; ++e)
-                        if (all || ph.take_and_advance()) f(Elem<T>::widen(row[t0 + e]));
+                    SamplePhase ph(row_k[k] * g.len + t0, block, stride);
+                    for (int e = 0; e < nvalid[k]; ++e)
+                        if (ph.take_and_advance()) f(Elem<T>::widen(row[t0 + e]));
                 }
             }
+        } else {                                                // unaligned rows: value by value
+            for (int k = 0; k < nk; ++k) {
+                const T* row = x + g.base + row_k[k] * g.row_stride;
+                const int64_t t0 = t0_k[k] + tid_off;
+                if (t0 >= g.len) continue;
+                const int nv = (g.len - t0 < V) ? (int)(g.len - t0) : V;
+                if (all) {
+                    for (int e = 0; e < nv; ++e) f(Elem<T>::widen(row[t0 + e]));
+                } else {
+                    SamplePhase ph(row_k[k] * g.len + t0, block, stride);
+                    for (int e = 0; e < nv; ++e)
+                        if (ph.take_and_advance()) f(Elem<T>::widen(row[t0 + e]));
+                }
+            }
+        }
+        r += step_r;
+        o += step_o;
+        if (o >= spr) {
+            o -= spr;
+            ++r;
         }
     }
 }
 
-__global__ void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots, int nh)
+// Range slots of the general sweeps: every histogram has kSubSlots of them and a workgroup publishes into slot
+// blockIdx.x % kSubSlots (a thousand workgroups that finish together would otherwise queue their atomics on one
+// address: that queue, not the data, set the time of the range sweep); the count sweep folds them.
+constexpr int kSubSlots = 32;
+
+__global__ void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots, int nh, RangeSlot* subs)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const RangeSlot empty = {0xffffffffu, 0u, 0u, 0u};
     if (i < nparts) parts[i] = 0u;
-    if (i < nh) {
-        slots[i].lo_key = 0xffffffffu;
-        slots[i].hi_key = 0u;
-        slots[i].saw_nan = 0u;
-        slots[i].pad = 0u;
-    }
+    if (i < nh) slots[i] = empty;
+    if (i < (int64_t)nh * kSubSlots) subs[i] = empty;
 }
 
 // ... and the integer atomics that publish it.  The slot is read first and an atomic is issued only if it
@@ -206,23 +311,6 @@ __device__ __forceinline__ void publish_range(float lo, float hi, bool nan, Rang
         if (khi > __atomic_load_n(&slot->hi_key, __ATOMIC_RELAXED)) atomicMax(&slot->hi_key, khi);
         if (knan) atomicOr(&slot->saw_nan, 1u);
     }
-}
-
-template <typename T>
-__global__ __launch_bounds__(kThreads) void k_entropy_range(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
-                                                            const int32_t* __restrict__ seqlens, int64_t stride, int64_t block,
-                                                            int vector_ok, RangeSlot* slots)
-{
-    const int h = blockIdx.y;
-    const Geometry g = geometry(h, B, D, L, seqlens);
-    float lo = INFINITY, hi = -INFINITY;
-    bool nan = false;
-    for_each_value(x, g, stride, block, vector_ok != 0, [&](float v) {
-        nan |= (v != v);
-        lo = fminf(lo, v);       // fminf/fmaxf drop a NaN operand; NaNs are flagged separately
-        hi = fmaxf(hi, v);
-    });
-    publish_range(lo, hi, nan, &slots[h]);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -284,6 +372,30 @@ template <> struct RangeFold<float> {
     }
     static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return mag > 0x7f800000u; }
 };
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_entropy_range(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
+                                                            const int32_t* __restrict__ seqlens, int64_t stride, int64_t block,
+                                                            int vector_ok, RangeSlot* subs)
+{
+    const int h = blockIdx.y;
+    const Geometry g = geometry(h, B, D, L, seqlens);
+    const int64_t nwg = active_groups<T>(g);
+    if ((int64_t)blockIdx.x >= nwg) return;                     // uniform
+    float lo = INFINITY, hi = -INFINITY;
+    uint32_t mag = 0u;                                          // whole vectors: NaN is read off the largest magnitude pattern
+    bool nan = false;
+    for_each_value(
+        x, g, stride, block, vector_ok != 0, nwg,
+        [&](float v) {
+            nan |= (v != v);
+            lo = fminf(lo, v);       // fminf/fmaxf drop a NaN operand; NaNs are flagged separately
+            hi = fmaxf(hi, v);
+        },
+        [&](const word4& q) { RangeFold<T>::fold(q, lo, hi, mag); });
+    nan |= RangeFold<T>::saw_nan(mag);
+    publish_range(lo, hi, nan, &subs[h * kSubSlots + blockIdx.x % kSubSlots]);
+}
 
 // The 16-byte words of a flat sweep.  Unsampled: word i is word i.  Sampled: the tensor is cut into blocks of
 // 2^bw_log2 words and every stride-th block is used; the sampled words are numbered consecutively.
@@ -354,14 +466,32 @@ __device__ __forceinline__ int lds_copies(int K)
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
                                                             const int32_t* __restrict__ seqlens, int64_t stride, int64_t block,
-                                                            int vector_ok, int K, const RangeSlot* __restrict__ slots,
-                                                            uint32_t* parts)
+                                                            int vector_ok, int K, const RangeSlot* __restrict__ subs,
+                                                            RangeSlot* __restrict__ slots, uint32_t* parts)
 {
     __shared__ uint32_t s_bins[kMaxLdsBins];
+    __shared__ RangeSlot s_slot;
     const int h = blockIdx.y;
-    float lo, hi;
-    if (!usable_range(slots[h], &lo, &hi)) return;            // counts stay zero, H and r become NaN
     const Geometry g = geometry(h, B, D, L, seqlens);
+    const int64_t nwg = active_groups<T>(g);
+    if ((int64_t)blockIdx.x >= nwg) return;                     // uniform; workgroup 0 always stays
+    {   // the range: every workgroup folds the histogram's sub-slots (half a KB from L2)
+        uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
+        if (threadIdx.x < kSubSlots) {
+            const RangeSlot rs = subs[h * kSubSlots + threadIdx.x];
+            klo = rs.lo_key;
+            khi = rs.hi_key;
+            knan = rs.saw_nan;
+        }
+        reduce_range_keys(klo, khi, knan);
+        if (threadIdx.x == 0) {
+            s_slot.lo_key = klo; s_slot.hi_key = khi; s_slot.saw_nan = knan; s_slot.pad = 0u;
+            if (blockIdx.x == 0) slots[h] = s_slot;           // for the reduction kernel
+        }
+        __syncthreads();
+    }
+    float lo, hi;
+    if (!usable_range(s_slot, &lo, &hi)) return;              // counts stay zero, H and r become NaN
     // as many private copies as fit (up to one per pair of lanes of a wave): lanes of a wave that hit the same
     // bin then mostly land on different addresses, which is what serialises LDS atomics
     const int cs = K + 1;                                     // copy stride: odd offset between copies, see lds_copies
@@ -372,17 +502,19 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count(const T* __restrict_
 
     if (hi == lo) {
         uint32_t n = 0;
-        for_each_value(x, g, stride, block, vector_ok != 0, [&](float) { ++n; });
+        for_each_value(x, g, stride, block, vector_ok != 0, nwg, [&](float) { ++n; },
+                       [&](const word4&) { n += Elem<T>::kVec; });
         if (n) atomicAdd(&mine[0], n);
     } else {
         const float scale = (float)((double)K / ((double)hi - (double)lo));
         const int top = K - 1;
-        for_each_value(x, g, stride, block, vector_ok != 0, [&](float v) {
+        auto bin = [&](float v) {
             const float q = __fmul_rn(__fsub_rn(v, lo), scale);   // two separate binary32 roundings
             int k = (int)q;                                        // truncation; q >= 0
             k = k > top ? top : (k < 0 ? 0 : k);
             atomicAdd(&mine[k], 1u);
-        });
+        };
+        for_each_value(x, g, stride, block, vector_ok != 0, nwg, bin, [&](const word4& q) { each_of_vector<T>(q, bin); });
     }
     __syncthreads();
     uint32_t* out = parts + ((int64_t)h * kParts + blockIdx.x % kParts) * K;
@@ -586,9 +718,12 @@ size_t slots_bytes(int64_t nh)
 
 size_t parts_bytes(int64_t nh, int32_t K) { return ((size_t)nh * kParts * K * sizeof(uint32_t) + 255) / 256 * 256; }
 
-size_t workspace_bytes(int64_t nh, int32_t K) { return slots_bytes(nh) + parts_bytes(nh, K) + (size_t)kMaxBlocks * sizeof(RangePart); }
+size_t workspace_bytes(int64_t nh, int32_t K)
+{
+    return slots_bytes(nh) + parts_bytes(nh, K) + (size_t)kMaxBlocks * sizeof(RangePart) + slots_bytes(nh * kSubSlots);
+}
 
-// Fold given partial ranges into the range slot of the (single) histogram.
+// Fold given partial ranges into the first sub-slot of the (single) histogram (the others stay empty).
 __global__ __launch_bounds__(kThreads) void k_entropy_fold_parts(const RangePart* __restrict__ rparts, int nrparts, RangeSlot* slots)
 {
     uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
@@ -624,6 +759,7 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
     const int nh = seqlens ? (int)B : 1;
     uint32_t* parts = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(slots) + slots_bytes(B));
     RangePart* rparts = reinterpret_cast<RangePart*>(reinterpret_cast<char*>(parts) + parts_bytes(B, K));
+    RangeSlot* subs = reinterpret_cast<RangeSlot*>(rparts + kMaxBlocks);
     const int64_t nparts = (int64_t)nh * kParts * K;
 
     constexpr int V = Elem<T>::kVec;
@@ -646,7 +782,7 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         }
         int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
         blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
         if (stride == 1)
             k_entropy_count_flat<T, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
                 static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
@@ -655,14 +791,14 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
                 static_cast<const word4*>(x), nwords, WordMap<true>{bw_log2, stride}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
     } else if (given_parts) {
         // unaligned tensor: one workgroup folds the partial ranges into the slot, then the general count sweep
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
-        k_entropy_fold_parts<<<dim3(1), dim3(kThreads), 0, stream>>>(given_parts, COREY_RANGE_PARTS, slots);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
+        k_entropy_fold_parts<<<dim3(1), dim3(kThreads), 0, stream>>>(given_parts, COREY_RANGE_PARTS, subs);
         const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
         int64_t blocks = B * D * ((L + seg - 1) / seg);
         blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
         k_entropy_count<T><<<dim3((unsigned)blocks, 1), dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, nullptr, stride,
-                                                                                   block, vector_ok ? 1 : 0, K, slots, parts);
+                                                                                   block, vector_ok ? 1 : 0, K, subs, slots, parts);
     } else if (flat_ok && stride == 1) {
         // whole tensor, every value, aligned: flat sweeps
         launch_flat<T, false>(static_cast<const word4*>(x), E / V, WordMap<false>{0, 1}, K, slots, parts, rparts, stream);
@@ -678,18 +814,21 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         launch_flat<T, true>(static_cast<const word4*>(x), (ns - 1) * bw + last_words, WordMap<true>{bw_log2, stride}, K, slots,
                              parts, rparts, stream);
     } else {
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
         const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
         const int64_t rows = seqlens ? D : B * D;
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
         const int64_t units = rows * ((L + seg - 1) / seg);
+        // about kMaxBlocks workgroups over all histograms (each pays for clearing and merging its LDS counters), at
+        // least 8 per histogram
+        const int64_t cap = kMaxBlocks / nh > 8 ? kMaxBlocks / nh : 8;
         int64_t blocks = units < 1 ? 1 : units;
-        if (blocks > kMaxBlocks) blocks = kMaxBlocks;
+        if (blocks > cap) blocks = cap;
         const dim3 grid((unsigned)blocks, (unsigned)nh);
         k_entropy_range<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride, block,
-                                                               vector_ok ? 1 : 0, slots);
+                                                               vector_ok ? 1 : 0, subs);
         k_entropy_count<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride, block,
-                                                               vector_ok ? 1 : 0, K, slots, parts);
+                                                               vector_ok ? 1 : 0, K, subs, slots, parts);
     }
     corey_policy no_policy = {};
     k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, slots, H_out, r_out, range_out,

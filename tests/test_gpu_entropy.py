@@ -90,6 +90,15 @@ def test_block_sampled_histogram(dtype):
     w = wl.make(cfg)
     _say(f"entropy {dtype} 2M values stride 8 block 512")
     _check(w.dev["u"], w.val["u"], cfg.dtype, 256, stride=8, block=512)
+    # per-sequence histograms over long rows: turns of whole slabs that cross rows, rows with a ragged last slab, and the
+    # sampled sweep that skips the vectors of unsampled blocks without fetching them
+    cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], B=3, D=6, L=6144, dtype=dtype, seqlens=(6144, 4096, 2056))
+    w = wl.make(cfg)
+    lens = np.array(cfg.seqlens, np.int32)
+    for stride, block in ((1, 1), (8, 512), (2, 8), (4, 2048), (8, 16384), (3, 64), (8, 4)):
+        _say(f"entropy {dtype} per sequence, long rows, stride {stride} block {block}")
+        _check(w.dev["u"], w.val["u"], cfg.dtype, 64, stride=stride, block=block, seqlens=lens)
+    _check(w.dev["u"], w.val["u"], cfg.dtype, 64, stride=8, block=512, seqlens=np.array([6144, 0, 6144], np.int32))
 
 
 def test_bin_limits_and_eps():
