@@ -36,7 +36,9 @@ using corey_range::RangePart;
 using corey_range::reduce_range_keys;
 constexpr int kVecBytes = 16;
 constexpr int kParts = 16;     // partial histograms per histogram in the workspace
-constexpr int kMaxBlocks = COREY_RANGE_PARTS;  // workgroups per sweep (four per compute unit)
+constexpr int kMaxBlocks = COREY_RANGE_PARTS;  // most workgroups per sweep (four per compute unit) and partial ranges kept
+constexpr int kFlatBlocks = 512;               // workgroups of a flat sweep: two per compute unit measured 4 % (exact) to
+                                               // 11 % (sampled) faster than four (fewer LDS clears, merges and range folds)
 
 struct RangeSlot {        // one per histogram, in the caller's workspace
     uint32_t lo_key;      // order-preserving image of the minimum (0xffffffff: nothing seen)
@@ -744,7 +746,7 @@ void launch_flat(const word4* x, int64_t nwords, WordMap<SAMPLED> map, int32_t K
                  RangePart* rparts, hipStream_t stream)
 {
     int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
-    blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
+    blocks = blocks < 1 ? 1 : (blocks > kFlatBlocks ? kFlatBlocks : blocks);
     k_entropy_range_flat<T, SAMPLED><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(x, nwords, map, rparts, parts, kParts * K);
     k_entropy_count_flat<T, SAMPLED><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(x, nwords, map, K, rparts, (int)blocks,
                                                                                           slots, parts);
@@ -781,7 +783,7 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
             nwords = (ns - 1) * bw + last_words;
         }
         int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
-        blocks = blocks < 1 ? 1 : (blocks > kMaxBlocks ? kMaxBlocks : blocks);
+        blocks = blocks < 1 ? 1 : (blocks > kFlatBlocks ? kFlatBlocks : blocks);
         k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
         if (stride == 1)
             k_entropy_count_flat<T, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
