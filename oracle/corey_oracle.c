@@ -29,7 +29,7 @@
  * tiny inputs and special cases that reduce to numpy/scipy routines.  Scan parity against the original
  * Mamba implementation itself is unpinned: no such code, weights or outputs exist beside this file.
  *
- * Readings taken where the paper is silent (all listed again in the design notes):
+ * Readings taken where the paper is silent:
  *   - bin index: t = x - lo and q = t * scale are each ONE IEEE binary32 operation (round to nearest
  *     even, no fused multiply-add), scale = (float)(K / ((double)hi - (double)lo)), k = trunc(q)
  *     clamped to K-1.  This is the precision the GPU kernel bins in, so both sides take the integer
