@@ -259,7 +259,7 @@ int corey_scan_structured_path(int enable);
 
 /* Bytes of workspace selective_scan_fwd needs (0 if the arguments are invalid): room for B and C as fp32, padded
  * along L to whole tiles and in N to a multiple of 4, in the two orders a launch may read them in (one launch can run
- * some channels with 16 and the others with 8 time steps per lane):
+ * some channels with 16 and the others with 8 or 4 time steps per lane):
  * 4 * B * roundup(N, 4) * roundup(L + 2048, 4) * 4. */
 size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L);
 

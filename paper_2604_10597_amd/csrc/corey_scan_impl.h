@@ -49,13 +49,13 @@ constexpr int kWaves = kBlock / 64;
 #define COREY_STAGE_FLOATS_K16 2048   // fp32 values of B (and of C) per LDS staging buffer (two buffers), 16 steps per lane
 #endif
 #ifndef COREY_STAGE_FLOATS_K8
-#define COREY_STAGE_FLOATS_K8 2048    // the same for 8 steps per lane
+#define COREY_STAGE_FLOATS_K8 2048    // the same for 8 or 4 steps per lane
 #endif
 #ifndef COREY_WAVES_K16
 #define COREY_WAVES_K16 4             // waves per SIMD the register allocation of the 16-step kernels leaves room for
 #endif
 #ifndef COREY_WAVES_K8
-#define COREY_WAVES_K8 4              // the same for 8 steps per lane (the spare registers hold the tile fetched ahead)
+#define COREY_WAVES_K8 4              // the same for 8 or 4 steps per lane (the spare registers hold the tile fetched ahead)
 #endif
 #ifndef COREY_CPREFETCH_MAXK
 #define COREY_CPREFETCH_MAXK 8        // geometries with at most this many steps per lane fetch C before the lane scan
