@@ -21,7 +21,8 @@ memory (no host round trip inside a step).  Prints ONE JSON line.
   structured_A  the same scan with the library's fast path for A[d, n] = (n + 1) A[d, 0] left on (the benchmark
              layers have that A; trained weights in general do not, so every other figure here is measured with the
              fast path switched off, i.e. one exponential per (channel, state, step))
-  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload on this host's cores
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload on this host's cores (and on one core),
+             with the CPU model
   parity     this run's own outputs against what the oracle computed in that leg: histogram counts and routed chunk
              equal (when the sample was the whole workload), worst error of y and of the final state over the
              tolerance the parity tests use (below 1 passes)
@@ -43,6 +44,17 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 
 # HBM bytes per scan launch measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`, scaled by what the same counters
 # read for a 256 MiB device copy (profiles/hot_path_c4_mamba2p8b_counters.txt); not re-measured by this script
 MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 768_100_000}
+
+
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main() -> int:
@@ -380,7 +392,8 @@ def main() -> int:
         import oracle
         cores = min(16, len(os.sched_getaffinity(0)))
 
-        def oracle_pass(nrows):
+        def oracle_pass(nrows, threads=None):
+            threads = threads or cores
             sel = np.linspace(0, cfg.D - 1, nrows).astype(np.int64)
             p3 = lambda a: np.ascontiguousarray(a[:, sel, :])
             t = time.perf_counter()
@@ -389,11 +402,12 @@ def main() -> int:
             c = max(oracle.select_chunk(float(h["r"][i]), int(Ls[i]), oracle.policy())[1] for i in range(len(h["r"])))
             _, y_ref, s_ref = oracle.selective_scan(p3(w.val["u"]), p3(w.val["delta"]), w.val["A"][sel], w.val["B"], w.val["C"],
                                                     Dv=w.val["D"][sel], z=p3(w.val["z"]), delta_bias=w.val["delta_bias"][sel],
-                                                    seqlens=w.seqlens, chunk=c, threads=cores)
+                                                    seqlens=w.seqlens, chunk=c, threads=threads)
             oracle_pass.last = (sel, h, c, y_ref, s_ref)
             return time.perf_counter() - t
 
         probe_rows = min(cfg.D, 2 * cores)
+        t_single = oracle_pass(probe_rows, threads=1)             # the same sample on one core
         t_probe = oracle_pass(probe_rows)
         nrows = int(min(cfg.D, max(probe_rows, probe_rows * args.cpu_seconds / max(t_probe, 1e-3))))
         t_cpu = oracle_pass(nrows)
@@ -401,7 +415,11 @@ def main() -> int:
         cpu = {"value": round(scan_bytes * frac / t_cpu * 1e-9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
                "tokens_per_s": round(tokens * frac / t_cpu, 1), "seconds": round(t_cpu, 2),
                "sample": f"{nrows} of {cfg.D} channels of {cfg.name} (all {tokens} tokens), histogram + chunk rule + scan, "
-                         f"double precision, OpenMP over channels"}
+                         f"double precision, OpenMP over channels",
+               "single_thread": {"value": round(scan_bytes * probe_rows / cfg.D / t_single * 1e-9, 4), "unit": "GB/s",
+                                 "tokens_per_s": round(tokens * probe_rows / cfg.D / t_single, 1),
+                                 "sample": f"{probe_rows} of {cfg.D} channels"},
+               "cpu_model": cpu_model()}
 
     # ---- parity of this very run against what the oracle just computed (the tests hold the full checks)
     parity = None
