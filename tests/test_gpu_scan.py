@@ -443,3 +443,34 @@ def test_full_size_sampled_rows(name):
     ys = y[:, torch.from_numpy(rows).cuda(), :]
     assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y device-routed", store_bits(cfg))
     assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state device-routed")
+
+
+@pytest.mark.parametrize("lens", [(8192, 512), (2048, 512), (8192, 8192)])
+def test_padded_pairs_of_the_mixed_regime_layer_at_full_size(lens):
+    """The mixed-regime layer (two sequences of a 1.4B-shaped layer, right-padded to 8192) with the other pairs of its
+    three prompt lengths: per-sequence statistic and rule on the GPU, the scan reading each sequence's chunk from device
+    memory.  Counts against the oracle on everything, y and state on sampled channels."""
+    import oracle
+    cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], seqlens=lens)
+    _say(f"mixed-regime pair {lens} at full size")
+    w = wl.make(cfg)
+    d = upload(w)
+    rows = np.unique(np.concatenate([[0, 1, cfg.D - 1], np.random.default_rng(sum(lens)).integers(0, cfg.D, 9)]))
+    y_ref, s_ref = oracle_scan(w, rows=rows)
+    pol = corey.policy_default()
+    pol.mode = 1                                                  # sequence-length gate, then the entropy rule
+    route = corey.corey_route_device(d["u"], cfg.K, pol, seqlens=d["seqlens"])
+    y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
+                                       seqlens=d["seqlens"], chunk=512, chunks_dev=route["chunks"])
+    torch.cuda.synchronize()
+    ref = oracle.entropy_hist(w.val["u"], cfg.K, seqlens=w.seqlens)
+    assert np.array_equal(route["counts"].cpu().numpy().view(np.uint32).reshape(ref["counts"].shape), ref["counts"])
+    opol = oracle.policy(mode=1)
+    for b, n in enumerate(lens):
+        st, c, margin = oracle.select_chunk(float(ref["r"][b]), n, opol)
+        assert st == oracle.OK and (margin < 1e-9 or route["chunks"][b].item() == c)
+    ys = y[:, torch.from_numpy(rows).cuda(), :]
+    assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), "y", store_bits(cfg))
+    assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), "state")
+    for b, n in enumerate(lens):
+        assert (y[b, :, n:] == 0).all()
