@@ -15,6 +15,7 @@ memory (no host round trip inside a step).  Prints ONE JSON line.
   producer   the causal convolution + SiLU that writes u and its range, and the statistic with and without that range
              (two sweeps, one sweep, one sweep over every 8th block), each also as a percentage of the scan
   decode     one generated token (selective_state_update), eager calls and replayed from a HIP graph
+  graph_replay  the same step replayed from a HIP graph (no faster than the eager launches here: the step is GPU-bound)
   overhead   entropy + routing cost relative to the scan alone at the routed chunk, for the exact statistic (the
              timed step) and for the sampled one (every 8th block of 512 values, the paper's stride-8 variant at
              cache-line granularity), and with the chunk rule on the host instead
@@ -186,6 +187,21 @@ def main() -> int:
     ms_step_sampled = time_steps(lambda: scan_routed(8, 512))
     r_sampled = [round(float(v), 6) for v in ent["r"].cpu().tolist()]
     chunk_sampled = int(chunks_dev.max().item())
+
+    # the same step replayed from a HIP graph (ten steps per graph): what a serving loop pays once the launches are recorded
+    torch.cuda.synchronize()
+    step_graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(step_graph):
+        for _ in range(10):
+            scan_routed()
+    step_graph.replay()
+    torch.cuda.synchronize()
+    t0g = time.perf_counter()
+    for _ in range(max(1, args.steps // 10)):
+        step_graph.replay()
+    torch.cuda.synchronize()
+    ms_step_graph = (time.perf_counter() - t0g) * 1e3 / (max(1, args.steps // 10) * 10)
+    chunk_graph = int(chunks_dev.max().item())
 
     # the same step with the chunk rule on the host (one 8-byte read of r and a synchronisation per step)
     for _ in range(2):
@@ -460,6 +476,9 @@ def main() -> int:
                 "frac_plain_instructions": round(scan_flop / scan_ms * 1e-9 / (FP32_VECTOR_PEAK_TFLOPS / 2), 4),
                 "issue_utilisation_at_2p2GHz": round(issue_cycles / 2.2e9 * 1e3 / scan_ms, 4),
                 "flop_per_state_update": 7, "state_updates": state_updates},
+        "graph_replay": {"ms_per_step": round(ms_step_graph, 4), "GBps": round(scan_bytes / ms_step_graph * 1e-6, 1),
+                         "routed_chunk": chunk_graph,
+                         "note": "the timed step (exact statistic + rule + device-routed scan) replayed from a HIP graph of ten steps"},
         "overhead": {"entropy_routing_pct_of_scan": round((ms_step - scan_alone_ms) / scan_alone_ms * 100, 2),
                      "host_routed_ms_per_step": round(ms_step_host, 4),
                      "host_routed_pct_of_scan": round((ms_step_host - scan_alone_ms) / scan_alone_ms * 100, 2),
