@@ -140,3 +140,28 @@ def test_launch_plan_of_the_scan():
     assert steps(1, 1536, 16, 256) == 4 and steps(1, 1536, 16, 512) == 8 and steps(1, 5120, 16, 128) == 4
     assert steps(1, 5120, 16, 256) == 8 and steps(4, 2048, 16, 64) == 4 and steps(4, 2048, 16, 128) == 8
     assert steps(1, 13000, 16, 64) == 8 and plan(1, 13000, 16, 64) == 0 and steps(1, 50000, 16, 16) == 8
+
+
+def test_product_fails_loudly_without_the_library_and_never_reaches_for_the_oracle():
+    """No CPU fallback: with the shared library missing the package raises on first use, and nothing under the product
+    package imports the oracle."""
+    import subprocess
+    import sys
+    code = ("import paper_2604_10597_amd as c, sys\n"
+            "try:\n    c.corey_version()\nexcept Exception as e:\n    print(type(e).__name__, e); sys.exit(7)\n")
+    env = dict(os.environ, COREY_LIB="/nonexistent/libcorey.so", PYTHONPATH=ROOT)
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, cwd=ROOT)
+    assert r.returncode == 7 and "libcorey" in r.stdout, (r.returncode, r.stdout, r.stderr)
+    pkg = os.path.join(ROOT, "paper_2604_10597_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "corey_oracle" not in text, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, cwd=ROOT)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
