@@ -474,3 +474,20 @@ def test_padded_pairs_of_the_mixed_regime_layer_at_full_size(lens):
     assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), "state")
     for b, n in enumerate(lens):
         assert (y[b, :, n:] == 0).all()
+
+
+@pytest.mark.parametrize("chunk", [64, 512, 2048])
+def test_very_long_sequence(chunk):
+    """262144 steps on a few channels (hundreds to thousands of tiles per row, a ragged last tile, B and C of 16 MB): the
+    carried state and the tile bookkeeping over a long run; the tolerance on the fp32 state grows with sqrt(L)."""
+    cfg = wl.scaled(wl.CONFIGS["c1_mamba130m"], D=6, L=262144 - 24)
+    _say(f"scan L={cfg.L} chunk {chunk}")
+    w = wl.make(cfg, a_kind="random", with_h0=True)
+    d = upload(w)
+    y_ref, s_ref = oracle_scan(w)
+    y, s = _run(d, chunk)
+    assert_close(y, y_ref, y_rtol(cfg), "y", store_bits(cfg))
+    assert_close(s, s_ref, fp32_rtol(cfg.L), "state")
+    ent = corey.corey_entropy_hist(d["u"], 4096)
+    ref = oracle.entropy_hist(w.val["u"], 4096)
+    assert np.array_equal(ent["counts"].cpu().numpy().view(np.uint32).reshape(ref["counts"].shape), ref["counts"])
