@@ -491,3 +491,45 @@ def test_very_long_sequence(chunk):
     ent = corey.corey_entropy_hist(d["u"], 4096)
     ref = oracle.entropy_hist(w.val["u"], 4096)
     assert np.array_equal(ent["counts"].cpu().numpy().view(np.uint32).reshape(ref["counts"].shape), ref["counts"])
+
+
+def test_more_than_two_to_the_31_elements():
+    """One tensor of 2.2e9 elements (4.4 GB in bf16): every index that is a product of sizes has to be 64-bit.  Inputs are
+    drawn on the GPU (seeded); the oracle recomputes three channels, the histogram is checked against plain torch
+    operations that follow the stated binary32 bin arithmetic."""
+    B, D, N, L, K = 1, 2100, 16, (1 << 20) + 8, 256
+    assert B * D * L > (1 << 31)
+    _say(f"scan and histogram on {B * D * L} elements")
+    g = torch.Generator(device="cuda").manual_seed(77)
+    rnd = lambda *shape, scale=1.0: (torch.randn(*shape, generator=g, device="cuda", dtype=torch.float32) * scale)
+    u = torch.empty((B, D, L), dtype=torch.bfloat16, device="cuda")
+    delta, z = torch.empty_like(u), torch.empty_like(u)
+    for t in (u, delta, z):                                      # row blocks: no 8.8 GB fp32 temporary
+        for d0 in range(0, D, 300):
+            t[:, d0:d0 + 300] = rnd(B, min(300, D - d0), L, scale=0.5 if t is delta else 1.0).to(torch.bfloat16)
+    Bm, Cm = rnd(B, N, L).to(torch.bfloat16), rnd(B, N, L).to(torch.bfloat16)
+    A = -torch.exp(rnd(D, N))
+    Dv, bias = rnd(D), torch.log(torch.rand(D, generator=g, device="cuda") * 0.099 + 0.001)
+    y, last = corey.selective_scan_fwd(u, delta, A, Bm, Cm, Dv=Dv, z=z, delta_bias=bias, chunk=1024)
+    torch.cuda.synchronize()
+    rows = [0, D // 2 + 1, D - 1]
+    f = lambda t: t.float().cpu().numpy()
+    st, y_ref, s_ref = oracle.selective_scan(f(u[:, rows]), f(delta[:, rows]), f(A[rows]), f(Bm), f(Cm), Dv=f(Dv[rows]), z=f(z[:, rows]),
+                                             delta_bias=f(bias[rows]), chunk=256, threads=3)
+    assert st == oracle.OK
+    assert_close(f(y[:, rows]).astype(np.float64), y_ref, 3e-3, "y", True)
+    assert_close(last[:, rows].cpu().numpy().astype(np.float64), s_ref, fp32_rtol(L), "state")
+    assert bool(torch.isfinite(last).all())
+
+    ent = corey.corey_entropy_hist(u, K)
+    torch.cuda.synchronize()
+    lo, hi = ent["range"].reshape(-1).tolist()
+    assert lo == min(u[:, d0:d0 + 300].min().item() for d0 in range(0, D, 300))
+    assert hi == max(u[:, d0:d0 + 300].max().item() for d0 in range(0, D, 300))
+    scale = torch.tensor(np.float32(np.float64(K) / (np.float64(hi) - np.float64(lo))), device="cuda")
+    counts = torch.zeros(K, dtype=torch.int64, device="cuda")
+    for d0 in range(0, D, 100):
+        q = (u[:, d0:d0 + 100].float() - lo) * scale             # two separate binary32 operations
+        counts += torch.bincount(q.to(torch.int32).clamp_(max=K - 1).reshape(-1), minlength=K)
+    got = ent["counts"].reshape(-1).to(torch.int64) & 0xFFFFFFFF
+    assert torch.equal(got, counts) and int(counts.sum()) == B * D * L
