@@ -221,3 +221,35 @@ def test_generation_steps_continue_the_prompt_bit_for_bit(dtype):
     view = torch.int16 if dtype == wl.BF16 else torch.int32
     assert torch.equal(torch.cat(outs, dim=2).view(view), whole.view(view))
     assert torch.equal(state.view(view), s_whole.view(view))
+
+
+def test_more_than_two_to_the_31_elements():
+    """x and u of 2.2e9 elements each: 64-bit indexing in the producer and in the count sweep that takes its range.
+    Inputs drawn on the GPU (seeded); the oracle recomputes three channels."""
+    B, D, L, W, K = 1, 2100, (1 << 20) + 8, 4, 256
+    _say(f"conv on {B * D * L} elements")
+    g = torch.Generator(device="cuda").manual_seed(78)
+    x = torch.empty((B, D, L), dtype=torch.bfloat16, device="cuda")
+    for d0 in range(0, D, 300):
+        x[:, d0:d0 + 300] = torch.randn(B, min(300, D - d0), L, generator=g, device="cuda").to(torch.bfloat16)
+    wt = torch.rand(D, W, generator=g, device="cuda") - 0.5
+    bs = torch.rand(D, generator=g, device="cuda") - 0.5
+    st_in = torch.randn(B, D, W - 1, generator=g, device="cuda").to(torch.bfloat16)
+    u, st_out, parts = corey.causal_conv1d_silu_fwd(x, wt, bs, st_in, want_state=True)
+    torch.cuda.synchronize()
+    rows = [0, D // 2 + 1, D - 1]
+    val = {"x": _widen(x[:, rows]), "weight": _widen(wt[rows]), "bias": _widen(bs[rows]), "state_in": _widen(st_in[:, rows])}
+    ref_u, ref_so = oracle.causal_conv1d_silu(val["x"], val["weight"], val["bias"], val["state_in"])
+    err = np.abs(_widen(u[:, rows]).astype(np.float64) - ref_u)
+    assert not (err > _tolerance(ref_u, val, W, wl.BF16)).any()
+    assert np.array_equal(_widen(st_out[:, rows]), ref_so)
+    lo, hi, nan = _parts_range(parts)
+    assert not nan and lo == min(u[:, d0:d0 + 300].min().item() for d0 in range(0, D, 300))
+    assert hi == max(u[:, d0:d0 + 300].max().item() for d0 in range(0, D, 300))
+    fused = corey.corey_entropy_hist(u, K, range_parts=parts)
+    plain = corey.corey_entropy_hist(u, K)
+    sampled = corey.corey_entropy_hist(u, K, range_parts=parts, stride=8, block=512)
+    torch.cuda.synchronize()
+    assert torch.equal(fused["counts"], plain["counts"]) and int(counts_u32(fused["counts"]).astype(np.int64).sum()) == B * D * L
+    nblocks = -(-B * D * L // 512)
+    assert int(counts_u32(sampled["counts"]).astype(np.int64).sum()) == sum(min(512, B * D * L - i * 512) for i in range(0, nblocks, 8))
