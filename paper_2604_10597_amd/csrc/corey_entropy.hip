@@ -290,13 +290,29 @@ __device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, in
 // address: that queue, not the data, set the time of the range sweep); the count sweep folds them.
 constexpr int kSubSlots = 32;
 
-__global__ void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots, int nh, RangeSlot* subs)
+// `given` (or NULL): partial ranges handed over by the producer of the tensor; the first workgroup folds them into
+// the slot of the (single) histogram, so that the count sweep's workgroups read 16 bytes instead of all partials.
+__global__ __launch_bounds__(kThreads) void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots, int nh, RangeSlot* subs,
+                                                           const RangePart* __restrict__ given, int ngiven)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const RangeSlot empty = {0xffffffffu, 0u, 0u, 0u};
     if (i < nparts) parts[i] = 0u;
-    if (i < nh) slots[i] = empty;
+    if (i < nh && !(given && i == 0)) slots[i] = empty;
     if (i < (int64_t)nh * kSubSlots) subs[i] = empty;
+    if (given && blockIdx.x == 0) {                             // uniform over the workgroup
+        uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
+        for (int k = threadIdx.x; k < ngiven; k += kThreads) {
+            const RangePart rp = given[k];
+            klo = min(klo, rp.lo_key);
+            khi = max(khi, rp.hi_key);
+            knan |= rp.saw_nan;
+        }
+        reduce_range_keys(klo, khi, knan);
+        if (threadIdx.x == 0) {
+            slots[0].lo_key = klo; slots[0].hi_key = khi; slots[0].saw_nan = knan; slots[0].pad = 0u;
+        }
+    }
 }
 
 // ... and the integer atomics that publish it.  The slot is read first and an atomic is issued only if it
@@ -534,7 +550,7 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
 {
     __shared__ uint32_t s_bins[kMaxLdsBins];
     __shared__ RangeSlot s_slot;
-    {   // the range: every workgroup reduces the partial ranges of the sweep before (a few KB from L2)
+    if (nrparts > 0) {   // the range: every workgroup reduces the partial ranges of the sweep before (a few KB from L2)
         uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
         for (int i = threadIdx.x; i < nrparts; i += kThreads) {
             const RangePart rp = rparts[i];
@@ -547,6 +563,9 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
             s_slot.lo_key = klo; s_slot.hi_key = khi; s_slot.saw_nan = knan; s_slot.pad = 0u;
             if (blockIdx.x == 0) slots[0] = s_slot;           // for the reduction kernel
         }
+        __syncthreads();
+    } else {             // the clearing launch already folded the producer's partial ranges into the slot
+        if (threadIdx.x == 0) s_slot = slots[0];
         __syncthreads();
     }
     float lo, hi;
@@ -648,18 +667,20 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
     }
     float lo = 0.f, hi = 0.f;
     const bool ok = usable_range(slots[h], &lo, &hi);
-    __shared__ double s_red[kThreads];
-    __shared__ unsigned long long s_n[kThreads];
+    // two workgroup sums (the sample count, then the entropy terms): butterfly inside each wave, the waves' totals
+    // through LDS; every thread ends up with the same total, added in the same order
+    __shared__ double s_red[kThreads / 64];
+    __shared__ unsigned long long s_n[kThreads / 64];
+    const int wave = threadIdx.x >> 6;
 
     unsigned long long n_part = 0;
     for (int k = threadIdx.x; k < K; k += kThreads) n_part += c[k];
-    s_n[threadIdx.x] = n_part;
+    for (int off = 32; off > 0; off >>= 1) n_part += __shfl_xor(n_part, off);
+    if ((threadIdx.x & 63) == 0) s_n[wave] = n_part;
     __syncthreads();
-    for (int off = kThreads / 2; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) s_n[threadIdx.x] += s_n[threadIdx.x + off];
-        __syncthreads();
-    }
-    const double n = (double)s_n[0];
+    unsigned long long n_all = 0;
+    for (int w = 0; w < kThreads / 64; ++w) n_all += s_n[w];
+    const double n = (double)n_all;
 
     double part = 0.0;
     if (ok && n > 0.0)
@@ -667,16 +688,15 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
             const double p = (double)c[k] / n;
             part += p * log(p + eps);
         }
-    s_red[threadIdx.x] = part;
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+    if ((threadIdx.x & 63) == 0) s_red[wave] = part;
     __syncthreads();
-    for (int off = kThreads / 2; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) s_red[threadIdx.x] += s_red[threadIdx.x + off];
-        __syncthreads();
-    }
     if (threadIdx.x == 0) {
         double H = NAN, r = NAN;
         if (ok && n > 0.0) {
-            H = -s_red[0];
+            double acc = 0.0;
+            for (int w = 0; w < kThreads / 64; ++w) acc += s_red[w];
+            H = -acc;
             r = H / log((double)K);
             r = r < 0.0 ? 0.0 : (r > 1.0 ? 1.0 : r);
         }
@@ -784,16 +804,18 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         }
         int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
         blocks = blocks < 1 ? 1 : (blocks > kFlatBlocks ? kFlatBlocks : blocks);
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs,
+                                                                                                             given_parts, COREY_RANGE_PARTS);
         if (stride == 1)
             k_entropy_count_flat<T, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
-                static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
+                static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, given_parts, 0, slots, parts);
         else
             k_entropy_count_flat<T, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
-                static_cast<const word4*>(x), nwords, WordMap<true>{bw_log2, stride}, K, given_parts, COREY_RANGE_PARTS, slots, parts);
+                static_cast<const word4*>(x), nwords, WordMap<true>{bw_log2, stride}, K, given_parts, 0, slots, parts);
     } else if (given_parts) {
         // unaligned tensor: one workgroup folds the partial ranges into the slot, then the general count sweep
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs,
+                                                                                                             nullptr, 0);
         k_entropy_fold_parts<<<dim3(1), dim3(kThreads), 0, stream>>>(given_parts, COREY_RANGE_PARTS, subs);
         const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
@@ -816,7 +838,8 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         launch_flat<T, true>(static_cast<const word4*>(x), (ns - 1) * bw + last_words, WordMap<true>{bw_log2, stride}, K, slots,
                              parts, rparts, stream);
     } else {
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs,
+                                                                                                             nullptr, 0);
         const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
         const int64_t rows = seqlens ? D : B * D;
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
