@@ -44,7 +44,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
 # HBM bytes per scan launch measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`, scaled by what the same counters
 # read for a 256 MiB device copy (profiles/hot_path_c4_mamba2p8b_counters.txt); not re-measured by this script
-MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 755_800_000}
+MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 746_400_000}
 
 
 def cpu_model() -> str:
