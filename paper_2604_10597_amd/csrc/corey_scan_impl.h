@@ -456,6 +456,9 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
     const int64_t total = (ntiles * N) << slots_log2;
     const T* Bs = Bm + (int64_t)b * Nreal * L;
     const T* Cs = Cm + (int64_t)b * Nreal * L;
+    struct alignas(4 * sizeof(T)) Quad { T v[4]; };
+    // t is always a multiple of 4: rows of whole, aligned quads can be fetched four values at a time
+    const bool quads_ok = L % 4 == 0 && reinterpret_cast<uintptr_t>(Bm) % sizeof(Quad) == 0 && reinterpret_cast<uintptr_t>(Cm) % sizeof(Quad) == 0;
     for (int pass = 0; pass < 2; ++pass) {                       // the order of the 16-step rows, then that of the others
         const int K = pass == 0 ? 16 : (klo == 8 ? 8 : 4);       // 4 or fewer steps per lane read B / C in time order
         if (pass == 0 ? d16 <= 0 : d16 >= D) continue;           // no channel of this sequence uses it
@@ -475,10 +478,18 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
             const T* pb = Bs + (int64_t)n * L + t;
             const T* pc = Cs + (int64_t)n * L + t;
             float4v vb, vc;
-            vb.x = (t + 0 < len) ? Io<T>::ld(pb + 0) : 0.f; vb.y = (t + 1 < len) ? Io<T>::ld(pb + 1) : 0.f;
-            vb.z = (t + 2 < len) ? Io<T>::ld(pb + 2) : 0.f; vb.w = (t + 3 < len) ? Io<T>::ld(pb + 3) : 0.f;
-            vc.x = (t + 0 < len) ? Io<T>::ld(pc + 0) : 0.f; vc.y = (t + 1 < len) ? Io<T>::ld(pc + 1) : 0.f;
-            vc.z = (t + 2 < len) ? Io<T>::ld(pc + 2) : 0.f; vc.w = (t + 3 < len) ? Io<T>::ld(pc + 3) : 0.f;
+            if (quads_ok && t + 4 <= len) {                      // four values of each operand in one load
+                Quad qb, qc;
+                __builtin_memcpy(&qb, __builtin_assume_aligned(pb, sizeof(Quad)), sizeof(Quad));
+                __builtin_memcpy(&qc, __builtin_assume_aligned(pc, sizeof(Quad)), sizeof(Quad));
+                vb.x = Io<T>::ld(&qb.v[0]); vb.y = Io<T>::ld(&qb.v[1]); vb.z = Io<T>::ld(&qb.v[2]); vb.w = Io<T>::ld(&qb.v[3]);
+                vc.x = Io<T>::ld(&qc.v[0]); vc.y = Io<T>::ld(&qc.v[1]); vc.z = Io<T>::ld(&qc.v[2]); vc.w = Io<T>::ld(&qc.v[3]);
+            } else {
+                vb.x = (t + 0 < len) ? Io<T>::ld(pb + 0) : 0.f; vb.y = (t + 1 < len) ? Io<T>::ld(pb + 1) : 0.f;
+                vb.z = (t + 2 < len) ? Io<T>::ld(pb + 2) : 0.f; vb.w = (t + 3 < len) ? Io<T>::ld(pb + 3) : 0.f;
+                vc.x = (t + 0 < len) ? Io<T>::ld(pc + 0) : 0.f; vc.y = (t + 1 < len) ? Io<T>::ld(pc + 1) : 0.f;
+                vc.z = (t + 2 < len) ? Io<T>::ld(pc + 2) : 0.f; vc.w = (t + 3 < len) ? Io<T>::ld(pc + 3) : 0.f;
+            }
             oB[i] = vb;
             oC[i] = vc;
         }
