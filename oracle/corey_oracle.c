@@ -38,6 +38,8 @@
  *   - hi == lo: all samples fall in bin 0.
  *   - non-finite min or max: status ORACLE_ENONFINITE, counts zero, H and r NaN.
  *   - natural logarithm (the paper reports nats); r is clamped to [0, 1].
+ *   - an empty bin contributes nothing to Eq. 1 (the term p log(p + eps) is 0 at p = 0 for every eps > 0, and
+ *     its limit is 0 for eps = 0, the usual 0 log 0 = 0 of Shannon entropy), so eps = 0 gives a finite H.
  *   - `round` in Eq. 2 is floor(v + 0.5) on v = log2(.) in double.
  *   - candidates above the next power of two >= L are never useful; Eq. 2's result is capped there
  *     (but never below c_min).  The sequence-length table and a static chunk are returned as given,
@@ -152,6 +154,7 @@ int oracle_entropy_hist(const float* x, int64_t B, int64_t D, int64_t L, const i
         for (int32_t k = 0; k < K; ++k) n += (double)c[k];
         double acc = 0.0;
         for (int32_t k = 0; k < K; ++k) {
+            if (c[k] == 0) continue;       /* an empty bin adds nothing: p log(p + eps) is 0 at p = 0, also for eps = 0 */
             double p = (double)c[k] / n;
             acc += p * log(p + eps);
         }

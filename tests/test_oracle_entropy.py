@@ -38,6 +38,22 @@ def test_hand_counted_bins():
     assert p.sum() == pytest.approx(1.0)
 
 
+def test_empty_bins_add_nothing_also_without_eps():
+    # counts (3, 0, 0, 1): H = -(3/4 ln 3/4 + 1/4 ln 1/4) = 0.5623351446...; the two empty bins are 0 log 0 = 0, so
+    # eps = 0 gives the same finite value as a vanishing eps (and not 0 * -inf = NaN)
+    expect = 0.75 * math.log(4 / 3) + 0.25 * math.log(4)
+    assert expect == pytest.approx(0.5623351446188083, rel=1e-15)
+    res0 = oracle.entropy_hist(_x([0, 0, 0, 10]), 4, eps=0.0)
+    assert res0["status"] == oracle.OK and res0["counts"][0].tolist() == [3, 0, 0, 1]
+    assert res0["H"][0] == pytest.approx(expect, rel=1e-15)
+    assert res0["r"][0] == pytest.approx(expect / math.log(4), rel=1e-15)
+    res = oracle.entropy_hist(_x([0, 0, 0, 10]), 4, eps=1e-300)
+    assert res["H"][0] == pytest.approx(expect, rel=1e-15)
+    # with eps > 0 the value is that of the populated bins alone
+    res8 = oracle.entropy_hist(_x([0, 0, 0, 10]), 4, eps=1e-8)
+    assert res8["H"][0] == pytest.approx(-(0.75 * math.log(0.75 + 1e-8) + 0.25 * math.log(0.25 + 1e-8)), rel=1e-15)
+
+
 def test_eps_sits_inside_the_log_only():
     # counts (1, 3): p = (.25, .75); eps = 0.5: H = -(.25 ln .75 + .75 ln 1.25) = -0.0954371...
     res = oracle.entropy_hist(_x([0, 1, 1, 1]), 2, eps=0.5)

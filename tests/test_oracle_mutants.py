@@ -29,6 +29,7 @@ MUTANTS = [
     ("entropy: sign", "double h = -acc;", "double h = acc;"),
     ("entropy: eps outside the logarithm", "acc += p * log(p + eps);", "acc += p * (log(p) + eps);"),
     ("entropy: base-2 logarithm in the normaliser", "double rr = h / log((double)K);", "double rr = h / log2((double)K);"),
+    ("entropy: an empty bin evaluated as 0 * log(0 + eps)", "if (c[k] == 0) continue;", ""),
     ("entropy: probabilities not normalised", "double p = (double)c[k] / n;", "double p = (double)c[k];"),
     ("sampling: stride applied to elements, not blocks", "const int sampled = (j / block) % stride == 0;",
      "const int sampled = j % stride == 0;"),
