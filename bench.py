@@ -90,7 +90,6 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    corey.corey_scan_structured_path(False)           # headline figures: the general path
     cfg = wl.CONFIGS[args.config]
     w = wl.make(cfg)
 
@@ -116,9 +115,12 @@ def main() -> int:
     pol = corey.policy_default()
     r_pinned = torch.empty(ent["r"].shape, dtype=torch.float64).pin_memory()
 
-    def scan(chunk):
+    # every headline figure is measured on the general path (COREY_SCAN_GENERAL_A): the benchmark layers' A = -(n + 1) would
+    # otherwise take the library's power-chain path, which trained weights in general cannot
+    def scan(chunk, general_a=True):
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
-                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=chunk, y=y, last_state=last, workspace=scan_ws)
+                                 delta_bias=d["delta_bias"], seqlens=seqlens, chunk=chunk, y=y, last_state=last, workspace=scan_ws,
+                                 general_a=general_a)
 
     ent["chunks"] = torch.empty(ent["r"].numel(), dtype=torch.int32, device="cuda")
     chunks_dev = ent["chunks"]
@@ -131,7 +133,7 @@ def main() -> int:
         corey.corey_route_device(d["u"], cfg.K, pol, seqlens=seqlens, out=ent, stride=stride, block=block)
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
                                  delta_bias=d["delta_bias"], seqlens=seqlens, chunk=hint, chunks_dev=chunks_dev,
-                                 y=y, last_state=last, workspace=scan_ws)
+                                 y=y, last_state=last, workspace=scan_ws, general_a=True)
 
     def route_on_host():
         corey.corey_entropy_hist(d["u"], cfg.K, seqlens=seqlens, out=ent, workspace=ent["workspace"])
@@ -165,7 +167,7 @@ def main() -> int:
         ev0[i].record()
         corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
                                  delta_bias=d["delta_bias"], seqlens=seqlens, chunk=hint, chunks_dev=chunks_dev,
-                                 y=y, last_state=last, workspace=scan_ws)
+                                 y=y, last_state=last, workspace=scan_ws, general_a=True)
         ev1[i].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -213,14 +215,14 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_step_host = (time.perf_counter() - t0h) * 1e3 / args.steps
 
-    def time_scan(c, warm, reps):
+    def time_scan(c, warm, reps, general_a=True):
         for _ in range(warm):
-            scan(c)
+            scan(c, general_a)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record()
         for _ in range(reps):
-            scan(c)
+            scan(c, general_a)
         b.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
@@ -251,15 +253,13 @@ def main() -> int:
                                  "hbm_frac": round(scan_bytes / ms * 1e-6 / HBM_PEAK_GBPS, 4)}
 
     # ---- the structured-A fast path, reported separately
-    corey.corey_scan_structured_path(True)
     structured = {"note": "A[d,n] = (n+1) A[d,0] detected on the GPU: exp(dl A[d,n]) formed as exp(dl A[d,0])^(n+1)",
                   "scan_ms": {}, "GBps": {}}
     for c in (sorted({chunk, 1024}) if args.no_sweep else cfg.chunks):
-        ms = time_scan(c, 2, 10)
+        ms = time_scan(c, 2, 10, general_a=False)
         structured["scan_ms"][str(c)] = round(ms, 4)
         structured["GBps"][str(c)] = round(scan_bytes / ms * 1e-6, 1)
     structured["hbm_frac_at_routed_chunk"] = round(structured["GBps"][str(chunk)] / HBM_PEAK_GBPS, 4)
-    corey.corey_scan_structured_path(False)
 
     # ---- ceilings beside the HBM peak: what a plain device copy reaches on this machine, and the time the scan's own
     # instruction stream needs when every SIMD issues without a gap (counts per wave-level state update from the
@@ -382,7 +382,7 @@ def main() -> int:
 
         def p_scan(c):
             corey.selective_scan_fwd(pd["u"], pd["delta"], pd["A"], pd["B"], pd["C"], Dv=pd["D"], z=pd["z"],
-                                     delta_bias=pd["delta_bias"], chunk=c, y=p_y, last_state=p_last, workspace=p_ws)
+                                     delta_bias=pd["delta_bias"], chunk=c, y=p_y, last_state=p_last, workspace=p_ws, general_a=True)
 
         def p_time(c):
             for _ in range(5):

@@ -22,7 +22,7 @@
  *     the host before anything is launched; outputs are then untouched.
  *   - Tensors are dense and row-major with the last index contiguous.  Activation tensors (x, u, delta,
  *     z, y) are [B, D, L] (batch, channel, time); Bm and Cm are [B, N, L]; A is [D, N].
- *   - Calls are thread-safe; two calls that share an output or workspace buffer must be ordered by the
+ *   - The library keeps no settings between calls: every option is an argument.  Calls are thread-safe; two calls that share an output or workspace buffer must be ordered by the
  *     caller (same stream, or events).
  */
 #ifndef COREY_H
@@ -69,6 +69,7 @@ typedef enum {
  * r = clamp(H / log K, 0, 1).  Bin index of a value v, stated to the rounding because counts are integers:
  *     scale = (float)(K / ((double)hi - (double)lo));  k = min((int)((v - lo) * scale), K - 1)
  * with the subtraction and the multiplication each one binary32 operation (no fused multiply-add).
+ * An empty bin contributes nothing to H (p log(p + eps) is 0 at p = 0; for eps = 0 this is the usual 0 log 0 = 0).
  * hi == lo puts every sample in bin 0.  If S is empty or its range is not finite (NaN or infinity in the
  * input) the counts are zero and H and r are NaN.  binary32 subnormal inputs are outside the contract.
  *
@@ -151,7 +152,8 @@ int corey_select_chunk(double r, int64_t L, const corey_policy* p, int32_t* chun
  *                "use the host chunk".
  * Same arithmetic as corey_select_chunk (double precision, round = floor(v + 0.5)); the device log2 can differ
  * from the host's in the last bit, which matters only within ~1e-15 of a rounding tie of Eq. 2.
- * Errors (host side, before the launch): COREY_ENULL, COREY_EINVAL as for corey_select_chunk, nh < 1.
+ * Errors (host side, before the launch): COREY_ENULL, COREY_EINVAL as for corey_select_chunk, nh < 1, or a policy
+ * whose mode can select a chunk above COREY_MAX_CHUNK (the scan could not run it).
  * ----------------------------------------------------------------------------------------------------- */
 int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64_t L, int32_t nh,
                               const corey_policy* p, int32_t* chunks_out, void* hip_stream);
@@ -228,34 +230,38 @@ int causal_conv1d_silu_fwd(const void* x, const float* weight, const float* bias
  *                    y is written as 0 for the padded positions and last_state is the state after the
  *                    last valid step.
  *   chunk            HOST value: power of two in [COREY_MIN_CHUNK, COREY_MAX_CHUNK].  chunk > L is legal.
- *   chunks_dev       DEVICE int32[B] or NULL: per-sequence chunk (same constraints) that overrides `chunk`
- *                    without a host round trip; out-of-range or non-power-of-two entries fall back to `chunk`.
+ *   chunks_dev       DEVICE int32[B] (int32[1] with COREY_SCAN_ONE_CHUNK) or NULL: per-sequence chunk (same
+ *                    constraints) that overrides `chunk` without a host round trip; out-of-range or
+ *                    non-power-of-two entries fall back to `chunk`.
  *   last_state       DEVICE float[B, D, N], required.
  *   workspace        DEVICE, at least selective_scan_fwd_workspace(B, N, L) bytes, 16-byte aligned; scratch only
  *                    (the call first rewrites B and C there as fp32 in the order, or the two orders, the scan reads
  *                    them in).
  *   1 <= N <= COREY_MAX_STATE;  B*D*L and B*N*L must fit in int64 and B*D in int32.
+ *   flags            bitwise OR of COREY_SCAN_* options, 0 for the defaults.
+ *                    COREY_SCAN_GENERAL_A: never take the fast path for structured A.  By default, when
+ *                    A[d, n] = (n + 1) * A[d, 0] holds exactly for the channels of a workgroup -- Mamba's S4D-real
+ *                    initialisation, A = -(1 .. N), which the benchmark layers use; trained weights in general do
+ *                    not -- and the storage type is 16-bit, exp(dl * A[d, n]) is formed as exp(dl * A[d, 0])^(n + 1)
+ *                    by repeated multiplication: one exponential per time step instead of one per (time step,
+ *                    state).  The result differs from the general path only by the chain's roundings (at most about
+ *                    (n + 1) * 2^-24 relative per decay factor).  The test is made on the GPU per workgroup; any
+ *                    other A takes the general path whatever the flag.
+ *                    COREY_SCAN_ONE_CHUNK: chunks_dev holds ONE entry that applies to every sequence (the chunk
+ *                    routed from a whole-tensor statistic of a batch: corey_route_device without seqlens writes one).
+ *                    Unknown bits: COREY_EINVAL.
  * y and last_state may not alias any input.  Accuracy against a double-precision evaluation of the same
  * bits: about 1e-6 relative to the row's scale for fp32 storage; for bf16 storage y carries one bf16
- * rounding (2^-9 relative) on top.
+ * rounding (half an ulp: up to 2^-8 relative) on top, for fp16 storage 2^-11.
  * ----------------------------------------------------------------------------------------------------- */
+#define COREY_SCAN_GENERAL_A 1u
+#define COREY_SCAN_ONE_CHUNK 2u
 int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
                        const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
                        const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
                        void* y, float* last_state, corey_dtype dt,
-                       int64_t B, int64_t D, int64_t N, int64_t L,
+                       int64_t B, int64_t D, int64_t N, int64_t L, uint32_t flags,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
-
-/* -------------------------------------------------------------------------------------------------------
- * corey_scan_structured_path -- switch for a fast path of selective_scan_fwd (process-wide; returns the previous
- * setting; default on).  When A[d, n] = (n + 1) * A[d, 0] holds exactly for the channels of a workgroup -- Mamba's
- * S4D-real initialisation, A = -(1 .. N), which the benchmark layers use; trained weights in general do not --
- * and the storage type is 16-bit, exp(dl * A[d, n]) is formed as exp(dl * A[d, 0])^(n + 1) by repeated
- * multiplication: one exponential per time step instead of one per (time step, state).  The result differs from
- * the general path only by the chain's roundings (at most about (n + 1) * 2^-24 relative per decay factor).  The
- * test is made on the GPU per workgroup; any other A takes the general path whatever the setting.
- * ----------------------------------------------------------------------------------------------------- */
-int corey_scan_structured_path(int enable);
 
 /* Bytes of workspace selective_scan_fwd needs (0 if the arguments are invalid): room for B and C as fp32, padded
  * along L to whole tiles and in N to a multiple of 4, in the two orders a launch may read them in (one launch can run

@@ -19,7 +19,7 @@ STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
            "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
-           "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "corey_scan_structured_path", "corey_last_error", "corey_version")
+           "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "corey_last_error", "corey_version")
 
 
 class CoreyError(RuntimeError):
@@ -69,9 +69,7 @@ def lib() -> ctypes.CDLL:
         L.corey_select_chunk_device.argtypes = [vp, vp, i64, i32, ctypes.POINTER(Policy), vp, vp]
         L.selective_scan_fwd.restype = ctypes.c_int
         L.selective_scan_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, vp, vp, vp,
-                                         ctypes.c_int, i64, i64, i64, i64, vp, ctypes.c_size_t, vp]
-        L.corey_scan_structured_path.restype = ctypes.c_int
-        L.corey_scan_structured_path.argtypes = [ctypes.c_int]
+                                         ctypes.c_int, i64, i64, i64, i64, ctypes.c_uint32, vp, ctypes.c_size_t, vp]
         L.selective_scan_fwd_plan.restype = ctypes.c_int64
         L.selective_scan_fwd_plan.argtypes = [i64, i64, i64, i32]
         L.selective_scan_fwd_plan_steps.restype = i32
@@ -112,6 +110,12 @@ def _dev(t, name):
         raise ValueError(f"{name} must be a contiguous GPU tensor")
 
 
+def _want(t, name, dtype, shape):
+    """Optional tensor `t` must have this dtype and shape (the library reads raw memory and cannot check either)."""
+    if t is not None and (t.dtype != dtype or tuple(t.shape) != tuple(shape)):
+        raise TypeError(f"{name} must be {dtype} of shape {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+
+
 def policy_default() -> Policy:
     p = Policy()
     _check(lib().corey_policy_default(ctypes.byref(p)))
@@ -150,6 +154,7 @@ def selective_state_update(state: torch.Tensor, x: torch.Tensor, delta: torch.Te
 
 
 RANGE_PARTS_BYTES = 1024 * 16      # COREY_RANGE_PARTS records of 16 bytes
+CHUNK_SLOTS = 12                   # COREY_CHUNK_SLOTS
 
 
 def causal_conv1d_silu_fwd(x: torch.Tensor, weight: torch.Tensor, bias: torch.Tensor | None = None,
@@ -184,6 +189,7 @@ def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int =
         raise ValueError("x must be [B, D, L]")
     B, D, L = x.shape
     nh = B if seqlens is not None else 1
+    _want(seqlens, "seqlens", torch.int32, (B,))
     if out is None:
         out = dict(counts=torch.empty((nh, K), dtype=torch.int32, device=x.device),   # uint32 bit patterns
                    H=torch.empty(nh, dtype=torch.float64, device=x.device),
@@ -220,6 +226,9 @@ def corey_route_device(x: torch.Tensor, K: int, policy: Policy | None = None, ep
         raise ValueError("x must be [B, D, L]")
     B, D, L = x.shape
     nh = B if seqlens is not None else 1
+    _want(seqlens, "seqlens", torch.int32, (B,))
+    _want(ema_state, "ema_state", torch.float64, (nh,))
+    _want(chunk_calls, "chunk_calls", torch.int32, (CHUNK_SLOTS,))
     p = policy if policy is not None else policy_default()
     if out is None:
         out = dict(counts=torch.empty((nh, K), dtype=torch.int32, device=x.device),
@@ -253,15 +262,11 @@ def corey_select_chunk_device(r_dev: torch.Tensor, L: int, policy: Policy | None
         raise TypeError("r_dev must be float64")
     p = policy if policy is not None else policy_default()
     nh = r_dev.numel()
+    _want(seqlens, "seqlens", torch.int32, (nh,))
     if out is None:
         out = torch.empty(nh, dtype=torch.int32, device=r_dev.device)
     _check(lib().corey_select_chunk_device(_ptr(r_dev), _ptr(seqlens), int(L), nh, ctypes.byref(p), _ptr(out), _stream()))
     return out
-
-
-def corey_scan_structured_path(enable: bool) -> bool:
-    """Switch the structured-A fast path of selective_scan_fwd on or off; returns the previous setting."""
-    return bool(lib().corey_scan_structured_path(1 if enable else 0))
 
 
 def selective_scan_fwd_plan(B: int, D: int, N: int, chunk: int) -> int:
@@ -276,23 +281,40 @@ def selective_scan_fwd_workspace(B: int, N: int, L: int) -> int:
     return int(lib().selective_scan_fwd_workspace(B, N, L))
 
 
+COREY_SCAN_GENERAL_A = 1
+COREY_SCAN_ONE_CHUNK = 2
+
+
 def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True, h0=None,
-                       seqlens=None, chunk: int = 512, chunks_dev=None, y=None, last_state=None, workspace=None):
+                       seqlens=None, chunk: int = 512, chunks_dev=None, y=None, last_state=None, workspace=None,
+                       general_a: bool = False):
     """Tensors as in include/corey.h.  Returns (y, last_state); enqueues on torch's current stream.
-    `workspace`: uint8 GPU tensor of selective_scan_fwd_workspace(B, N, L) bytes (allocated here if omitted)."""
+    `workspace`: uint8 GPU tensor of selective_scan_fwd_workspace(B, N, L) bytes (allocated here if omitted).
+    `general_a`: COREY_SCAN_GENERAL_A, i.e. never take the fast path for A[d, n] = (n + 1) A[d, 0].
+    `chunks_dev` of one entry for a batch of several sequences is passed with COREY_SCAN_ONE_CHUNK."""
     for name, t in (("u", u), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dv", Dv), ("z", z),
-                    ("delta_bias", delta_bias), ("h0", h0), ("seqlens", seqlens), ("chunks_dev", chunks_dev)):
+                    ("delta_bias", delta_bias), ("h0", h0), ("seqlens", seqlens), ("chunks_dev", chunks_dev),
+                    ("y", y), ("last_state", last_state), ("workspace", workspace)):
         _dev(t, name)
+    if u.dim() != 3 or A.dim() != 2:
+        raise ValueError("u must be [B, D, L] and A [D, N]")
     B, D, L = u.shape
     N = A.shape[1]
     if A.shape != (D, N) or Bm.shape != (B, N, L) or Cm.shape != (B, N, L) or delta.shape != u.shape:
         raise ValueError("inconsistent shapes")
-    for t in (delta, Bm, Cm, z):
-        if t is not None and t.dtype != u.dtype:
-            raise TypeError("u, delta, Bm, Cm, z must share one storage type")
-    for t in (A, Dv, delta_bias, h0):
-        if t is not None and t.dtype != torch.float32:
-            raise TypeError("A, Dv, delta_bias, h0 must be float32")
+    for name, t in (("delta", delta), ("z", z), ("y", y)):
+        _want(t, name, u.dtype, (B, D, L))
+    for name, t in (("Bm", Bm), ("Cm", Cm)):
+        _want(t, name, u.dtype, (B, N, L))
+    _want(A, "A", torch.float32, (D, N))
+    for name, t in (("Dv", Dv), ("delta_bias", delta_bias)):
+        _want(t, name, torch.float32, (D,))
+    for name, t in (("h0", h0), ("last_state", last_state)):
+        _want(t, name, torch.float32, (B, D, N))
+    _want(seqlens, "seqlens", torch.int32, (B,))
+    # a single routed chunk (the whole-tensor statistic of a batch) applies to every sequence
+    one_chunk = chunks_dev is not None and B > 1 and tuple(chunks_dev.shape) == (1,)
+    _want(chunks_dev, "chunks_dev", torch.int32, (1,) if one_chunk else (B,))
     if y is None:
         y = torch.empty_like(u)
     if last_state is None:
@@ -302,5 +324,5 @@ def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, de
     _check(lib().selective_scan_fwd(_ptr(u), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dv), _ptr(z),
                                     _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(h0), _ptr(seqlens), int(chunk),
                                     _ptr(chunks_dev), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L,
-                                    _ptr(workspace), workspace.numel(), _stream()))
+                                    (COREY_SCAN_GENERAL_A if general_a else 0) | (COREY_SCAN_ONE_CHUNK if one_chunk else 0), _ptr(workspace), workspace.numel(), _stream()))
     return y, last_state

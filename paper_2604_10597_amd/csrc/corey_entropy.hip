@@ -685,6 +685,7 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
     double part = 0.0;
     if (ok && n > 0.0)
         for (int k = threadIdx.x; k < K; k += kThreads) {
+            if (c[k] == 0u) continue;                          // an empty bin adds nothing (0 log 0 = 0 when eps = 0)
             const double p = (double)c[k] / n;
             part += p * log(p + eps);
         }
@@ -714,7 +715,7 @@ __global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* _
             }
             const int32_t c = chunk_rule(r_rule, seqlens ? (int64_t)seqlens[h] : L_all, pol);
             chunks_out[h] = c;
-            if (chunk_calls && c > 0) atomicAdd(&chunk_calls[31 - __clz(c)], 1u);
+            if (chunk_calls && c > 0 && 31 - __clz(c) < COREY_CHUNK_SLOTS) atomicAdd(&chunk_calls[31 - __clz(c)], 1u);
         }
         if (range_out) {
             range_out[2 * h] = (slots[h].lo_key == 0xffffffffu) ? INFINITY : key_value(slots[h].lo_key);
@@ -866,19 +867,38 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
 
 }  // namespace
 
+namespace {
+
+// The policy as the GPU rule will apply it: the host rule's checks (r = 0.5 is a placeholder that no mode rejects), and
+// no chunk the scan cannot run (the rule's result goes straight into selective_scan_fwd's chunks_dev and into the
+// chunk-distribution counters, which have a slot per power of two up to COREY_MAX_CHUNK).
+int check_device_policy(const char* who, const corey_policy* p, int64_t L)
+{
+    using corey::fail;
+    int32_t probe = 0;
+    const int st = corey_select_chunk(0.5, L < 1 ? 1 : L, p, &probe);
+    if (st != COREY_OK) return st;
+    if (p->mode == 1 && !corey::is_pow2(p->short_chunk)) return fail(COREY_EINVAL, "%s: short_chunk = %d", who, p->short_chunk);
+    const bool entropy = p->mode == 0 || p->mode == 1 || p->mode == 4;
+    const bool table = p->mode == 1 || p->mode == 2;
+    if ((entropy && p->c_max > COREY_MAX_CHUNK) || (table && p->short_chunk > COREY_MAX_CHUNK) ||
+        (p->mode == 2 && p->long_chunk > COREY_MAX_CHUNK) || (p->mode == 3 && p->static_chunk > COREY_MAX_CHUNK) ||
+        (p->mode == 4 && p->safe_chunk > COREY_MAX_CHUNK))
+        return fail(COREY_EINVAL, "%s: the policy can select a chunk above %d", who, COREY_MAX_CHUNK);
+    return COREY_OK;
+}
+
+}  // namespace
+
 extern "C" int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64_t L, int32_t nh,
                                          const corey_policy* p, int32_t* chunks_out, void* hip_stream)
 {
     using corey::fail;
-    using corey::is_pow2;
     if (!r_dev || !p || !chunks_out) return fail(COREY_ENULL, "corey_select_chunk_device: r_dev, p and chunks_out are required");
     if (nh < 1) return fail(COREY_EINVAL, "corey_select_chunk_device: nh = %d < 1", nh);
     if (!seqlens && L < 1) return fail(COREY_EINVAL, "corey_select_chunk_device: L = %lld < 1", (long long)L);
-    // validate the policy on the host with the host rule (r = 0.5 is a placeholder that no mode rejects)
-    int32_t probe = 0;
-    const int st = corey_select_chunk(0.5, L < 1 ? 1 : L, p, &probe);
+    const int st = check_device_policy("corey_select_chunk_device", p, L);
     if (st != COREY_OK) return st;
-    if (p->mode == 1 && !is_pow2(p->short_chunk)) return fail(COREY_EINVAL, "corey_select_chunk_device: short_chunk = %d", p->short_chunk);
     k_select_chunk<<<dim3((unsigned)((nh + 63) / 64)), dim3(64), 0, static_cast<hipStream_t>(hip_stream)>>>(r_dev, seqlens, L, nh, *p, chunks_out);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "corey_select_chunk_device launch");
@@ -949,11 +969,8 @@ extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int6
     if (!p || !chunks_out) return fail(COREY_ENULL, "corey_route_device: p and chunks_out are required");
     if (ema_state && !(ema_lambda >= 0.0 && ema_lambda < 1.0))
         return fail(COREY_EINVAL, "corey_route_device: ema_lambda = %g outside [0, 1)", ema_lambda);
-    // validate the policy on the host with the host rule (r = 0.5 is a placeholder that no mode rejects)
-    int32_t probe = 0;
-    const int st = corey_select_chunk(0.5, L < 1 ? 1 : L, p, &probe);
+    const int st = check_device_policy("corey_route_device", p, L);
     if (st != COREY_OK) return st;
-    if (p->mode == 1 && !corey::is_pow2(p->short_chunk)) return fail(COREY_EINVAL, "corey_route_device: short_chunk = %d", p->short_chunk);
     return entropy_hist_impl("corey_route_device", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
                              workspace, workspace_bytes_given, hip_stream, p, chunks_out, ema_lambda, ema_state, chunk_calls, range_parts);
 }

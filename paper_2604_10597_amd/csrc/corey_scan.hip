@@ -1,8 +1,6 @@
 // selective_scan_fwd: host entry.  Validates the arguments, lays out the launch and hands over to the kernels of
 // the storage type (corey_scan_impl.h, instantiated per type in corey_scan_f32/bf16/f16.hip).
 #include <hip/hip_runtime.h>
-#include <atomic>
-#include <cstdlib>
 
 #include "corey_scan_impl.h"
 
@@ -14,13 +12,7 @@ void launch_scan_f16(const ScanArgs& a, const LaunchPlan& p);
 
 namespace {
 int64_t padded_len(int64_t L) { return (L + corey_scan::kPad + 3) / 4 * 4; }
-std::atomic<int> g_structured{1};
 }  // namespace
-
-extern "C" int corey_scan_structured_path(int enable)
-{
-    return g_structured.exchange(enable ? 1 : 0);
-}
 
 extern "C" size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L)
 {
@@ -48,7 +40,7 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
                                   const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
                                   const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
                                   void* y, float* last_state, corey_dtype dt, int64_t B, int64_t D, int64_t N, int64_t L,
-                                  void* workspace, size_t workspace_bytes, void* hip_stream)
+                                  uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     using corey::fail;
     if (!u || !delta || !A || !Bm || !Cm || !y || !last_state)
@@ -62,6 +54,7 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
         return fail(COREY_ESHAPE, "selective_scan_fwd: tensor sizes overflow the kernel's indexing");
     if (chunk < COREY_MIN_CHUNK || chunk > COREY_MAX_CHUNK || !corey::is_pow2(chunk))
         return fail(COREY_EINVAL, "selective_scan_fwd: chunk = %d must be a power of two in [%d, %d]", chunk, COREY_MIN_CHUNK, COREY_MAX_CHUNK);
+    if (flags & ~(COREY_SCAN_GENERAL_A | COREY_SCAN_ONE_CHUNK)) return fail(COREY_EINVAL, "selective_scan_fwd: unknown flags 0x%x", flags);
 
     const size_t need = selective_scan_fwd_workspace(B, N, L);
     if (!workspace || workspace_bytes < need)
@@ -84,7 +77,8 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.ws_C8 = a.ws_B8 + (size_t)B * a.Np * a.Lpad;
     a.L = L; a.rows_total = B * D; a.D = (int32_t)D; a.N = (int32_t)N; a.chunk = chunk; a.softplus = delta_softplus ? 1 : 0;
     a.vector_ok = vector_ok ? 1 : 0;
-    a.allow_structured = g_structured.load();
+    a.allow_structured = (flags & COREY_SCAN_GENERAL_A) ? 0 : 1;
+    a.one_chunk = (flags & COREY_SCAN_ONE_CHUNK) ? 1 : 0;
     // LDS budget for the per-row arrays (carried state and A): at most 32 rows and 8 KiB each, so that the staging
     // buffers and the rows of a workgroup stay below what a compute unit gives four workgroups (chunks below 64,
     // which would put more than 32 rows into a workgroup, run with idle lanes).
@@ -94,17 +88,6 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     corey_scan::LaunchPlan p;
     a.d16 = corey_scan::plan_d16(B, D, chunk, a.rows_cap);
     a.klo = corey_scan::plan_klo(B, D, chunk, a.d16);
-#ifdef COREY_DEV_KNOBS
-    if (const char* e = getenv("COREY_ITEMS")) {
-        const int k = atoi(e);
-        a.d16 = ((k == 8 && chunk <= 512) || (k == 4 && chunk <= 256)) ? 0 : D;
-        a.klo = a.d16 == 0 ? k : 8;
-    }
-    if (const char* e = getenv("COREY_D16")) {
-        a.d16 = chunk <= 512 ? (atoi(e) >= D ? D : atoi(e) / 32 * 32) : D;
-        a.klo = 8;
-    }
-#endif
     p.chunk = chunk;
     p.routed = chunks_dev != nullptr;
     p.B = B; p.D = D; p.N = N;

@@ -411,13 +411,14 @@ struct ScanArgs {
     int32_t softplus;
     int32_t allow_structured;   // take the power-chain path when A[d, n] = (n + 1) A[d, 0] (16-bit storage only)
     int32_t vector_ok;      // rows of the [.., L] tensors are 16-byte aligned
+    int32_t one_chunk;      // chunks_dev holds a single entry that applies to every sequence
 };
 
 __device__ __forceinline__ int resolve_chunk(const ScanArgs& a, int b)
 {
     int chunk = a.chunk;
     if (a.chunks_dev) {
-        const int c = a.chunks_dev[b];
+        const int c = a.chunks_dev[a.one_chunk ? 0 : b];
         if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
     }
     return chunk;
@@ -433,7 +434,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, const T* __restrict__ Cm, float* __restrict__ ws_B,
                                                      float* __restrict__ ws_C, float* __restrict__ ws_B8, float* __restrict__ ws_C8,
                                                      const int32_t* __restrict__ seqlens, const int32_t* __restrict__ chunks_dev,
-                                                     int chunk_host, int64_t d16_host, int klo_host, int64_t Bn, int64_t D, int rows_cap,
+                                                     int one_chunk, int chunk_host, int64_t d16_host, int klo_host, int64_t Bn, int64_t D, int rows_cap,
                                                      int Nreal, int N, int64_t L, int64_t Lpad)
 {
     const int b = blockIdx.y;
@@ -441,7 +442,7 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
     int64_t d16 = d16_host;
     int klo = klo_host;
     if (chunks_dev) {
-        const int c = chunks_dev[b];
+        const int c = chunks_dev[one_chunk ? 0 : b];
         if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
         d16 = plan_d16(Bn, D, chunk, rows_cap);
         klo = plan_klo(Bn, D, chunk, d16);
@@ -977,7 +978,7 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
     rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
     k_relayout_bc<T><<<dim3((unsigned)rb, (unsigned)p.B), dim3(256), 0, p.stream>>>(
         static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.ws_B8, a.ws_C8, a.seqlens, a.chunks_dev,
-        p.chunk, a.d16, a.klo, p.B, p.D, a.rows_cap, (int)p.N, a.Np, a.L, a.Lpad);
+        a.one_chunk, p.chunk, a.d16, a.klo, p.B, p.D, a.rows_cap, (int)p.N, a.Np, a.L, a.Lpad);
     int64_t gx = 0, g;
     size_t lds = 0, l;
     if (p.routed) {

@@ -104,15 +104,34 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
     ss = lambda **kw: lib.selective_scan_fwd(
         kw.get("u", fake), fake, fake, fake, fake, none, none, none, 1, none, none, kw.get("chunk", 256), none,
         kw.get("y", fake), kw.get("last", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("N", 16),
-        kw.get("L", 64), kw.get("ws", fake), kw.get("wsb", 1 << 30), none)
+        kw.get("L", 64), kw.get("flags", 0), kw.get("ws", fake), kw.get("wsb", 1 << 30), none)
     assert ss(u=none) == 2 and ss(y=none) == 2 and ss(last=none) == 2
-    assert ss(dt=3) == 1
+    assert ss(dt=3) == 1 and ss(flags=4) == 1 and ss(flags=0x80000001) == 1
     for bad in (0, 8, 100, 4096, -64):
         assert ss(chunk=bad) == 1
     assert ss(N=0) == 3 and ss(N=257) == 3 and ss(B=0) == 3 and ss(L=0) == 3 and ss(B=70000) == 3
     assert ss(ws=none) == 7 and ss(wsb=64) == 7
     assert lib.selective_scan_fwd_workspace(1, 16, 64) == 4 * 16 * (64 + 2048) * 4
     assert lib.selective_scan_fwd_workspace(0, 16, 64) == 0 and lib.selective_scan_fwd_workspace(1, 300, 64) == 0
+
+
+def test_device_rule_rejects_a_policy_that_can_pick_a_chunk_the_scan_cannot_run():
+    """corey_select_chunk_device / corey_route_device feed selective_scan_fwd's chunks_dev and the chunk-distribution
+    counters (one slot per power of two up to COREY_MAX_CHUNK): a policy that can select more is refused on the host."""
+    lib = binding.lib()
+    fake, none = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    for field, mode in (("c_max", 0), ("c_max", 1), ("c_max", 4), ("static_chunk", 3), ("long_chunk", 2), ("short_chunk", 2),
+                        ("short_chunk", 1), ("safe_chunk", 4)):
+        p = binding.policy_default()
+        p.mode = mode
+        setattr(p, field, 4096)
+        assert lib.corey_select_chunk_device(fake, none, 4096, 1, ctypes.byref(p), fake, none) == 1, (field, mode)
+        assert lib.corey_route_device(fake, 1, 1, 4, 8, none, 16, 1e-8, 1, 1, ctypes.byref(p), 0.0, none, none, fake, fake, fake, none,
+                                      none, fake, fake, 1 << 20, none) == 1, (field, mode)
+        assert binding.corey_select_chunk(0.99, 1 << 20, p) > 0            # the host rule itself has no such limit
+    p = binding.policy_default()
+    p.static_chunk = 4096                                                  # unused by the mode: accepted
+    assert lib.corey_select_chunk_device(none, none, 4096, 1, ctypes.byref(p), fake, none) == 2   # (fails later, on the NULL r)
 
 
 def test_launch_plan_of_the_scan():

@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import paper_2604_10597_amd as corey
-from gpu_util import assert_close, fp32_rtol, oracle_scan, store_bits, upload, y_rtol, y_to_f64
+from gpu_util import assert_close, chain_rtol, check_y, fp32_rtol, oracle_scan, store_bits, upload, y_rtol, y_to_f64
 from paper_2604_10597_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -22,11 +22,11 @@ def _say(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def _run(d, chunk, use_z=True, use_h0=True, chunks_dev=None, softplus=True):
+def _run(d, chunk, use_z=True, use_h0=True, chunks_dev=None, softplus=True, general_a=False):
     y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"] if use_z else None,
                                        delta_bias=d["delta_bias"], delta_softplus=softplus,
                                        h0=d.get("h0") if use_h0 else None, seqlens=d["seqlens"], chunk=chunk,
-                                       chunks_dev=chunks_dev)
+                                       chunks_dev=chunks_dev, general_a=general_a)
     torch.cuda.synchronize()
     return y_to_f64(y), last.cpu().numpy().astype(np.float64)
 
@@ -36,11 +36,15 @@ def _parity(cfg, chunks, a_kind="mamba", with_h0=False, use_z=True):
     d = upload(w)
     y_ref, s_ref = oracle_scan(w, use_z=use_z)
     worst = 0.0
-    for chunk in chunks:
-        _say(f"scan {cfg.name} B{cfg.B} D{cfg.D} N{cfg.N} L{cfg.L} {cfg.dtype} A={a_kind} chunk={chunk} z={use_z} h0={with_h0}")
-        y, s = _run(d, chunk, use_z=use_z)
-        worst = max(worst, assert_close(y, y_ref, y_rtol(cfg), f"y chunk {chunk}", store_bits(cfg)))
-        assert_close(s, s_ref, fp32_rtol(cfg.L), f"last_state chunk {chunk}")
+    # a structured A takes the power-chain path by default: run the general path on it as well (the benchmark's figures
+    # are measured on the general path)
+    for general_a in ((False, True) if a_kind == "mamba" and cfg.dtype != wl.F32 else (False,)):
+        for chunk in chunks:
+            _say(f"scan {cfg.name} B{cfg.B} D{cfg.D} N{cfg.N} L{cfg.L} {cfg.dtype} A={a_kind} chunk={chunk} z={use_z} h0={with_h0} "
+                 f"general_a={general_a}")
+            y, s = _run(d, chunk, use_z=use_z, general_a=general_a)
+            worst = max(worst, check_y(y, y_ref, cfg, f"y chunk {chunk} general_a={general_a}")[0])
+            assert_close(s, s_ref, fp32_rtol(cfg.L), f"last_state chunk {chunk} general_a={general_a}")
     return worst
 
 
@@ -119,6 +123,14 @@ def test_per_sequence_device_chunks():
     for b, c in enumerate((2048, 64, 512, 256)):
         yb, sb = _run(d, c)
         assert np.array_equal(yb[b], y[b]) and np.array_equal(sb[b], s[b])
+    # one routed chunk for the whole batch (COREY_SCAN_ONE_CHUNK): equal to a uniform launch with that chunk
+    y1, s1 = _run(d, 2048, chunks_dev=torch.tensor([128], dtype=torch.int32, device="cuda"))
+    yu, su = _run(d, 128)
+    assert np.array_equal(y1, yu) and np.array_equal(s1, su)
+    with pytest.raises(TypeError):
+        _run(d, 256, chunks_dev=torch.tensor([128, 128], dtype=torch.int32, device="cuda"))     # neither one entry nor B
+    with pytest.raises(TypeError):
+        _run(d, 256, chunks_dev=torch.tensor([128, 128, 128, 128], device="cuda"))              # int64
 
 
 def test_device_side_routing_matches_the_oracle_rule():
@@ -230,44 +242,43 @@ def upload_one(store):
 
 
 def test_structured_A_fast_path():
-    """A[d, n] = (n + 1) A[d, 0] with 16-bit storage takes the power-chain path: it must meet the same bounds as the
-    general path, differ from it only by the chain's roundings, and leave every other A untouched."""
-    try:
-        for name, dtype in (("c2_mamba370m", wl.BF16), ("paper_w1_fp16", wl.F16)):
-            cfg = wl.scaled(wl.CONFIGS[name], D=40, L=1300, dtype=dtype)
-            w = wl.make(cfg, a_kind="mamba", with_h0=True)
-            d = upload(w)
-            y_ref, s_ref = oracle_scan(w)
-            for chunk in (64, 512, 1024, 2048):
-                _say(f"scan structured A {name} {dtype} chunk={chunk}")
-                corey.corey_scan_structured_path(True)
-                y1, s1 = _run(d, chunk)
-                assert corey.corey_scan_structured_path(False) is True
-                y0, s0 = _run(d, chunk)
-                for y, s in ((y1, s1), (y0, s0)):
-                    assert_close(y, y_ref, y_rtol(cfg), f"y chunk {chunk}", store_bits(cfg))
-                    assert_close(s, s_ref, fp32_rtol(cfg.L), f"state chunk {chunk}")
-                assert not np.array_equal(s1, s0)             # the two paths really are different code
-                assert_close(s1, s0, 4e-6, "structured against general state")
-            # an unstructured A, and a structured one whose first channel is off by one ulp, take the general path
-            wr = wl.make(cfg, a_kind="random")
-            dr = upload(wr)
-            corey.corey_scan_structured_path(True)
-            ya, sa = _run(dr, 512)
-            corey.corey_scan_structured_path(False)
-            yb, sb = _run(dr, 512)
-            assert np.array_equal(ya, yb) and np.array_equal(sa, sb)
-        # fp32 storage never takes it
-        cfg = wl.scaled(wl.CONFIGS["c0_tiny_f32"], D=16, L=512)
-        w = wl.make(cfg)
+    """A[d, n] = (n + 1) A[d, 0] with 16-bit storage takes the power-chain path unless COREY_SCAN_GENERAL_A is given: it
+    must meet the same bounds as the general path, differ from it only by the chain's roundings (gpu_util.chain_rtol),
+    and leave every other A untouched."""
+    for name, dtype in (("c2_mamba370m", wl.BF16), ("paper_w1_fp16", wl.F16)):
+        cfg = wl.scaled(wl.CONFIGS[name], D=40, L=1300, dtype=dtype)
+        w = wl.make(cfg, a_kind="mamba", with_h0=True)
         d = upload(w)
-        corey.corey_scan_structured_path(True)
-        ya, sa = _run(d, 256)
-        corey.corey_scan_structured_path(False)
-        yb, sb = _run(d, 256)
+        y_ref, s_ref = oracle_scan(w)
+        for chunk in (64, 512, 1024, 2048):
+            _say(f"scan structured A {name} {dtype} chunk={chunk}")
+            y1, s1 = _run(d, chunk)
+            y0, s0 = _run(d, chunk, general_a=True)
+            for y, s in ((y1, s1), (y0, s0)):
+                check_y(y, y_ref, cfg, f"y chunk {chunk}")
+                assert_close(s, s_ref, fp32_rtol(cfg.L), f"state chunk {chunk}")
+            assert not np.array_equal(s1, s0)             # the two paths really are different code
+            assert_close(s1, s0, chain_rtol(cfg.N), "structured against general state")
+        # an unstructured A takes the general path whatever the flag
+        wr = wl.make(cfg, a_kind="random")
+        dr = upload(wr)
+        ya, sa = _run(dr, 512)
+        yb, sb = _run(dr, 512, general_a=True)
         assert np.array_equal(ya, yb) and np.array_equal(sa, sb)
-    finally:
-        corey.corey_scan_structured_path(True)
+    # fp32 storage never takes it
+    cfg = wl.scaled(wl.CONFIGS["c0_tiny_f32"], D=16, L=512)
+    w = wl.make(cfg)
+    d = upload(w)
+    ya, sa = _run(d, 256)
+    yb, sb = _run(d, 256, general_a=True)
+    assert np.array_equal(ya, yb) and np.array_equal(sa, sb)
+    # an unknown flag bit is an error, found before any launch
+    lib, ptr = corey.binding.lib(), corey.binding._ptr
+    ws = torch.empty(corey.selective_scan_fwd_workspace(cfg.B, cfg.N, cfg.L), dtype=torch.uint8, device="cuda")
+    y, last = torch.empty_like(d["u"]), torch.empty((cfg.B, cfg.D, cfg.N), dtype=torch.float32, device="cuda")
+    st = lib.selective_scan_fwd(ptr(d["u"]), ptr(d["delta"]), ptr(d["A"]), ptr(d["B"]), ptr(d["C"]), None, None, None, 1, None, None, 256,
+                                None, ptr(y), ptr(last), 0, cfg.B, cfg.D, cfg.N, cfg.L, 4, ptr(ws), ws.numel(), None)
+    assert st == 1
 
 
 def test_invariants_on_the_gpu_path():
@@ -377,16 +388,12 @@ def test_structured_path_on_every_row_at_full_size(chunk):
     w = wl.make(cfg)
     d = upload(w)
     _say(f"structured against general, every row, chunk {chunk}")
-    try:
-        res = []
-        for on in (True, False):
-            corey.corey_scan_structured_path(on)
-            y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
-                                               delta_bias=d["delta_bias"], chunk=chunk)
-            torch.cuda.synchronize()
-            res.append((y.float(), last))
-    finally:
-        corey.corey_scan_structured_path(True)
+    res = []
+    for general_a in (False, True):
+        y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
+                                           delta_bias=d["delta_bias"], chunk=chunk, general_a=general_a)
+        torch.cuda.synchronize()
+        res.append((y.float(), last))
     (y1, s1), (y0, s0) = res
     assert torch.isfinite(y1).all() and torch.isfinite(y0).all()
     tol = 0.01 * (y0.abs() + y0.pow(2).mean(-1, keepdim=True).sqrt())          # a bf16 ulp is 0.4 to 0.8 % of the value
@@ -417,7 +424,9 @@ def test_mixed_launch_with_padded_sequences_and_a_chunk_per_sequence():
 
 @pytest.mark.parametrize("name", ["c1_mamba130m", "c2_mamba370m", "c3_mamba1p4b", "c4_mamba2p8b", "paper_w1_fp16"])
 def test_full_size_sampled_rows(name):
-    """The benchmark's launch configuration at full size; the oracle recomputes sampled channels one by one."""
+    """The benchmark's launch configuration at full size; the oracle recomputes sampled channels one by one.  Every
+    launch runs twice: on the general path (COREY_SCAN_GENERAL_A, the path every headline figure is measured on) and with
+    the fast path for the layers' structured A left on."""
     cfg = wl.CONFIGS[name]
     w = wl.make(cfg)
     d = upload(w)
@@ -425,34 +434,42 @@ def test_full_size_sampled_rows(name):
     y_ref, s_ref = oracle_scan(w, rows=rows)
     ent = corey.corey_entropy_hist(d["u"], cfg.K)
     chunk = corey.corey_select_chunk(ent["r"].item(), cfg.L)
-    for c in sorted({chunk, 64, 2048}):
-        _say(f"scan full size {name} chunk={c} (routed={chunk})")
-        y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
-                                           delta_bias=d["delta_bias"], seqlens=d["seqlens"], chunk=c)
-        torch.cuda.synchronize()
-        ys = y[:, torch.from_numpy(rows).cuda(), :]
-        assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y chunk {c}", store_bits(cfg))
-        assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state chunk {c}")
+    idx = torch.from_numpy(rows).cuda()
+    worst = [0.0, 0.0, 0.0]
+
+    def check(y, last, what):
         assert torch.isfinite(y.to(torch.float32)).all()
-    # the launch the benchmark times: statistic and rule on the GPU, the scan reading the chunk from device memory
-    _say(f"scan full size {name} device-routed")
-    route = corey.corey_route_device(d["u"], cfg.K, corey.policy_default(), seqlens=d["seqlens"])
-    y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
-                                       seqlens=d["seqlens"], chunk=chunk, chunks_dev=route["chunks"])
-    torch.cuda.synchronize()
-    ys = y[:, torch.from_numpy(rows).cuda(), :]
-    assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), f"{name} y device-routed", store_bits(cfg))
-    assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state device-routed")
+        a, b = check_y(y_to_f64(y[:, idx, :]), y_ref, cfg, f"{name} y {what}")
+        c = assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"{name} state {what}")
+        worst[:] = max(worst[0], a), max(worst[1], b), max(worst[2], c)
+
+    for general_a in (True, False):
+        for c in sorted({chunk, 64, 2048}):
+            _say(f"scan full size {name} chunk={c} (routed={chunk}) general_a={general_a}")
+            y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
+                                               delta_bias=d["delta_bias"], seqlens=d["seqlens"], chunk=c, general_a=general_a)
+            torch.cuda.synchronize()
+            check(y, last, f"chunk {c} general_a={general_a}")
+        # the launch the benchmark times: statistic and rule on the GPU, the scan reading the chunk from device memory
+        _say(f"scan full size {name} device-routed general_a={general_a}")
+        route = corey.corey_route_device(d["u"], cfg.K, corey.policy_default(), seqlens=d["seqlens"])
+        y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
+                                           seqlens=d["seqlens"], chunk=chunk, chunks_dev=route["chunks"], general_a=general_a)
+        torch.cuda.synchronize()
+        check(y, last, f"device-routed general_a={general_a}")
+    print(f"[worst] {name}: y error / stated bound {worst[0]:.3f}, / fp32 computation bound {worst[1]:.3f}, state / bound {worst[2]:.3f}",
+          flush=True)
 
 
-@pytest.mark.parametrize("lens", [(8192, 512), (2048, 512), (8192, 8192)])
-def test_padded_pairs_of_the_mixed_regime_layer_at_full_size(lens):
+@pytest.mark.parametrize("general_a", [True, False])
+@pytest.mark.parametrize("lens", [(8192, 512), (8192, 2048), (2048, 512), (8192, 8192)])
+def test_padded_pairs_of_the_mixed_regime_layer_at_full_size(lens, general_a):
     """The mixed-regime layer (two sequences of a 1.4B-shaped layer, right-padded to 8192) with the other pairs of its
     three prompt lengths: per-sequence statistic and rule on the GPU, the scan reading each sequence's chunk from device
     memory.  Counts against the oracle on everything, y and state on sampled channels."""
     import oracle
     cfg = wl.scaled(wl.CONFIGS["c3_mamba1p4b"], seqlens=lens)
-    _say(f"mixed-regime pair {lens} at full size")
+    _say(f"mixed-regime pair {lens} at full size general_a={general_a}")
     w = wl.make(cfg)
     d = upload(w)
     rows = np.unique(np.concatenate([[0, 1, cfg.D - 1], np.random.default_rng(sum(lens)).integers(0, cfg.D, 9)]))
@@ -461,7 +478,7 @@ def test_padded_pairs_of_the_mixed_regime_layer_at_full_size(lens):
     pol.mode = 1                                                  # sequence-length gate, then the entropy rule
     route = corey.corey_route_device(d["u"], cfg.K, pol, seqlens=d["seqlens"])
     y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
-                                       seqlens=d["seqlens"], chunk=512, chunks_dev=route["chunks"])
+                                       seqlens=d["seqlens"], chunk=512, chunks_dev=route["chunks"], general_a=general_a)
     torch.cuda.synchronize()
     ref = oracle.entropy_hist(w.val["u"], cfg.K, seqlens=w.seqlens)
     assert np.array_equal(route["counts"].cpu().numpy().view(np.uint32).reshape(ref["counts"].shape), ref["counts"])
@@ -470,7 +487,7 @@ def test_padded_pairs_of_the_mixed_regime_layer_at_full_size(lens):
         st, c, margin = oracle.select_chunk(float(ref["r"][b]), n, opol)
         assert st == oracle.OK and (margin < 1e-9 or route["chunks"][b].item() == c)
     ys = y[:, torch.from_numpy(rows).cuda(), :]
-    assert_close(y_to_f64(ys), y_ref, y_rtol(cfg), "y", store_bits(cfg))
+    check_y(y_to_f64(ys), y_ref, cfg, "y")
     assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), "state")
     for b, n in enumerate(lens):
         assert (y[b, :, n:] == 0).all()
