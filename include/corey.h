@@ -108,6 +108,26 @@ int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int6
 size_t corey_entropy_hist_workspace(int64_t B, int32_t K);
 
 /* -------------------------------------------------------------------------------------------------------
+ * corey_entropy_hist_static -- corey_entropy_hist for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as corey_entropy_hist, minus the workspace: the scratch memory is a buffer of
+ * COREY_STATIC_SCRATCH_BYTES built into the library's GPU code (each GPU the library runs on holds one copy until the
+ * process ends).  The call allocates and frees nothing, on the host or on the GPU.
+ *   Limit: corey_entropy_hist_workspace(B, K) <= COREY_STATIC_SCRATCH_BYTES (e.g. B = 1 with any K, B <= 60 at
+ *   K = 256); beyond it COREY_EWORKSPACE, nothing launched.
+ *   Every call on one GPU uses that GPU's one buffer: calls that may overlap on a GPU (different streams, different
+ *   threads) race on it and must be ordered by the caller.  The buffer keeps the last call's contents; the kernels
+ *   clear what has to start at zero, as they do for a caller's workspace.
+ *   Errors besides those of corey_entropy_hist: COREY_EHIP if the buffer's address cannot be obtained,
+ *   COREY_EUNSUPPORTED for a device index of 64 or more.
+ * ----------------------------------------------------------------------------------------------------- */
+#define COREY_STATIC_SCRATCH_BYTES (1 << 20)
+int corey_entropy_hist_static(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
+                              const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
+                              uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
+                              const void* range_parts, void* hip_stream);
+
+/* -------------------------------------------------------------------------------------------------------
  * corey_select_chunk -- Eq. 2:  C = clip(2^round(log2(c_min + r (c_max - c_min))), c_min, c_max).
  *
  * Pure host function (HOST pointers, no GPU work), evaluated in double; round(v) = floor(v + 0.5).

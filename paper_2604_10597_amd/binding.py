@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("COREY_LIB") or os.path.join(_HERE, "libcorey.so")   #
 COREY_F32, COREY_BF16, COREY_F16 = 0, 1, 2
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
-EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
+EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_static", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
            "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
            "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "corey_last_error", "corey_version")
 
@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.corey_entropy_hist.restype = ctypes.c_int
         L.corey_entropy_hist.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp, vp,
                                          ctypes.c_size_t, vp]
+        L.corey_entropy_hist_static.restype = ctypes.c_int
+        L.corey_entropy_hist_static.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp, vp]
         L.selective_state_update.restype = ctypes.c_int
         L.selective_state_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, i64, i64, i64, vp]
         L.causal_conv1d_silu_fwd.restype = ctypes.c_int
@@ -202,6 +204,29 @@ def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int =
                                     _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
                                     _ptr(range_parts), _ptr(workspace), workspace.numel(), _stream()))
     out["workspace"] = workspace
+    return out
+
+
+STATIC_SCRATCH_BYTES = 1 << 20     # COREY_STATIC_SCRATCH_BYTES
+
+
+def corey_entropy_hist_static(x: torch.Tensor, K: int, out: dict, eps: float = 1e-8, stride: int = 1,
+                              seqlens: torch.Tensor | None = None, block: int = 1, range_parts: torch.Tensor | None = None):
+    """corey_entropy_hist on the library's built-in scratch buffer: nothing is allocated, here or in the library, so
+    `out` (dict(counts, H, r[, range]) of GPU tensors, as corey_entropy_hist returns) must be given."""
+    _dev(x, "x"), _dev(seqlens, "seqlens")
+    if x.dim() != 3:
+        raise ValueError("x must be [B, D, L]")
+    B, D, L = x.shape
+    nh = B if seqlens is not None else 1
+    _want(seqlens, "seqlens", torch.int32, (B,))
+    _want(out["counts"], "counts", torch.int32, (nh, K))
+    _want(out["H"], "H", torch.float64, (nh,))
+    _want(out["r"], "r", torch.float64, (nh,))
+    _want(out.get("range"), "range", torch.float32, (nh, 2))
+    _check(lib().corey_entropy_hist_static(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride, block,
+                                           _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
+                                           _ptr(range_parts), _stream()))
     return out
 
 

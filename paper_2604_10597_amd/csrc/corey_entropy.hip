@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 
 #include "corey_internal.h"
 #include "corey_range.h"
@@ -957,6 +958,63 @@ extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int6
 {
     return entropy_hist_impl("corey_entropy_hist", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
                              workspace, workspace_bytes_given, hip_stream, nullptr, nullptr, 0.0, nullptr, nullptr, range_parts);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// corey_entropy_hist_static: the same statistic for callers that cannot allocate (HIP graph capture, serving loops
+// that may not call hipMalloc).  The workspace of corey_entropy_hist lives in an array in the GPU's global memory that is
+// part of the library's code object: every GPU the library runs on holds its own copy at its own address until the
+// process ends.  On the host the array's name is only a handle: the address kernels can use is asked for once per
+// device (hipGetSymbolAddress, with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[COREY_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};      // address of `scratch` on each device, filled on first use
+
+// The current device's copy of `scratch` (NULL after recording the error).
+void* static_scratch(const char* who)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        corey::hip_fail(e, who);
+        return nullptr;
+    }
+    if (dev < 0 || dev >= kMaxDevices) {
+        corey::fail(COREY_EUNSUPPORTED, "%s: device index %d beyond the %d this entry point keeps an address for", who, dev, kMaxDevices);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            corey::hip_fail(e, "hipGetSymbolAddress(scratch)");
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" int corey_entropy_hist_static(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
+                                         int32_t K, double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out,
+                                         double* r_out, float* range_out, const void* range_parts, void* hip_stream)
+{
+    const size_t need = corey_entropy_hist_workspace(B, K);     // 0 for invalid B or K: the common checks below name those
+    if (need > COREY_STATIC_SCRATCH_BYTES)
+        return corey::fail(COREY_EWORKSPACE, "corey_entropy_hist_static: B = %lld with K = %d needs %zu bytes of scratch, the built-in "
+                           "buffer holds %d (use corey_entropy_hist with a workspace of your own)", (long long)B, K, need,
+                           COREY_STATIC_SCRATCH_BYTES);
+    void* ws = static_scratch("corey_entropy_hist_static");
+    if (!ws) return COREY_EHIP;
+    return entropy_hist_impl("corey_entropy_hist_static", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out,
+                             range_out, ws, COREY_STATIC_SCRATCH_BYTES, hip_stream, nullptr, nullptr, 0.0, nullptr, nullptr, range_parts);
 }
 
 extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
