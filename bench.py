@@ -351,7 +351,7 @@ def main() -> int:
 
         def layer_token(i):
             corey.binding._check(lib.causal_conv1d_silu_fwd(ptr(xt), ptr(cw), ptr(cb), ptr(win[i & 1]), ptr(ut), ptr(win[(i & 1) ^ 1]),
-                                                             ptr(cparts), corey.binding._dtype_code(xt), Bd, cfg.D, 1, 4,
+                                                             ptr(cparts), None, 0, corey.binding._dtype_code(xt), Bd, cfg.D, 1, 4,
                                                              corey.binding._stream()))
             corey.selective_state_update(dd["state"], ut.view(Bd, cfg.D), dd["delta"], dd["A"], dd["Bt"], dd["Ct"], Dv=dd["D"],
                                          z=dd["z"], delta_bias=dd["delta_bias"], y=yd)

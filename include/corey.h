@@ -208,6 +208,37 @@ int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int6
                        int32_t* chunks_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------
+ * corey_entropy_hist_onesweep -- Eq. 1 and r = H / log K for a 16-bit tensor from ONE pass over it.
+ *
+ * The paper's estimator reads the tensor twice (a min/max pass, then a bin-count pass: "Entropy Estimation Protocol";
+ * its overhead budget counts 2 * N * sizeof bytes, "Active-Mode Overhead Budget").  For 16-bit storage one pass
+ * suffices: count how often each of the 65536 bit patterns occurs, then take the range and the K bin counts from
+ * that table.  A value's bin depends on the value and the range only, so the counts, H and r are exactly those of
+ * corey_entropy_hist (same binary32 bin expression, applied once per occurring pattern with its multiplicity).
+ * Whole-tensor statistic, every value (no seqlens, no sampling).
+ *
+ *   x           DEVICE, [B, D, L] in `dt`; dt must be COREY_BF16 or COREY_F16 (COREY_F32: COREY_EUNSUPPORTED).
+ *   p, chunks_out   HOST policy and DEVICE int32[1], or both NULL: with a policy the chunk rule is applied to r on
+ *               the GPU as by corey_route_device (sequence length L).
+ *   counts_out  DEVICE uint32[K].   H_out, r_out: DEVICE double[1].   range_out: DEVICE float[2] or NULL.
+ *   table_ws    DEVICE, corey_pattern_table_workspace() bytes (about 33 MiB: one 128 KiB table per compute unit),
+ *               256-byte aligned; scratch, contents undefined afterwards.
+ * Errors: COREY_ENULL, COREY_EINVAL, COREY_ESHAPE (B*D*L >= 2^32), COREY_EUNSUPPORTED, COREY_EWORKSPACE, COREY_EHIP.
+ *
+ * corey_entropy_hist_from_table -- the same statistic from a table that causal_conv1d_silu_fwd filled while it wrote
+ * the tensor (its `pattern_table` argument): no pass over the tensor at all, which is how the paper proposes to make
+ * routing cheap ("fuse the entropy statistic more deeply").  Arguments as above; L is only the sequence length the
+ * rule is applied for.  The table is consumed: one call per producer call.
+ * ----------------------------------------------------------------------------------------------------- */
+size_t corey_pattern_table_workspace(void);
+int corey_entropy_hist_onesweep(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, int32_t K, double eps,
+                                const corey_policy* p, int32_t* chunks_out, uint32_t* counts_out, double* H_out,
+                                double* r_out, float* range_out, void* table_ws, size_t table_ws_bytes, void* hip_stream);
+int corey_entropy_hist_from_table(corey_dtype dt, int64_t L, int32_t K, double eps, const corey_policy* p,
+                                  int32_t* chunks_out, uint32_t* counts_out, double* H_out, double* r_out,
+                                  float* range_out, void* table_ws, size_t table_ws_bytes, void* hip_stream);
+
+/* -------------------------------------------------------------------------------------------------------
  * causal_conv1d_silu_fwd -- the step before the path: the causal depthwise convolution and SiLU that produce the
  * scan input u (step (1) of the paper's inline hook, "Active-Mode Overhead Budget": convolution, then the entropy of
  * the post-convolution tensor, then the rule, then the scan), with the range of u taken in the same pass (the paper
@@ -224,11 +255,15 @@ int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int6
  *               overlap state_in.
  *   range_parts DEVICE, COREY_RANGE_PARTS * 16 bytes, or NULL: partial minima / maxima (and a NaN flag) of the
  *               values of u *as stored*, for corey_entropy_hist / corey_route_device on this u.
- * Errors: COREY_ENULL, COREY_EINVAL (dtype, W), COREY_ESHAPE.
+ *   pattern_table, pattern_table_bytes   DEVICE, corey_pattern_table_workspace() bytes, 256-byte aligned, or NULL / 0
+ *               (16-bit storage only): the kernel also counts the bit patterns of the values of u it stores, so that
+ *               corey_entropy_hist_from_table gives the exact statistic of u without reading u at all.
+ * Errors: COREY_ENULL, COREY_EINVAL (dtype, W), COREY_ESHAPE, COREY_EUNSUPPORTED (pattern_table with fp32 storage),
+ * COREY_EWORKSPACE (pattern_table too small or misaligned).
  * ----------------------------------------------------------------------------------------------------- */
 int causal_conv1d_silu_fwd(const void* x, const float* weight, const float* bias, const void* state_in,
-                           void* u, void* state_out, void* range_parts, corey_dtype dt,
-                           int64_t B, int64_t D, int64_t L, int32_t W, void* hip_stream);
+                           void* u, void* state_out, void* range_parts, void* pattern_table, size_t pattern_table_bytes,
+                           corey_dtype dt, int64_t B, int64_t D, int64_t L, int32_t W, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------
  * selective_scan_fwd -- the recurrence h_t = A_t h_{t-1} + B_t x_t, y_t = C_t h_t + D_t x_t (Method,

@@ -17,7 +17,8 @@ LIB_PATH = os.environ.get("COREY_LIB") or os.path.join(_HERE, "libcorey.so")   #
 COREY_F32, COREY_BF16, COREY_F16 = 0, 1, 2
 STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE", 4: "COREY_ENONFINITE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
-EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_static", "corey_entropy_hist_workspace", "corey_policy_default", "corey_select_chunk",
+EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_static", "corey_entropy_hist_workspace", "corey_pattern_table_workspace",
+           "corey_entropy_hist_onesweep", "corey_entropy_hist_from_table", "corey_policy_default", "corey_select_chunk",
            "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
            "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "corey_last_error", "corey_version")
 
@@ -52,10 +53,18 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_size_t, vp]
         L.corey_entropy_hist_static.restype = ctypes.c_int
         L.corey_entropy_hist_static.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.corey_pattern_table_workspace.restype = ctypes.c_size_t
+        L.corey_pattern_table_workspace.argtypes = []
+        L.corey_entropy_hist_onesweep.restype = ctypes.c_int
+        L.corey_entropy_hist_onesweep.argtypes = [vp, ctypes.c_int, i64, i64, i64, i32, dbl, ctypes.POINTER(Policy), vp, vp, vp, vp, vp, vp,
+                                                  ctypes.c_size_t, vp]
+        L.corey_entropy_hist_from_table.restype = ctypes.c_int
+        L.corey_entropy_hist_from_table.argtypes = [ctypes.c_int, i64, i32, dbl, ctypes.POINTER(Policy), vp, vp, vp, vp, vp, vp,
+                                                    ctypes.c_size_t, vp]
         L.selective_state_update.restype = ctypes.c_int
         L.selective_state_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_int, i64, i64, i64, vp]
         L.causal_conv1d_silu_fwd.restype = ctypes.c_int
-        L.causal_conv1d_silu_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, i64, i64, i64, i32, vp]
+        L.causal_conv1d_silu_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int, i64, i64, i64, i32, vp]
         L.corey_route_device.restype = ctypes.c_int
         L.corey_route_device.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, ctypes.POINTER(Policy), dbl, vp, vp,
                                          vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -161,11 +170,14 @@ CHUNK_SLOTS = 12                   # COREY_CHUNK_SLOTS
 
 def causal_conv1d_silu_fwd(x: torch.Tensor, weight: torch.Tensor, bias: torch.Tensor | None = None,
                            state_in: torch.Tensor | None = None, u: torch.Tensor | None = None, want_state: bool = False,
-                           range_parts: torch.Tensor | None = None):
+                           range_parts: torch.Tensor | None = None, pattern_table: torch.Tensor | None = None):
     """x [B, D, L] GPU tensor, weight float32 [D, W], bias float32 [D].  Returns (u, state_out or None, range_parts):
     range_parts (uint8 GPU tensor of RANGE_PARTS_BYTES, allocated here if omitted) can be handed to
-    corey_entropy_hist / corey_route_device on this u, which then skip their range sweep."""
-    for name, t in (("x", x), ("weight", weight), ("bias", bias), ("state_in", state_in), ("u", u), ("range_parts", range_parts)):
+    corey_entropy_hist / corey_route_device on this u, which then skip their range sweep.  pattern_table: uint8 GPU
+    tensor of corey_pattern_table_workspace() bytes; the kernel then also fills the bit-pattern table of u for
+    corey_entropy_hist_from_table."""
+    for name, t in (("x", x), ("weight", weight), ("bias", bias), ("state_in", state_in), ("u", u), ("range_parts", range_parts),
+                    ("pattern_table", pattern_table)):
         _dev(t, name)
     B, D, L = x.shape
     W = weight.shape[1]
@@ -177,7 +189,8 @@ def causal_conv1d_silu_fwd(x: torch.Tensor, weight: torch.Tensor, bias: torch.Te
     if range_parts is None:
         range_parts = torch.empty(RANGE_PARTS_BYTES, dtype=torch.uint8, device=x.device)
     _check(lib().causal_conv1d_silu_fwd(_ptr(x), _ptr(weight), _ptr(bias), _ptr(state_in), _ptr(u), _ptr(state_out),
-                                        _ptr(range_parts), _dtype_code(x), B, D, L, W, _stream()))
+                                        _ptr(range_parts), _ptr(pattern_table), 0 if pattern_table is None else pattern_table.numel(),
+                                        _dtype_code(x), B, D, L, W, _stream()))
     return u, state_out, range_parts
 
 
@@ -204,6 +217,49 @@ def corey_entropy_hist(x: torch.Tensor, K: int, eps: float = 1e-8, stride: int =
                                     _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
                                     _ptr(range_parts), _ptr(workspace), workspace.numel(), _stream()))
     out["workspace"] = workspace
+    return out
+
+
+def corey_pattern_table_workspace() -> int:
+    return int(lib().corey_pattern_table_workspace())
+
+
+def _table_out(K, device, policy, out):
+    if out is None:
+        out = dict(counts=torch.empty((1, K), dtype=torch.int32, device=device), H=torch.empty(1, dtype=torch.float64, device=device),
+                   r=torch.empty(1, dtype=torch.float64, device=device), range=torch.empty((1, 2), dtype=torch.float32, device=device))
+    if policy is not None and out.get("chunks") is None:
+        out["chunks"] = torch.empty(1, dtype=torch.int32, device=device)
+    return out
+
+
+def corey_entropy_hist_onesweep(x: torch.Tensor, K: int, eps: float = 1e-8, policy: Policy | None = None, out: dict | None = None,
+                                table_ws: torch.Tensor | None = None):
+    """The statistic of a bfloat16 / float16 tensor from one pass over it (bit-pattern table).  Returns the dict of
+    corey_entropy_hist (plus `chunks` when a policy is given, as corey_route_device) and `table_ws`."""
+    _dev(x, "x"), _dev(table_ws, "table_ws")
+    if x.dim() != 3:
+        raise ValueError("x must be [B, D, L]")
+    B, D, L = x.shape
+    out = _table_out(K, x.device, policy, out)
+    if table_ws is None:
+        table_ws = torch.empty(corey_pattern_table_workspace(), dtype=torch.uint8, device=x.device)
+    _check(lib().corey_entropy_hist_onesweep(_ptr(x), _dtype_code(x), B, D, L, K, eps, ctypes.byref(policy) if policy is not None else None,
+                                             _ptr(out.get("chunks")) if policy is not None else None, _ptr(out["counts"]), _ptr(out["H"]),
+                                             _ptr(out["r"]), _ptr(out.get("range")), _ptr(table_ws), table_ws.numel(), _stream()))
+    out["table_ws"] = table_ws
+    return out
+
+
+def corey_entropy_hist_from_table(table_ws: torch.Tensor, dtype: torch.dtype, L: int, K: int, eps: float = 1e-8,
+                                  policy: Policy | None = None, out: dict | None = None):
+    """The statistic of the tensor whose producer (causal_conv1d_silu_fwd with pattern_table=table_ws) filled the table."""
+    _dev(table_ws, "table_ws")
+    out = _table_out(K, table_ws.device, policy, out)
+    code = {torch.bfloat16: COREY_BF16, torch.float16: COREY_F16, torch.float32: COREY_F32}[dtype]
+    _check(lib().corey_entropy_hist_from_table(code, L, K, eps, ctypes.byref(policy) if policy is not None else None,
+                                               _ptr(out.get("chunks")) if policy is not None else None, _ptr(out["counts"]), _ptr(out["H"]),
+                                               _ptr(out["r"]), _ptr(out.get("range")), _ptr(table_ws), table_ws.numel(), _stream()))
     return out
 
 

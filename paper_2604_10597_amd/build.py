@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcorey.so")
 # one translation unit per storage type of the scan: they compile side by side
-SOURCES = ["corey_host.cpp", "corey_entropy.hip", "corey_conv.hip", "corey_decode.hip", "corey_scan.hip", "corey_scan_bf16.hip", "corey_scan_f16.hip",
+SOURCES = ["corey_host.cpp", "corey_entropy.hip", "corey_table.hip", "corey_conv.hip", "corey_decode.hip", "corey_scan.hip", "corey_scan_bf16.hip", "corey_scan_f16.hip",
            "corey_scan_f32.hip"]
 
 # Packed-FP32 instruction selection is switched off for all device code (plain fp32 VALU ops only).

@@ -15,6 +15,7 @@
 
 #include "corey_internal.h"
 #include "corey_range.h"
+#include "corey_table.h"
 
 namespace {
 
@@ -164,14 +165,49 @@ __device__ __forceinline__ Cursor advance(Cursor c, const Stride& s)
     return c;
 }
 
-template <typename T, int W>
-__global__ __launch_bounds__(kThreads) void k_conv1d_silu(const T* __restrict__ x, const float* __restrict__ weight,
-                                                          const float* __restrict__ bias, const T* __restrict__ state_in,
-                                                          T* __restrict__ u, T* __restrict__ state_out, RangePart* __restrict__ rparts,
-                                                          int64_t rows, int64_t D, int64_t L, int vector_ok)
+// Count the stored values of one vector in the workgroup's bit-pattern table (16-bit storage).
+template <typename T>
+__device__ __forceinline__ void table_add_vector(uint32_t* s_tab, corey_table::Shared& sh, const T (&out)[St<T>::kVec], int nvalid)
 {
+    if constexpr (sizeof(T) == 2) {
+        if (nvalid == St<T>::kVec) {
+            uint32_t w[4];
+            __builtin_memcpy(w, out, 16);
+            corey_table::add_word4(s_tab, sh, w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < St<T>::kVec; ++e) {
+                if (e < nvalid) {
+                    uint16_t bits;
+                    __builtin_memcpy(&bits, &out[e], 2);
+                    corey_table::add(s_tab, sh, bits);
+                }
+            }
+        }
+    }
+}
+
+// NT lanes per workgroup.  TABLE: the workgroup also counts the bit patterns of the values it stores (corey_table.h:
+// NT = corey_table::kLanes, at most corey_table::kMaxSlabs workgroups, 16-bit storage); a turn of the unit loop adds at
+// most U * NT * 8 = 16384 values and ends at a barrier, inside the table's bound of 32768 per round.
+template <typename T, int W, int NT, bool TABLE>
+__global__ __launch_bounds__(NT) void k_conv1d_silu(const T* __restrict__ x, const float* __restrict__ weight,
+                                                    const float* __restrict__ bias, const T* __restrict__ state_in,
+                                                    T* __restrict__ u, T* __restrict__ state_out, RangePart* __restrict__ rparts,
+                                                    void* table_ws, int64_t rows, int64_t D, int64_t L, int vector_ok)
+{
+    constexpr int kThreads = NT;                              // (shadows the 256 of the other kernels in this file)
     constexpr int V = St<T>::kVec;
     constexpr int U = COREY_CONV_UNITS;                       // units in flight per lane: their loads go out together
+    static_assert(!TABLE || (NT == corey_table::kLanes && U * NT * 8 <= corey_table::kRoundAdds && sizeof(T) == 2),
+                  "a turn must stay inside the table's round");
+    __shared__ uint32_t s_tab[TABLE ? corey_table::kWords : 1];
+    __shared__ corey_table::Shared sh;
+    corey_table::Workspace tws = {};
+    if constexpr (TABLE) {
+        tws = corey_table::carve(table_ws);
+        corey_table::begin(s_tab, sh, tws);
+    }
     constexpr int64_t kSeg = (int64_t)kThreads * V;
     const int64_t nseg = (L + kSeg - 1) / kSeg;
     const int64_t nfull = vector_ok ? L / kSeg : 0;           // segments of a row that are whole and aligned
@@ -236,7 +272,9 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_silu(const T* __restrict__ 
                 word4 q;
                 __builtin_memcpy(&q, out, 16);
                 *reinterpret_cast<word4*>(u + c[j].row * L + c[j].seg * kSeg + (int64_t)threadIdx.x * V) = q;
+                if constexpr (TABLE) table_add_vector<T>(s_tab, sh, out, V);
             }
+            if constexpr (TABLE) __syncthreads();             // end of the table's round
             continue;
         }
 #pragma unroll
@@ -261,7 +299,9 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_silu(const T* __restrict__ 
                 for (int e = 0; e < V; ++e)
                     if (e < nvalid) ur[e] = out[e];
             }
+            if constexpr (TABLE) table_add_vector<T>(s_tab, sh, out, nvalid);
         }
+        if constexpr (TABLE) __syncthreads();                 // end of the table's round (the loop condition is uniform)
     }
     if (lo <= hi) {                                           // the stored extremes: one rounding each
         float pad[V], two[V];
@@ -288,18 +328,19 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_silu(const T* __restrict__ 
         }
     }
 
-    if (rparts) {
+    if (rparts || TABLE) {
         uint32_t klo = (lo <= hi) ? order_key(lo) : 0xffffffffu;
         uint32_t khi = (lo <= hi) ? order_key(hi) : 0u;
         uint32_t knan = nan ? 1u : 0u;
-        reduce_range_keys(klo, khi, knan);
-        if (threadIdx.x == 0) {
+        if constexpr (TABLE) corey_table::end(s_tab, sh, tws, klo, khi, knan);     // also reduces the keys into thread 0
+        else reduce_range_keys<NT>(klo, khi, knan);
+        if (rparts && threadIdx.x == 0) {
             RangePart rp;
             rp.lo_key = klo; rp.hi_key = khi; rp.saw_nan = knan; rp.pad = 0u;
             rparts[blockIdx.x] = rp;
         }
         // entries no workgroup owns say "nothing seen"
-        if (blockIdx.x == 0)
+        if (rparts && blockIdx.x == 0)
             for (int i = gridDim.x + threadIdx.x; i < COREY_RANGE_PARTS; i += kThreads) {
                 RangePart rp;
                 rp.lo_key = 0xffffffffu; rp.hi_key = 0u; rp.saw_nan = 0u; rp.pad = 0u;
@@ -387,13 +428,33 @@ __global__ __launch_bounds__(kThreads) void k_conv1d_silu_short(const T* __restr
 
 template <typename T>
 void launch(const void* x, const float* weight, const float* bias, const void* state_in, void* u, void* state_out, void* rparts,
-            int64_t B, int64_t D, int64_t L, int W, hipStream_t stream)
+            void* table_ws, int64_t B, int64_t D, int64_t L, int W, hipStream_t stream)
 {
     constexpr int V = St<T>::kVec;
     bool vector_ok = (L % V) == 0;
     for (const void* p : {x, (const void*)u})
         if (reinterpret_cast<uintptr_t>(p) % 16 != 0) vector_ok = false;
     const int64_t rows = B * D;
+    if constexpr (sizeof(T) == 2) {
+        if (table_ws) {                                       // one workgroup of 1024 lanes per compute unit, each with a table
+            constexpr int NT = corey_table::kLanes;
+            const int64_t seg = (int64_t)NT * V;
+            int64_t blocks = rows * ((L + seg - 1) / seg);
+            blocks = blocks < 1 ? 1 : (blocks > corey_table::kMaxSlabs ? corey_table::kMaxSlabs : blocks);
+            auto go_table = [&](auto kernel) {
+                kernel<<<dim3((unsigned)blocks), dim3(NT), 0, stream>>>(
+                    static_cast<const T*>(x), weight, bias, static_cast<const T*>(state_in), static_cast<T*>(u), static_cast<T*>(state_out),
+                    static_cast<RangePart*>(rparts), table_ws, rows, D, L, vector_ok ? 1 : 0);
+            };
+            switch (W) {
+            case 1: go_table(k_conv1d_silu<T, 1, NT, true>); break;
+            case 2: go_table(k_conv1d_silu<T, 2, NT, true>); break;
+            case 3: go_table(k_conv1d_silu<T, 3, NT, true>); break;
+            default: go_table(k_conv1d_silu<T, 4, NT, true>); break;
+            }
+            return;
+        }
+    }
     if (L <= kShortL) {
         int64_t nb = (rows + kThreads - 1) / kThreads;
         nb = nb > COREY_RANGE_PARTS ? COREY_RANGE_PARTS : nb;
@@ -416,21 +477,21 @@ void launch(const void* x, const float* weight, const float* bias, const void* s
     auto go = [&](auto kernel) {
         kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
             static_cast<const T*>(x), weight, bias, static_cast<const T*>(state_in), static_cast<T*>(u), static_cast<T*>(state_out),
-            static_cast<RangePart*>(rparts), rows, D, L, vector_ok ? 1 : 0);
+            static_cast<RangePart*>(rparts), nullptr, rows, D, L, vector_ok ? 1 : 0);
     };
     switch (W) {                                              // the tap count is a compile-time constant of the kernel
-    case 1: go(k_conv1d_silu<T, 1>); break;
-    case 2: go(k_conv1d_silu<T, 2>); break;
-    case 3: go(k_conv1d_silu<T, 3>); break;
-    default: go(k_conv1d_silu<T, 4>); break;
+    case 1: go(k_conv1d_silu<T, 1, kThreads, false>); break;
+    case 2: go(k_conv1d_silu<T, 2, kThreads, false>); break;
+    case 3: go(k_conv1d_silu<T, 3, kThreads, false>); break;
+    default: go(k_conv1d_silu<T, 4, kThreads, false>); break;
     }
 }
 
 }  // namespace
 
 extern "C" int causal_conv1d_silu_fwd(const void* x, const float* weight, const float* bias, const void* state_in, void* u,
-                                      void* state_out, void* range_parts, corey_dtype dt, int64_t B, int64_t D, int64_t L,
-                                      int32_t W, void* hip_stream)
+                                      void* state_out, void* range_parts, void* pattern_table, size_t pattern_table_bytes,
+                                      corey_dtype dt, int64_t B, int64_t D, int64_t L, int32_t W, void* hip_stream)
 {
     using corey::fail;
     if (!x || !weight || !u) return fail(COREY_ENULL, "causal_conv1d_silu_fwd: x, weight and u are required");
@@ -441,10 +502,17 @@ extern "C" int causal_conv1d_silu_fwd(const void* x, const float* weight, const 
     if (x == u) return fail(COREY_EINVAL, "causal_conv1d_silu_fwd: u may not alias x");
     if (range_parts && reinterpret_cast<uintptr_t>(range_parts) % 16 != 0)
         return fail(COREY_EINVAL, "causal_conv1d_silu_fwd: range_parts must be 16-byte aligned");
+    if (pattern_table) {
+        if (dt == COREY_F32) return fail(COREY_EUNSUPPORTED, "causal_conv1d_silu_fwd: the bit-pattern table exists for 16-bit storage only");
+        if (pattern_table_bytes < corey_table::kWorkspaceBytes || reinterpret_cast<uintptr_t>(pattern_table) % 256 != 0)
+            return fail(COREY_EWORKSPACE, "causal_conv1d_silu_fwd: pattern_table needs %zu bytes, 256-byte aligned", corey_table::kWorkspaceBytes);
+        if ((double)B * (double)D * (double)L >= 4294967296.0)
+            return fail(COREY_ESHAPE, "causal_conv1d_silu_fwd: more than 2^32-1 values would overflow the table's 32-bit totals");
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (dt == COREY_F32) launch<float>(x, weight, bias, state_in, u, state_out, range_parts, B, D, L, W, stream);
-    else if (dt == COREY_F16) launch<_Float16>(x, weight, bias, state_in, u, state_out, range_parts, B, D, L, W, stream);
-    else launch<uint16_t>(x, weight, bias, state_in, u, state_out, range_parts, B, D, L, W, stream);
+    if (dt == COREY_F32) launch<float>(x, weight, bias, state_in, u, state_out, range_parts, nullptr, B, D, L, W, stream);
+    else if (dt == COREY_F16) launch<_Float16>(x, weight, bias, state_in, u, state_out, range_parts, pattern_table, B, D, L, W, stream);
+    else launch<uint16_t>(x, weight, bias, state_in, u, state_out, range_parts, pattern_table, B, D, L, W, stream);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "causal_conv1d_silu_fwd launch");
     return COREY_OK;

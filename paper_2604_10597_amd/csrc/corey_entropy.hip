@@ -34,19 +34,16 @@ using corey_range::kThreads;
 using corey_range::key_value;
 using corey_range::order_key;
 using corey_range::RangePart;
+using corey_range::RangeSlot;
+using corey_range::RangeFold;
+using corey_range::usable_range;
+using corey_range::word4;
 using corey_range::reduce_range_keys;
 constexpr int kVecBytes = 16;
-constexpr int kParts = 16;     // partial histograms per histogram in the workspace
+using corey_range::kParts;     // partial histograms per histogram in the workspace
 constexpr int kMaxBlocks = COREY_RANGE_PARTS;  // most workgroups per sweep (four per compute unit) and partial ranges kept
 constexpr int kFlatBlocks = 512;               // workgroups of a flat sweep: two per compute unit measured 4 % (exact) to
                                                // 11 % (sampled) faster than four (fewer LDS clears, merges and range folds)
-
-struct RangeSlot {        // one per histogram, in the caller's workspace
-    uint32_t lo_key;      // order-preserving image of the minimum (0xffffffff: nothing seen)
-    uint32_t hi_key;      // order-preserving image of the maximum (0: nothing seen)
-    uint32_t saw_nan;
-    uint32_t pad;
-};
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -337,61 +334,6 @@ __device__ __forceinline__ void publish_range(float lo, float hi, bool nan, Rang
 // The tensor is then a flat array of 16-byte words; a workgroup walks it grid-stride with kUnroll loads in
 // flight per lane and nothing but straight-line code in between.
 
-// min/max that ignore a NaN operand (hardware behaviour of v_min3/v_max3 in IEEE mode), two values per
-// instruction; written as instructions so that no canonicalising v_max(x, x) is added per operand.
-__device__ __forceinline__ void minmax3(float& lo, float& hi, float a, float b)
-{
-    asm("v_min3_f32 %0, %0, %1, %2" : "+v"(lo) : "v"(a), "v"(b));
-    asm("v_max3_f32 %0, %0, %1, %2" : "+v"(hi) : "v"(a), "v"(b));
-}
-
-typedef uint32_t word4 __attribute__((ext_vector_type(4)));
-
-// Fold one 16-byte word into the running range.  `mag` tracks the largest magnitude bit pattern seen
-// (per 16-bit half for bf16), from which NaN (pattern above infinity's) is read off at the end.
-template <typename T> struct RangeFold;
-template <> struct RangeFold<uint16_t> {
-    typedef uint16_t half2 __attribute__((ext_vector_type(2)));
-    static __device__ __forceinline__ void fold(const word4& q, float& lo, float& hi, uint32_t& mag)
-    {
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            minmax3(lo, hi, __uint_as_float(w[k] << 16), __uint_as_float(w[k] & 0xffff0000u));
-            half2 m, c;
-            const uint32_t a = w[k] & 0x7fff7fffu;
-            __builtin_memcpy(&m, &mag, 4);
-            __builtin_memcpy(&c, &a, 4);
-            m = __builtin_elementwise_max(m, c);
-            __builtin_memcpy(&mag, &m, 4);
-        }
-    }
-    static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return (mag & 0xffffu) > 0x7f80u || (mag >> 16) > 0x7f80u; }
-};
-template <> struct RangeFold<_Float16> {
-    static __device__ __forceinline__ void fold(const word4& q, float& lo, float& hi, uint32_t& mag)
-    {
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            float a, b;
-            Elem<_Float16>::widen2(w[k], a, b);
-            minmax3(lo, hi, a, b);
-            mag = max(mag, max(__float_as_uint(a) & 0x7fffffffu, __float_as_uint(b) & 0x7fffffffu));
-        }
-    }
-    static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return mag > 0x7f800000u; }
-};
-template <> struct RangeFold<float> {
-    static __device__ __forceinline__ void fold(const word4& q, float& lo, float& hi, uint32_t& mag)
-    {
-        minmax3(lo, hi, __uint_as_float(q.x), __uint_as_float(q.y));
-        minmax3(lo, hi, __uint_as_float(q.z), __uint_as_float(q.w));
-        mag = max(max(mag, q.x & 0x7fffffffu), max(q.y & 0x7fffffffu, max(q.z & 0x7fffffffu, q.w & 0x7fffffffu)));
-    }
-    static __device__ __forceinline__ bool saw_nan(uint32_t mag) { return mag > 0x7f800000u; }
-};
-
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_entropy_range(const T* __restrict__ x, int64_t B, int64_t D, int64_t L,
                                                             const int32_t* __restrict__ seqlens, int64_t stride, int64_t block,
@@ -460,14 +402,6 @@ __global__ __launch_bounds__(kThreads) void k_entropy_range_flat(const word4* __
         rp.lo_key = klo; rp.hi_key = khi; rp.saw_nan = knan; rp.pad = 0u;
         rparts[blockIdx.x] = rp;
     }
-}
-
-__device__ __forceinline__ bool usable_range(const RangeSlot& s, float* lo, float* hi)
-{
-    if (s.saw_nan || s.lo_key == 0xffffffffu || s.hi_key == 0u) return false;
-    *lo = key_value(s.lo_key);
-    *hi = key_value(s.hi_key);
-    return isfinite(*lo) && isfinite(*hi);
 }
 
 constexpr int kMaxLdsBins = 8192;   // uint32 counters in LDS (32 KiB)
@@ -868,7 +802,7 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
 
 }  // namespace
 
-namespace {
+namespace corey {
 
 // The policy as the GPU rule will apply it: the host rule's checks (r = 0.5 is a placeholder that no mode rejects), and
 // no chunk the scan cannot run (the rule's result goes straight into selective_scan_fwd's chunks_dev and into the
@@ -889,7 +823,22 @@ int check_device_policy(const char* who, const corey_policy* p, int64_t L)
     return COREY_OK;
 }
 
-}  // namespace
+int launch_entropy_finalise(const uint32_t* parts, uint32_t* counts, int32_t K, double eps, const void* slot, double* H_out,
+                            double* r_out, float* range_out, const corey_policy* pol, int32_t* chunks_out, int64_t L,
+                            hipStream_t stream)
+{
+    corey_policy no_policy = {};
+    k_entropy_finalise<<<dim3(1), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, static_cast<const RangeSlot*>(slot), H_out, r_out,
+                                                               range_out, pol ? chunks_out : nullptr, nullptr, L, pol ? *pol : no_policy, 0.0,
+                                                               nullptr, nullptr);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "entropy reduction launch");
+    return COREY_OK;
+}
+
+}  // namespace corey
+
+using corey::check_device_policy;
 
 extern "C" int corey_select_chunk_device(const double* r_dev, const int32_t* seqlens, int64_t L, int32_t nh,
                                          const corey_policy* p, int32_t* chunks_out, void* hip_stream)

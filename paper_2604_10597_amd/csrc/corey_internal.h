@@ -32,5 +32,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     return (uint16_t)(w >> 16);
 }
 
+// Launch the O(K) reduction of corey_entropy_hist for ONE histogram whose kParts partial histograms of K bins sit in
+// `parts` and whose range sits in `slot` (a corey_range::RangeSlot): sums the partials into counts, H, r, optionally the
+// range and, with a policy, the chunk for sequence length L.  Defined in corey_entropy.hip.
+int launch_entropy_finalise(const uint32_t* parts, uint32_t* counts, int32_t K, double eps, const void* slot, double* H_out,
+                            double* r_out, float* range_out, const corey_policy* pol, int32_t* chunks_out, int64_t L,
+                            hipStream_t stream);
+
+// The checks corey_select_chunk_device makes on a policy before the GPU applies it (corey_entropy.hip).
+int check_device_policy(const char* who, const corey_policy* p, int64_t L);
+
 }  // namespace corey
 #endif

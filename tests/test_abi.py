@@ -87,12 +87,25 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
 
     cv = lambda **kw: lib.causal_conv1d_silu_fwd(
         kw.get("x", fake), kw.get("w", fake), none, none, kw.get("u", ctypes.c_void_p(0x2000)), none, kw.get("rp", none),
-        kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("L", 8), kw.get("W", 4), none)
+        kw.get("pt", none), kw.get("ptb", 0), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("L", 8), kw.get("W", 4), none)
+    big = lib.corey_pattern_table_workspace()
+    assert big > 256 * 131072
+    assert cv(pt=fake, ptb=big, dt=0) == 5 and cv(pt=fake, ptb=1024) == 7 and cv(pt=ctypes.c_void_p(0x1010), ptb=big) == 7
     assert cv(x=none) == 2 and cv(w=none) == 2 and cv(u=none) == 2
     assert cv(dt=9) == 1 and cv(W=0) == 1 and cv(W=5) == 1 and cv(u=fake) == 1 and cv(rp=ctypes.c_void_p(0x1004)) == 1
     assert cv(B=0) == 3 and cv(L=0) == 3
     assert lib.corey_entropy_hist_workspace(0, 16) == 0 and lib.corey_entropy_hist_workspace(3, 1) == 0
     assert lib.corey_entropy_hist_workspace(3, 256) >= 3 * 16
+
+    one = lambda **kw: lib.corey_entropy_hist_onesweep(
+        kw.get("x", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("L", 8), kw.get("K", 16), kw.get("eps", 1e-8),
+        kw.get("p", None), kw.get("chunks", none), kw.get("counts", fake), fake, fake, none, kw.get("ws", fake), kw.get("wsb", big), none)
+    assert one(x=none) == 2 and one(counts=none) == 2 and one(dt=0) == 5 and one(dt=9) == 1 and one(K=1) == 1 and one(eps=-1.0) == 1
+    assert one(B=0) == 3 and one(B=1 << 20, D=1 << 10, L=1 << 10) == 3 and one(ws=none) == 7 and one(wsb=4096) == 7
+    assert one(x=ctypes.c_void_p(0x1001)) == 1 and one(p=ctypes.byref(binding.policy_default())) == 2     # a policy needs chunks_out
+    ft = lambda **kw: lib.corey_entropy_hist_from_table(kw.get("dt", 1), kw.get("L", 8), kw.get("K", 16), 1e-8, None, none,
+                                                        kw.get("counts", fake), fake, fake, none, kw.get("ws", fake), kw.get("wsb", big), none)
+    assert ft(counts=none) == 2 and ft(dt=0) == 5 and ft(K=5000) == 1 and ft(L=0) == 3 and ft(ws=none) == 7 and ft(wsb=1) == 7
 
     su = lambda **kw: lib.selective_state_update(
         kw.get("state", fake), kw.get("x", fake), fake, fake, fake, fake, none, none, none, 1, kw.get("y", fake), kw.get("dt", 1),
