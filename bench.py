@@ -346,7 +346,7 @@ def main() -> int:
         ut = torch.empty_like(xt)
         cw, cb = torch.rand(cfg.D, 4, device="cuda") - 0.5, torch.rand(cfg.D, device="cuda") - 0.5
         win = [torch.zeros((Bd, cfg.D, 3), dtype=xt.dtype, device="cuda") for _ in range(2)]
-        cparts = torch.empty(corey.binding.RANGE_PARTS_BYTES, dtype=torch.uint8, device="cuda")
+        cparts = torch.empty(corey.binding.HANDOFF_BYTES, dtype=torch.uint8, device="cuda")
         lib, ptr = corey.binding.lib(), corey.binding._ptr
 
         def layer_token(i):

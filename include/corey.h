@@ -60,6 +60,7 @@ typedef enum {
 #define COREY_CHUNK_SLOTS 12     /* chunk-distribution counters: slot log2(chunk), chunk = 1 .. 2048 */
 #define COREY_MAX_CONV 4         /* taps of the causal convolution that produces u */
 #define COREY_RANGE_PARTS 1024   /* partial ranges a producer of u hands to corey_entropy_hist (16 bytes each) */
+#define COREY_HANDOFF_BYTES (COREY_RANGE_PARTS * 16 + 16 * COREY_MAX_BINS * 4)   /* the buffer a producer of u hands to the statistic */
 
 /* -------------------------------------------------------------------------------------------------------
  * corey_entropy_hist -- Eq. 1 and r = H / log K.
@@ -86,9 +87,11 @@ typedef enum {
  *               the sampled runs of memory are fetched, so the statistic costs 1/stride of the traffic.
  *   counts_out  DEVICE uint32[nh * K].   H_out, r_out: DEVICE double[nh].
  *   range_out   DEVICE float[nh * 2] (lo, hi per histogram) or NULL.
- *   range_parts DEVICE, COREY_RANGE_PARTS * 16 bytes as written by causal_conv1d_silu_fwd for this same tensor, or
- *               NULL.  With it the range sweep is skipped (the producer of x already saw every value): only the
- *               count sweep reads x.  Requires seqlens == NULL (COREY_EINVAL otherwise).  With stride > 1 the bins are
+ *   range_parts DEVICE, COREY_HANDOFF_BYTES as written by causal_conv1d_silu_fwd for this same tensor, or NULL.  With
+ *               it the range sweep is skipped (the producer of x already saw every value) and so is the launch that
+ *               clears the partial histograms (the producer cleared the ones inside this buffer; the call leaves them
+ *               cleared again, so the buffer serves any number of calls): only the count sweep reads x.  The buffer
+ *               is read and written.  Requires seqlens == NULL (COREY_EINVAL otherwise).  With stride > 1 the bins are
  *               then bounded by the minimum and maximum of ALL values while the counts are those of the sampled
  *               blocks (without range_parts a sampled statistic takes the range of the sampled values; the paper
  *               does not say which its sampled variant uses): the cheapest statistic the library offers, one read
@@ -102,7 +105,7 @@ typedef enum {
 int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
                        const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
                        uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
-                       const void* range_parts, void* workspace, size_t workspace_bytes, void* hip_stream);
+                       void* range_parts, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of workspace corey_entropy_hist needs for batch B and K bins (0 if the arguments are invalid). */
 size_t corey_entropy_hist_workspace(int64_t B, int32_t K);
@@ -125,7 +128,7 @@ size_t corey_entropy_hist_workspace(int64_t B, int32_t K);
 int corey_entropy_hist_static(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
                               const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
                               uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
-                              const void* range_parts, void* hip_stream);
+                              void* range_parts, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------
  * corey_select_chunk -- Eq. 2:  C = clip(2^round(log2(c_min + r (c_max - c_min))), c_min, c_max).
@@ -204,8 +207,31 @@ int corey_ema_update(double lambda, double* state, double H);
 int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
                        const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
                        const corey_policy* p, double ema_lambda, double* ema_state, uint32_t* chunk_calls,
-                       uint32_t* counts_out, double* H_out, double* r_out, float* range_out, const void* range_parts,
+                       uint32_t* counts_out, double* H_out, double* r_out, float* range_out, void* range_parts,
                        int32_t* chunks_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* -------------------------------------------------------------------------------------------------------
+ * corey_route_device_deferred / selective_scan_fwd_routed -- the routed path with one launch fewer.  The paper names
+ * "histogram construction, synchronization boundaries around runtime feature collection, and scheduler dispatch
+ * overhead" as the costs that make routing lose end to end: each dependent launch between the producer of u and the
+ * scan is such a cost.  corey_route_device_deferred runs the sweeps of corey_route_device but not its O(K) reduction;
+ * it fills *route (HOST, caller-owned, opaque) instead.  selective_scan_fwd_routed is selective_scan_fwd with the
+ * reduction and the chunk rule evaluated at the start of its own first kernel: every result corey_route_device
+ * would have written (counts, H, r, range, chunk, chunk counters) is written then, bit for bit the same, and the scan
+ * runs with the chunk so selected (per sequence when the statistic was per sequence, else one chunk for all).
+ * With range_parts from the producer the whole routed path is: producer, one count sweep, scan.
+ *   Arguments as for corey_route_device and selective_scan_fwd (which has no chunks_dev here).  ema_state must be NULL
+ *   (COREY_EUNSUPPORTED: the smoothed rule needs the reduction in a launch of its own).  *route is valid for ONE
+ *   selective_scan_fwd_routed call on the same stream, with the buffers it names still alive; `chunk` of that call is
+ *   the launch-shape hint and the fallback when r is NaN.
+ * ----------------------------------------------------------------------------------------------------- */
+typedef struct { uint64_t opaque[40]; } corey_deferred_route;
+int corey_route_device_deferred(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L,
+                                const int32_t* seqlens, int32_t K, double eps, int64_t stride, int64_t block,
+                                const corey_policy* p, uint32_t* chunk_calls,
+                                uint32_t* counts_out, double* H_out, double* r_out, float* range_out, void* range_parts,
+                                int32_t* chunks_out, void* workspace, size_t workspace_bytes,
+                                corey_deferred_route* route, void* hip_stream);
 
 /* -------------------------------------------------------------------------------------------------------
  * corey_entropy_hist_onesweep -- Eq. 1 and r = H / log K for a 16-bit tensor from ONE pass over it.
@@ -253,8 +279,8 @@ int corey_entropy_hist_from_table(corey_dtype dt, int64_t L, int32_t K, double e
  *   state_in    DEVICE [B, D, W-1] in `dt` or NULL: the W-1 inputs that precede t = 0 (oldest first).
  *   state_out   DEVICE [B, D, W-1] in `dt` or NULL: the last W-1 inputs (for continuing the sequence); may not
  *               overlap state_in.
- *   range_parts DEVICE, COREY_RANGE_PARTS * 16 bytes, or NULL: partial minima / maxima (and a NaN flag) of the
- *               values of u *as stored*, for corey_entropy_hist / corey_route_device on this u.
+ *   range_parts DEVICE, COREY_HANDOFF_BYTES, or NULL: partial minima / maxima (and a NaN flag) of the values of u *as
+ *               stored*, followed by cleared partial histograms, for corey_entropy_hist / corey_route_device on this u.
  *   pattern_table, pattern_table_bytes   DEVICE, corey_pattern_table_workspace() bytes, 256-byte aligned, or NULL / 0
  *               (16-bit storage only): the kernel also counts the bit patterns of the values of u it stores, so that
  *               corey_entropy_hist_from_table gives the exact statistic of u without reading u at all.
@@ -317,6 +343,13 @@ int selective_scan_fwd(const void* u, const void* delta, const float* A, const v
                        void* y, float* last_state, corey_dtype dt,
                        int64_t B, int64_t D, int64_t N, int64_t L, uint32_t flags,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+int selective_scan_fwd_routed(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
+                              const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
+                              const float* h0, const int32_t* seqlens, int32_t chunk, const corey_deferred_route* route,
+                              void* y, float* last_state, corey_dtype dt,
+                              int64_t B, int64_t D, int64_t N, int64_t L, uint32_t flags,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of workspace selective_scan_fwd needs (0 if the arguments are invalid): room for B and C as fp32, padded
  * along L to whole tiles and in N to a multiple of 4, in the two orders a launch may read them in (one launch can run

@@ -19,7 +19,7 @@ STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE",
           5: "COREY_EUNSUPPORTED", 6: "COREY_EHIP", 7: "COREY_EWORKSPACE"}
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_static", "corey_entropy_hist_workspace", "corey_pattern_table_workspace",
            "corey_entropy_hist_onesweep", "corey_entropy_hist_from_table", "corey_policy_default", "corey_select_chunk",
-           "corey_select_chunk_device", "corey_route_device", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
+           "corey_select_chunk_device", "corey_route_device", "corey_route_device_deferred", "selective_scan_fwd_routed", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
            "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "corey_last_error", "corey_version")
 
 
@@ -35,6 +35,11 @@ class Policy(ctypes.Structure):
                 ("h_ref_scale", ctypes.c_double), ("short_len", ctypes.c_int32), ("short_chunk", ctypes.c_int32),
                 ("long_chunk", ctypes.c_int32), ("static_chunk", ctypes.c_int32), ("safe_chunk", ctypes.c_int32),
                 ("guard_buckets", ctypes.c_int32)]
+
+
+class DeferredRoute(ctypes.Structure):
+    """corey_deferred_route: opaque, filled by corey_route_device_deferred, consumed by selective_scan_fwd_routed"""
+    _fields_ = [("opaque", ctypes.c_uint64 * 40)]
 
 
 _lib = None
@@ -68,6 +73,12 @@ def lib() -> ctypes.CDLL:
         L.corey_route_device.restype = ctypes.c_int
         L.corey_route_device.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, ctypes.POINTER(Policy), dbl, vp, vp,
                                          vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.corey_route_device_deferred.restype = ctypes.c_int
+        L.corey_route_device_deferred.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, i32, dbl, i64, i64, ctypes.POINTER(Policy), vp,
+                                                  vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(DeferredRoute), vp]
+        L.selective_scan_fwd_routed.restype = ctypes.c_int
+        L.selective_scan_fwd_routed.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, ctypes.POINTER(DeferredRoute),
+                                                vp, vp, ctypes.c_int, i64, i64, i64, i64, ctypes.c_uint32, vp, ctypes.c_size_t, vp]
         L.corey_ema_update.restype = ctypes.c_int
         L.corey_ema_update.argtypes = [dbl, ctypes.POINTER(dbl), dbl]
         L.corey_entropy_hist_workspace.restype = ctypes.c_size_t
@@ -164,7 +175,8 @@ def selective_state_update(state: torch.Tensor, x: torch.Tensor, delta: torch.Te
     return y
 
 
-RANGE_PARTS_BYTES = 1024 * 16      # COREY_RANGE_PARTS records of 16 bytes
+HANDOFF_BYTES = 1024 * 16 + 16 * 4096 * 4      # COREY_HANDOFF_BYTES: partial ranges + partial histograms
+RANGE_PARTS_BYTES = HANDOFF_BYTES
 CHUNK_SLOTS = 12                   # COREY_CHUNK_SLOTS
 
 
@@ -172,7 +184,7 @@ def causal_conv1d_silu_fwd(x: torch.Tensor, weight: torch.Tensor, bias: torch.Te
                            state_in: torch.Tensor | None = None, u: torch.Tensor | None = None, want_state: bool = False,
                            range_parts: torch.Tensor | None = None, pattern_table: torch.Tensor | None = None):
     """x [B, D, L] GPU tensor, weight float32 [D, W], bias float32 [D].  Returns (u, state_out or None, range_parts):
-    range_parts (uint8 GPU tensor of RANGE_PARTS_BYTES, allocated here if omitted) can be handed to
+    range_parts (uint8 GPU tensor of HANDOFF_BYTES, allocated here if omitted) can be handed to
     corey_entropy_hist / corey_route_device on this u, which then skip their range sweep.  pattern_table: uint8 GPU
     tensor of corey_pattern_table_workspace() bytes; the kernel then also fills the bit-pattern table of u for
     corey_entropy_hist_from_table."""
@@ -187,7 +199,9 @@ def causal_conv1d_silu_fwd(x: torch.Tensor, weight: torch.Tensor, bias: torch.Te
         u = torch.empty_like(x)
     state_out = torch.empty((B, D, W - 1), dtype=x.dtype, device=x.device) if want_state else None
     if range_parts is None:
-        range_parts = torch.empty(RANGE_PARTS_BYTES, dtype=torch.uint8, device=x.device)
+        range_parts = torch.empty(HANDOFF_BYTES, dtype=torch.uint8, device=x.device)
+    elif range_parts.numel() < HANDOFF_BYTES or range_parts.dtype != torch.uint8:
+        raise TypeError(f"range_parts must be a uint8 tensor of {HANDOFF_BYTES} bytes")
     _check(lib().causal_conv1d_silu_fwd(_ptr(x), _ptr(weight), _ptr(bias), _ptr(state_in), _ptr(u), _ptr(state_out),
                                         _ptr(range_parts), _ptr(pattern_table), 0 if pattern_table is None else pattern_table.numel(),
                                         _dtype_code(x), B, D, L, W, _stream()))
@@ -328,6 +342,39 @@ def corey_route_device(x: torch.Tensor, K: int, policy: Policy | None = None, ep
     return out
 
 
+def corey_route_device_deferred(x: torch.Tensor, K: int, policy: Policy | None = None, eps: float = 1e-8, stride: int = 1, block: int = 1,
+                                seqlens: torch.Tensor | None = None, out: dict | None = None, workspace: torch.Tensor | None = None,
+                                chunk_calls: torch.Tensor | None = None, range_parts: torch.Tensor | None = None):
+    """The sweeps of corey_route_device without its reduction: returns the same dict (its tensors are written by the
+    selective_scan_fwd_routed call that follows) with `route`, the ticket that call takes."""
+    _dev(chunk_calls, "chunk_calls"), _dev(x, "x"), _dev(seqlens, "seqlens")
+    if x.dim() != 3:
+        raise ValueError("x must be [B, D, L]")
+    B, D, L = x.shape
+    nh = B if seqlens is not None else 1
+    _want(seqlens, "seqlens", torch.int32, (B,))
+    _want(chunk_calls, "chunk_calls", torch.int32, (CHUNK_SLOTS,))
+    p = policy if policy is not None else policy_default()
+    if out is None:
+        out = dict(counts=torch.empty((nh, K), dtype=torch.int32, device=x.device),
+                   H=torch.empty(nh, dtype=torch.float64, device=x.device),
+                   r=torch.empty(nh, dtype=torch.float64, device=x.device),
+                   range=torch.empty((nh, 2), dtype=torch.float32, device=x.device),
+                   chunks=torch.empty(nh, dtype=torch.int32, device=x.device))
+    if workspace is None:
+        workspace = out.get("workspace")
+    if workspace is None:
+        workspace = torch.empty(max(corey_entropy_hist_workspace(B, K), 256), dtype=torch.uint8, device=x.device)
+    route = out.get("route") or DeferredRoute()
+    _check(lib().corey_route_device_deferred(_ptr(x), _dtype_code(x), B, D, L, _ptr(seqlens), K, eps, stride, block, ctypes.byref(p),
+                                             _ptr(chunk_calls), _ptr(out["counts"]), _ptr(out["H"]), _ptr(out["r"]), _ptr(out.get("range")),
+                                             _ptr(range_parts), _ptr(out["chunks"]), _ptr(workspace), workspace.numel(),
+                                             ctypes.byref(route), _stream()))
+    out["workspace"] = workspace
+    out["route"] = route
+    return out
+
+
 def corey_select_chunk(r: float, L: int, policy: Policy | None = None) -> int:
     p = policy if policy is not None else policy_default()
     c = ctypes.c_int32(0)
@@ -368,11 +415,12 @@ COREY_SCAN_ONE_CHUNK = 2
 
 def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True, h0=None,
                        seqlens=None, chunk: int = 512, chunks_dev=None, y=None, last_state=None, workspace=None,
-                       general_a: bool = False):
+                       general_a: bool = False, route: DeferredRoute | None = None):
     """Tensors as in include/corey.h.  Returns (y, last_state); enqueues on torch's current stream.
     `workspace`: uint8 GPU tensor of selective_scan_fwd_workspace(B, N, L) bytes (allocated here if omitted).
     `general_a`: COREY_SCAN_GENERAL_A, i.e. never take the fast path for A[d, n] = (n + 1) A[d, 0].
-    `chunks_dev` of one entry for a batch of several sequences is passed with COREY_SCAN_ONE_CHUNK."""
+    `chunks_dev` of one entry for a batch of several sequences is passed with COREY_SCAN_ONE_CHUNK.
+    `route`: the ticket of corey_route_device_deferred; the call is then selective_scan_fwd_routed (no chunks_dev)."""
     for name, t in (("u", u), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dv", Dv), ("z", z),
                     ("delta_bias", delta_bias), ("h0", h0), ("seqlens", seqlens), ("chunks_dev", chunks_dev),
                     ("y", y), ("last_state", last_state), ("workspace", workspace)):
@@ -402,6 +450,14 @@ def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, de
         last_state = torch.empty((B, D, N), dtype=torch.float32, device=u.device)
     if workspace is None:
         workspace = torch.empty(selective_scan_fwd_workspace(B, N, L), dtype=torch.uint8, device=u.device)
+    if route is not None:
+        if chunks_dev is not None:
+            raise ValueError("a route brings its own chunks")
+        _check(lib().selective_scan_fwd_routed(_ptr(u), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dv), _ptr(z),
+                                               _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(h0), _ptr(seqlens), int(chunk),
+                                               ctypes.byref(route), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L,
+                                               COREY_SCAN_GENERAL_A if general_a else 0, _ptr(workspace), workspace.numel(), _stream()))
+        return y, last_state
     _check(lib().selective_scan_fwd(_ptr(u), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dv), _ptr(z),
                                     _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(h0), _ptr(seqlens), int(chunk),
                                     _ptr(chunks_dev), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L,

@@ -22,6 +22,7 @@ namespace {
 using corey::bf16_to_f32;
 using corey_range::kThreads;
 using corey_range::order_key;
+using corey_range::Handoff;
 using corey_range::RangePart;
 using corey_range::reduce_range_keys;
 
@@ -193,9 +194,11 @@ __device__ __forceinline__ void table_add_vector(uint32_t* s_tab, corey_table::S
 template <typename T, int W, int NT, bool TABLE>
 __global__ __launch_bounds__(NT) void k_conv1d_silu(const T* __restrict__ x, const float* __restrict__ weight,
                                                     const float* __restrict__ bias, const T* __restrict__ state_in,
-                                                    T* __restrict__ u, T* __restrict__ state_out, RangePart* __restrict__ rparts,
+                                                    T* __restrict__ u, T* __restrict__ state_out, Handoff* __restrict__ handoff,
                                                     void* table_ws, int64_t rows, int64_t D, int64_t L, int vector_ok)
 {
+    RangePart* rparts = handoff ? handoff->parts : nullptr;
+    if (handoff) corey_range::clear_handoff_counts(handoff);   // the statistic's count sweep adds into them
     constexpr int kThreads = NT;                              // (shadows the 256 of the other kernels in this file)
     constexpr int V = St<T>::kVec;
     constexpr int U = COREY_CONV_UNITS;                       // units in flight per lane: their loads go out together
@@ -357,8 +360,10 @@ template <typename T, int W>
 __global__ __launch_bounds__(kThreads) void k_conv1d_silu_short(const T* __restrict__ x, const float* __restrict__ weight,
                                                                 const float* __restrict__ bias, const T* __restrict__ state_in,
                                                                 T* __restrict__ u, T* __restrict__ state_out,
-                                                                RangePart* __restrict__ rparts, int64_t rows, int64_t D, int L)
+                                                                Handoff* __restrict__ handoff, int64_t rows, int64_t D, int L)
 {
+    RangePart* rparts = handoff ? handoff->parts : nullptr;
+    if (handoff) corey_range::clear_handoff_counts(handoff);
     float lo = INFINITY, hi = -INFINITY;
     bool nan = false;
     for (int64_t r = (int64_t)blockIdx.x * kThreads + threadIdx.x; r < rows; r += (int64_t)gridDim.x * kThreads) {
@@ -444,7 +449,7 @@ void launch(const void* x, const float* weight, const float* bias, const void* s
             auto go_table = [&](auto kernel) {
                 kernel<<<dim3((unsigned)blocks), dim3(NT), 0, stream>>>(
                     static_cast<const T*>(x), weight, bias, static_cast<const T*>(state_in), static_cast<T*>(u), static_cast<T*>(state_out),
-                    static_cast<RangePart*>(rparts), table_ws, rows, D, L, vector_ok ? 1 : 0);
+                    static_cast<Handoff*>(rparts), table_ws, rows, D, L, vector_ok ? 1 : 0);
             };
             switch (W) {
             case 1: go_table(k_conv1d_silu<T, 1, NT, true>); break;
@@ -461,7 +466,7 @@ void launch(const void* x, const float* weight, const float* bias, const void* s
         auto go_short = [&](auto kernel) {
             kernel<<<dim3((unsigned)nb), dim3(kThreads), 0, stream>>>(
                 static_cast<const T*>(x), weight, bias, static_cast<const T*>(state_in), static_cast<T*>(u), static_cast<T*>(state_out),
-                static_cast<RangePart*>(rparts), rows, D, (int)L);
+                static_cast<Handoff*>(rparts), rows, D, (int)L);
         };
         switch (W) {
         case 1: go_short(k_conv1d_silu_short<T, 1>); break;
@@ -477,7 +482,7 @@ void launch(const void* x, const float* weight, const float* bias, const void* s
     auto go = [&](auto kernel) {
         kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
             static_cast<const T*>(x), weight, bias, static_cast<const T*>(state_in), static_cast<T*>(u), static_cast<T*>(state_out),
-            static_cast<RangePart*>(rparts), nullptr, rows, D, L, vector_ok ? 1 : 0);
+            static_cast<Handoff*>(rparts), nullptr, rows, D, L, vector_ok ? 1 : 0);
     };
     switch (W) {                                              // the tap count is a compile-time constant of the kernel
     case 1: go(k_conv1d_silu<T, 1, kThreads, false>); break;

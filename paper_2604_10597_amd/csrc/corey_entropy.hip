@@ -16,13 +16,18 @@
 // The common call (one histogram over the whole tensor, aligned, every value or every stride-th block of a
 // power-of-two number of 16-byte words) takes the *_flat kernels: the range sweep leaves one partial range per
 // workgroup (no atomics, so nothing has to be cleared first; it also clears the partial counts), the count sweep
-// starts by reducing those partials, and only the sampled 16-byte words are fetched at all.
+// starts by reducing those partials, and only the sampled 16-byte words are fetched at all.  When the producer of the
+// tensor hands over its partial ranges (and, beside them, partial histograms it cleared) the statistic is ONE launch,
+// the count sweep, plus the reduction; the reduction leaves those partial histograms cleared for the next call.  The
+// reduction itself (corey_finalise.h) can also be left to the first kernel of a routed scan (corey_route_device_deferred).
 // All of it is bandwidth work: no matrix instructions.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstring>
 #include <mutex>
 
+#include "corey_finalise.h"
 #include "corey_internal.h"
 #include "corey_range.h"
 
@@ -33,6 +38,7 @@ using corey::bf16_to_f32;
 using corey_range::kThreads;
 using corey_range::key_value;
 using corey_range::order_key;
+using corey_range::Handoff;
 using corey_range::RangePart;
 using corey_range::RangeSlot;
 using corey_range::RangeFold;
@@ -288,29 +294,13 @@ __device__ __forceinline__ void for_each_value(const T* x, const Geometry& g, in
 // address: that queue, not the data, set the time of the range sweep); the count sweep folds them.
 constexpr int kSubSlots = 32;
 
-// `given` (or NULL): partial ranges handed over by the producer of the tensor; the first workgroup folds them into
-// the slot of the (single) histogram, so that the count sweep's workgroups read 16 bytes instead of all partials.
-__global__ __launch_bounds__(kThreads) void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots, int nh, RangeSlot* subs,
-                                                           const RangePart* __restrict__ given, int ngiven)
+__global__ __launch_bounds__(kThreads) void k_entropy_init(uint32_t* parts, int64_t nparts, RangeSlot* slots, int nh, RangeSlot* subs)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const RangeSlot empty = {0xffffffffu, 0u, 0u, 0u};
     if (i < nparts) parts[i] = 0u;
-    if (i < nh && !(given && i == 0)) slots[i] = empty;
+    if (i < nh) slots[i] = empty;
     if (i < (int64_t)nh * kSubSlots) subs[i] = empty;
-    if (given && blockIdx.x == 0) {                             // uniform over the workgroup
-        uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
-        for (int k = threadIdx.x; k < ngiven; k += kThreads) {
-            const RangePart rp = given[k];
-            klo = min(klo, rp.lo_key);
-            khi = max(khi, rp.hi_key);
-            knan |= rp.saw_nan;
-        }
-        reduce_range_keys(klo, khi, knan);
-        if (threadIdx.x == 0) {
-            slots[0].lo_key = klo; slots[0].hi_key = khi; slots[0].saw_nan = knan; slots[0].pad = 0u;
-        }
-    }
 }
 
 // ... and the integer atomics that publish it.  The slot is read first and an atomic is issued only if it
@@ -485,7 +475,8 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
 {
     __shared__ uint32_t s_bins[kMaxLdsBins];
     __shared__ RangeSlot s_slot;
-    if (nrparts > 0) {   // the range: every workgroup reduces the partial ranges of the sweep before (a few KB from L2)
+    {   // the range: every workgroup reduces the partial ranges of the sweep before, or of the tensor's producer (a few KB
+        // from L2)
         uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
         for (int i = threadIdx.x; i < nrparts; i += kThreads) {
             const RangePart rp = rparts[i];
@@ -496,11 +487,8 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
         reduce_range_keys(klo, khi, knan);
         if (threadIdx.x == 0) {
             s_slot.lo_key = klo; s_slot.hi_key = khi; s_slot.saw_nan = knan; s_slot.pad = 0u;
-            if (blockIdx.x == 0) slots[0] = s_slot;           // for the reduction kernel
+            if (blockIdx.x == 0) slots[0] = s_slot;           // for the reduction
         }
-        __syncthreads();
-    } else {             // the clearing launch already folded the producer's partial ranges into the slot
-        if (threadIdx.x == 0) s_slot = slots[0];
         __syncthreads();
     }
     float lo, hi;
@@ -551,112 +539,10 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
     }
 }
 
-// Eq. 2 and the scheduler family around it for one histogram (see corey_select_chunk for the rule); 0 when r is NaN
-// in an entropy mode.
-__device__ __forceinline__ int32_t chunk_rule(double rv, int64_t L, const corey_policy& p)
+// The O(K) reduction and the chunk rule (corey_finalise.h), one workgroup per histogram.
+__global__ __launch_bounds__(kThreads) void k_entropy_finalise(const corey_finalise::Args a)
 {
-    if (L < 1) L = 1;
-    const bool short_seq = L <= p.short_len;
-    int64_t c;
-    if (p.mode == 3) {
-        c = p.static_chunk;
-    } else if (p.mode == 2) {
-        c = short_seq ? p.short_chunk : p.long_chunk;
-    } else if (p.mode == 1 && short_seq) {
-        c = p.short_chunk;
-    } else {
-        if (rv != rv) return 0;
-        double re = rv * p.h_ref_scale;
-        re = re < 0.0 ? 0.0 : (re > 1.0 ? 1.0 : re);
-        const double target = (double)p.c_min + re * (double)(p.c_max - p.c_min);
-        const double k = floor(log2(target) + 0.5);
-        c = (int64_t)1 << (int)k;
-        c = c < p.c_min ? p.c_min : (c > p.c_max ? p.c_max : c);
-        if (p.mode == 4) {
-            int away = (63 - __clzll((long long)c)) - (63 - __clzll((long long)p.safe_chunk));
-            away = away < 0 ? -away : away;
-            if (away < p.guard_buckets) c = p.safe_chunk;
-        }
-        int64_t cap = 1;
-        while (cap < L) cap <<= 1;
-        if (cap < p.c_min) cap = p.c_min;
-        if (c > cap) c = cap;
-    }
-    return (int32_t)c;
-}
-
-// With `chunks_out` the chunk rule is applied to r in the same kernel (routing without a further launch).
-__global__ __launch_bounds__(kThreads) void k_entropy_finalise(const uint32_t* __restrict__ parts, uint32_t* counts, int K, double eps,
-                                                               const RangeSlot* __restrict__ slots, double* H_out,
-                                                               double* r_out, float* range_out, int32_t* chunks_out,
-                                                               const int32_t* __restrict__ seqlens, int64_t L_all, corey_policy pol,
-                                                               double ema_lambda, double* ema_state, uint32_t* chunk_calls)
-{
-    const int h = blockIdx.x;
-    uint32_t* c = counts + (int64_t)h * K;
-    const uint32_t* ph = parts + (int64_t)h * kParts * K;
-    for (int k = threadIdx.x; k < K; k += kThreads) {           // each thread later re-reads only what it wrote
-        uint32_t sum = 0;
-        for (int q = 0; q < kParts; ++q) sum += ph[(size_t)q * K + k];
-        c[k] = sum;
-    }
-    float lo = 0.f, hi = 0.f;
-    const bool ok = usable_range(slots[h], &lo, &hi);
-    // two workgroup sums (the sample count, then the entropy terms): butterfly inside each wave, the waves' totals
-    // through LDS; every thread ends up with the same total, added in the same order
-    __shared__ double s_red[kThreads / 64];
-    __shared__ unsigned long long s_n[kThreads / 64];
-    const int wave = threadIdx.x >> 6;
-
-    unsigned long long n_part = 0;
-    for (int k = threadIdx.x; k < K; k += kThreads) n_part += c[k];
-    for (int off = 32; off > 0; off >>= 1) n_part += __shfl_xor(n_part, off);
-    if ((threadIdx.x & 63) == 0) s_n[wave] = n_part;
-    __syncthreads();
-    unsigned long long n_all = 0;
-    for (int w = 0; w < kThreads / 64; ++w) n_all += s_n[w];
-    const double n = (double)n_all;
-
-    double part = 0.0;
-    if (ok && n > 0.0)
-        for (int k = threadIdx.x; k < K; k += kThreads) {
-            if (c[k] == 0u) continue;                          // an empty bin adds nothing (0 log 0 = 0 when eps = 0)
-            const double p = (double)c[k] / n;
-            part += p * log(p + eps);
-        }
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-    if ((threadIdx.x & 63) == 0) s_red[wave] = part;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double H = NAN, r = NAN;
-        if (ok && n > 0.0) {
-            double acc = 0.0;
-            for (int w = 0; w < kThreads / 64; ++w) acc += s_red[w];
-            H = -acc;
-            r = H / log((double)K);
-            r = r < 0.0 ? 0.0 : (r > 1.0 ? 1.0 : r);
-        }
-        H_out[h] = H;
-        r_out[h] = r;
-        if (chunks_out) {
-            double r_rule = r;
-            if (ema_state) {                                   // the rule sees the entropy smoothed across calls
-                const double prev = ema_state[h];
-                double Hs = prev;
-                if (H == H) Hs = (prev != prev) ? H : ema_lambda * prev + (1.0 - ema_lambda) * H;
-                ema_state[h] = Hs;
-                r_rule = Hs / log((double)K);
-                r_rule = r_rule < 0.0 ? 0.0 : (r_rule > 1.0 ? 1.0 : r_rule);
-            }
-            const int32_t c = chunk_rule(r_rule, seqlens ? (int64_t)seqlens[h] : L_all, pol);
-            chunks_out[h] = c;
-            if (chunk_calls && c > 0 && 31 - __clz(c) < COREY_CHUNK_SLOTS) atomicAdd(&chunk_calls[31 - __clz(c)], 1u);
-        }
-        if (range_out) {
-            range_out[2 * h] = (slots[h].lo_key == 0xffffffffu) ? INFINITY : key_value(slots[h].lo_key);
-            range_out[2 * h + 1] = (slots[h].hi_key == 0u) ? -INFINITY : key_value(slots[h].hi_key);
-        }
-    }
+    corey_finalise::finalise(a, (int)blockIdx.x, true);
 }
 
 // One thread per histogram.
@@ -665,7 +551,7 @@ __global__ void k_select_chunk(const double* __restrict__ r, const int32_t* __re
 {
     const int h = blockIdx.x * blockDim.x + threadIdx.x;
     if (h >= nh) return;
-    chunks[h] = chunk_rule(r[h], seqlens ? (int64_t)seqlens[h] : L_all, p);
+    chunks[h] = corey_finalise::chunk_rule(r[h], seqlens ? (int64_t)seqlens[h] : L_all, p);
 }
 
 size_t slots_bytes(int64_t nh)
@@ -708,26 +594,37 @@ void launch_flat(const word4* x, int64_t nwords, WordMap<SAMPLED> map, int32_t K
                                                                                           slots, parts);
 }
 
+// What the caller wants done with the partial histograms once the sweeps are enqueued.
+struct Tail {
+    const corey_policy* pol;            // NULL: statistic only
+    int32_t* chunks_out;
+    double ema_lambda;
+    double* ema_state;
+    uint32_t* chunk_calls;
+    corey_finalise::Args* defer;        // not NULL: do not launch the reduction, describe it here instead
+};
+
 template <typename T>
 int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K, double eps, int64_t stride,
            int64_t block, uint32_t* counts, double* H_out, double* r_out, float* range_out, RangeSlot* slots, hipStream_t stream,
-           const corey_policy* pol, int32_t* chunks_out, double ema_lambda, double* ema_state, uint32_t* chunk_calls,
-           const RangePart* given_parts)
+           const Tail& tail, Handoff* handoff)
 {
     const int nh = seqlens ? (int)B : 1;
     uint32_t* parts = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(slots) + slots_bytes(B));
     RangePart* rparts = reinterpret_cast<RangePart*>(reinterpret_cast<char*>(parts) + parts_bytes(B, K));
     RangeSlot* subs = reinterpret_cast<RangeSlot*>(rparts + kMaxBlocks);
     const int64_t nparts = (int64_t)nh * kParts * K;
+    uint32_t* final_parts = parts;                              // where the reduction finds the partial histograms
+    bool rezero = false;
 
     constexpr int V = Elem<T>::kVec;
     const int64_t E = B * D * L;
     const bool flat_ok = !seqlens && reinterpret_cast<uintptr_t>(x) % kVecBytes == 0 && E % V == 0;
     const int64_t bw = block / V;                              // 16-byte words per sampling block
     const bool flat_blocks = flat_ok && block % V == 0 && corey::is_pow2(bw);    // sampled runs are whole 16-byte words
-    if (given_parts && flat_ok && (stride == 1 || flat_blocks)) {
-        // the producer of x left the partial ranges: clear the partial counts and go straight to the count sweep
-        // (over every word, or over the words of every stride-th block)
+    if (handoff && flat_ok && (stride == 1 || flat_blocks)) {
+        // the producer of x left its partial ranges and cleared partial histograms beside them: one launch, the count sweep
+        // (over every word, or over the words of every stride-th block), whose workgroups fold the partial ranges themselves
         int64_t nwords = E / V;
         int bw_log2 = 0;
         if (stride > 1) {
@@ -740,19 +637,19 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         }
         int64_t blocks = (nwords + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
         blocks = blocks < 1 ? 1 : (blocks > kFlatBlocks ? kFlatBlocks : blocks);
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs,
-                                                                                                             given_parts, COREY_RANGE_PARTS);
         if (stride == 1)
             k_entropy_count_flat<T, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
-                static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, given_parts, 0, slots, parts);
+                static_cast<const word4*>(x), nwords, WordMap<false>{0, 1}, K, handoff->parts, COREY_RANGE_PARTS, slots, handoff->counts);
         else
             k_entropy_count_flat<T, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
-                static_cast<const word4*>(x), nwords, WordMap<true>{bw_log2, stride}, K, given_parts, 0, slots, parts);
-    } else if (given_parts) {
+                static_cast<const word4*>(x), nwords, WordMap<true>{bw_log2, stride}, K, handoff->parts, COREY_RANGE_PARTS, slots,
+                handoff->counts);
+        final_parts = handoff->counts;
+        rezero = true;                                          // left cleared for the next statistic on this buffer
+    } else if (handoff) {
         // unaligned tensor: one workgroup folds the partial ranges into the slot, then the general count sweep
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs,
-                                                                                                             nullptr, 0);
-        k_entropy_fold_parts<<<dim3(1), dim3(kThreads), 0, stream>>>(given_parts, COREY_RANGE_PARTS, subs);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
+        k_entropy_fold_parts<<<dim3(1), dim3(kThreads), 0, stream>>>(handoff->parts, COREY_RANGE_PARTS, subs);
         const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
         int64_t blocks = B * D * ((L + seg - 1) / seg);
@@ -774,8 +671,7 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         launch_flat<T, true>(static_cast<const word4*>(x), (ns - 1) * bw + last_words, WordMap<true>{bw_log2, stride}, K, slots,
                              parts, rparts, stream);
     } else {
-        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs,
-                                                                                                             nullptr, 0);
+        k_entropy_init<<<dim3((unsigned)((nparts + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream>>>(parts, nparts, slots, nh, subs);
         const bool vector_ok = (reinterpret_cast<uintptr_t>(x) % kVecBytes == 0) && (L % V == 0);
         const int64_t rows = seqlens ? D : B * D;
         const int64_t seg = (int64_t)kThreads * V * kUnroll;
@@ -791,10 +687,14 @@ int launch(const void* x, int64_t B, int64_t D, int64_t L, const int32_t* seqlen
         k_entropy_count<T><<<grid, dim3(kThreads), 0, stream>>>(static_cast<const T*>(x), B, D, L, seqlens, stride, block,
                                                                vector_ok ? 1 : 0, K, subs, slots, parts);
     }
-    corey_policy no_policy = {};
-    k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, slots, H_out, r_out, range_out,
-                                                                          pol ? chunks_out : nullptr, seqlens, L, pol ? *pol : no_policy,
-                                                                          ema_lambda, ema_state, chunk_calls);
+    corey_finalise::Args fa = {};
+    fa.parts = final_parts; fa.slots = slots; fa.counts = counts; fa.H_out = H_out; fa.r_out = r_out; fa.range_out = range_out;
+    fa.chunks_out = tail.pol ? tail.chunks_out : nullptr; fa.seqlens = seqlens; fa.ema_state = tail.ema_state;
+    fa.chunk_calls = tail.chunk_calls; fa.L_all = L; fa.eps = eps; fa.ema_lambda = tail.ema_lambda;
+    if (tail.pol) fa.pol = *tail.pol;
+    fa.K = K; fa.nh = nh; fa.rezero = rezero ? 1 : 0;
+    if (tail.defer) *tail.defer = fa;                           // the scan's first kernel will do it
+    else k_entropy_finalise<<<dim3((unsigned)nh), dim3(kThreads), 0, stream>>>(fa);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "corey_entropy_hist launch");
     return COREY_OK;
@@ -827,10 +727,12 @@ int launch_entropy_finalise(const uint32_t* parts, uint32_t* counts, int32_t K, 
                             double* r_out, float* range_out, const corey_policy* pol, int32_t* chunks_out, int64_t L,
                             hipStream_t stream)
 {
-    corey_policy no_policy = {};
-    k_entropy_finalise<<<dim3(1), dim3(kThreads), 0, stream>>>(parts, counts, K, eps, static_cast<const RangeSlot*>(slot), H_out, r_out,
-                                                               range_out, pol ? chunks_out : nullptr, nullptr, L, pol ? *pol : no_policy, 0.0,
-                                                               nullptr, nullptr);
+    corey_finalise::Args fa = {};
+    fa.parts = const_cast<uint32_t*>(parts); fa.slots = static_cast<const RangeSlot*>(slot); fa.counts = counts; fa.H_out = H_out;
+    fa.r_out = r_out; fa.range_out = range_out; fa.chunks_out = pol ? chunks_out : nullptr; fa.L_all = L; fa.eps = eps;
+    if (pol) fa.pol = *pol;
+    fa.K = K; fa.nh = 1;
+    k_entropy_finalise<<<dim3(1), dim3(kThreads), 0, stream>>>(fa);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "entropy reduction launch");
     return COREY_OK;
@@ -865,9 +767,7 @@ namespace {
 
 int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens, int32_t K,
                       double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out, double* r_out, float* range_out,
-                      void* workspace, size_t workspace_bytes_given, void* hip_stream, const corey_policy* pol, int32_t* chunks_out,
-                      double ema_lambda = 0.0, double* ema_state = nullptr, uint32_t* chunk_calls = nullptr,
-                      const void* range_parts = nullptr)
+                      void* workspace, size_t workspace_bytes_given, void* hip_stream, const Tail& tail, void* range_parts)
 {
     using corey::fail;
     if (!x || !counts_out || !H_out || !r_out) return fail(COREY_ENULL, "%s: x, counts_out, H_out and r_out are required", who);
@@ -888,25 +788,23 @@ int entropy_hist_impl(const char* who, const void* x, corey_dtype dt, int64_t B,
     if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "%s: workspace must be 16-byte aligned", who);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     RangeSlot* slots = static_cast<RangeSlot*>(workspace);
+    Handoff* handoff = static_cast<Handoff*>(range_parts);
     if (dt == COREY_F32)
-        return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
-                             ema_state, chunk_calls, static_cast<const RangePart*>(range_parts));
+        return launch<float>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, tail, handoff);
     if (dt == COREY_F16)
-        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
-                             ema_state, chunk_calls, static_cast<const RangePart*>(range_parts));
-    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, pol, chunks_out, ema_lambda,
-                             ema_state, chunk_calls, static_cast<const RangePart*>(range_parts));
+        return launch<_Float16>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, tail, handoff);
+    return launch<uint16_t>(x, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out, slots, stream, tail, handoff);
 }
 
 }  // namespace
 
 extern "C" int corey_entropy_hist(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
                                   int32_t K, double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out,
-                                  double* r_out, float* range_out, const void* range_parts, void* workspace,
+                                  double* r_out, float* range_out, void* range_parts, void* workspace,
                                   size_t workspace_bytes_given, void* hip_stream)
 {
     return entropy_hist_impl("corey_entropy_hist", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
-                             workspace, workspace_bytes_given, hip_stream, nullptr, nullptr, 0.0, nullptr, nullptr, range_parts);
+                             workspace, workspace_bytes_given, hip_stream, Tail{}, range_parts);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -953,7 +851,7 @@ void* static_scratch(const char* who)
 
 extern "C" int corey_entropy_hist_static(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
                                          int32_t K, double eps, int64_t stride, int64_t block, uint32_t* counts_out, double* H_out,
-                                         double* r_out, float* range_out, const void* range_parts, void* hip_stream)
+                                         double* r_out, float* range_out, void* range_parts, void* hip_stream)
 {
     const size_t need = corey_entropy_hist_workspace(B, K);     // 0 for invalid B or K: the common checks below name those
     if (need > COREY_STATIC_SCRATCH_BYTES)
@@ -963,13 +861,13 @@ extern "C" int corey_entropy_hist_static(const void* x, corey_dtype dt, int64_t 
     void* ws = static_scratch("corey_entropy_hist_static");
     if (!ws) return COREY_EHIP;
     return entropy_hist_impl("corey_entropy_hist_static", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out,
-                             range_out, ws, COREY_STATIC_SCRATCH_BYTES, hip_stream, nullptr, nullptr, 0.0, nullptr, nullptr, range_parts);
+                             range_out, ws, COREY_STATIC_SCRATCH_BYTES, hip_stream, Tail{}, range_parts);
 }
 
 extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
                                   int32_t K, double eps, int64_t stride, int64_t block, const corey_policy* p,
                                   double ema_lambda, double* ema_state, uint32_t* chunk_calls,
-                                  uint32_t* counts_out, double* H_out, double* r_out, float* range_out, const void* range_parts,
+                                  uint32_t* counts_out, double* H_out, double* r_out, float* range_out, void* range_parts,
                                   int32_t* chunks_out, void* workspace, size_t workspace_bytes_given, void* hip_stream)
 {
     using corey::fail;
@@ -978,6 +876,31 @@ extern "C" int corey_route_device(const void* x, corey_dtype dt, int64_t B, int6
         return fail(COREY_EINVAL, "corey_route_device: ema_lambda = %g outside [0, 1)", ema_lambda);
     const int st = check_device_policy("corey_route_device", p, L);
     if (st != COREY_OK) return st;
+    Tail tail = {};
+    tail.pol = p; tail.chunks_out = chunks_out; tail.ema_lambda = ema_lambda; tail.ema_state = ema_state; tail.chunk_calls = chunk_calls;
     return entropy_hist_impl("corey_route_device", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out, range_out,
-                             workspace, workspace_bytes_given, hip_stream, p, chunks_out, ema_lambda, ema_state, chunk_calls, range_parts);
+                             workspace, workspace_bytes_given, hip_stream, tail, range_parts);
+}
+
+static_assert(sizeof(corey_finalise::Args) <= sizeof(corey_deferred_route), "the opaque ticket holds the reduction's arguments");
+
+extern "C" int corey_route_device_deferred(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, const int32_t* seqlens,
+                                           int32_t K, double eps, int64_t stride, int64_t block, const corey_policy* p,
+                                           uint32_t* chunk_calls, uint32_t* counts_out, double* H_out, double* r_out,
+                                           float* range_out, void* range_parts, int32_t* chunks_out, void* workspace,
+                                           size_t workspace_bytes_given, corey_deferred_route* route, void* hip_stream)
+{
+    using corey::fail;
+    if (!p || !chunks_out || !route) return fail(COREY_ENULL, "corey_route_device_deferred: p, chunks_out and route are required");
+    const int st = check_device_policy("corey_route_device_deferred", p, L);
+    if (st != COREY_OK) return st;
+    corey_finalise::Args fa = {};
+    Tail tail = {};
+    tail.pol = p; tail.chunks_out = chunks_out; tail.chunk_calls = chunk_calls; tail.defer = &fa;
+    const int rc = entropy_hist_impl("corey_route_device_deferred", x, dt, B, D, L, seqlens, K, eps, stride, block, counts_out, H_out, r_out,
+                                     range_out, workspace, workspace_bytes_given, hip_stream, tail, range_parts);
+    if (rc != COREY_OK) return rc;
+    memset(route, 0, sizeof(*route));
+    memcpy(route, &fa, sizeof(fa));
+    return COREY_OK;
 }

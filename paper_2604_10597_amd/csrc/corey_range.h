@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "corey.h"
+
 namespace corey_range {
 
 constexpr int kThreads = 256;      // lanes per workgroup of every kernel that uses reduce_range_keys
@@ -33,6 +35,20 @@ struct RangeSlot {        // the range of one histogram, in a caller's workspace
 };
 
 constexpr int kParts = 16;         // partial histograms per histogram in a workspace (spreads the merging atomics)
+
+// What the producer of a tensor hands to the statistic of that tensor (COREY_HANDOFF_BYTES): the partial ranges it saw
+// and, cleared by it, the partial histograms the count sweep adds into, so that the statistic needs no clearing launch.
+struct Handoff {
+    RangePart parts[COREY_RANGE_PARTS];
+    uint32_t counts[kParts * COREY_MAX_BINS];
+};
+static_assert(sizeof(Handoff) == COREY_HANDOFF_BYTES, "the header's size of the hand-over buffer");
+
+// Clear the hand-over buffer's partial histograms, spread over the workgroups of the kernel that calls it.
+__device__ __forceinline__ void clear_handoff_counts(Handoff* h)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kParts * COREY_MAX_BINS; i += gridDim.x * blockDim.x) h->counts[i] = 0u;
+}
 
 // Workgroup reduction of (lo, hi, nan flag) as order-preserving keys over NT lanes; the result is valid in thread 0.
 template <int NT = kThreads>

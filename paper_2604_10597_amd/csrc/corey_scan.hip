@@ -2,6 +2,8 @@
 // the storage type (corey_scan_impl.h, instantiated per type in corey_scan_f32/bf16/f16.hip).
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+
 #include "corey_scan_impl.h"
 
 namespace corey_scan {
@@ -36,30 +38,32 @@ extern "C" int32_t selective_scan_fwd_plan_steps(int64_t B, int64_t D, int64_t N
     return corey_scan::plan_klo(B, D, chunk, d16);
 }
 
-extern "C" int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
-                                  const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
-                                  const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
-                                  void* y, float* last_state, corey_dtype dt, int64_t B, int64_t D, int64_t N, int64_t L,
-                                  uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream)
+namespace {
+
+int scan_impl(const char* who, const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
+              const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
+              const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev, const corey_finalise::Args* route,
+              void* y, float* last_state, corey_dtype dt, int64_t B, int64_t D, int64_t N, int64_t L,
+              uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     using corey::fail;
     if (!u || !delta || !A || !Bm || !Cm || !y || !last_state)
-        return fail(COREY_ENULL, "selective_scan_fwd: u, delta, A, Bm, Cm, y and last_state are required");
-    if (dt != COREY_F32 && dt != COREY_BF16 && dt != COREY_F16) return fail(COREY_EINVAL, "selective_scan_fwd: unknown dtype %d", (int)dt);
-    if (B < 1 || D < 1 || L < 1) return fail(COREY_ESHAPE, "selective_scan_fwd: B, D, L must be >= 1");
-    if (N < 1 || N > COREY_MAX_STATE) return fail(COREY_ESHAPE, "selective_scan_fwd: N = %lld outside [1, %d]", (long long)N, COREY_MAX_STATE);
-    if (B > 65535) return fail(COREY_ESHAPE, "selective_scan_fwd: B = %lld exceeds 65535", (long long)B);
+        return fail(COREY_ENULL, "%s: u, delta, A, Bm, Cm, y and last_state are required", who);
+    if (dt != COREY_F32 && dt != COREY_BF16 && dt != COREY_F16) return fail(COREY_EINVAL, "%s: unknown dtype %d", who, (int)dt);
+    if (B < 1 || D < 1 || L < 1) return fail(COREY_ESHAPE, "%s: B, D, L must be >= 1", who);
+    if (N < 1 || N > COREY_MAX_STATE) return fail(COREY_ESHAPE, "%s: N = %lld outside [1, %d]", who, (long long)N, COREY_MAX_STATE);
+    if (B > 65535) return fail(COREY_ESHAPE, "%s: B = %lld exceeds 65535", who, (long long)B);
     if ((double)B * (double)D >= 2147483647.0 || (double)B * (double)D * (double)L >= 4.0e18 ||
         (double)B * (double)N * (double)L >= 4.0e18)
-        return fail(COREY_ESHAPE, "selective_scan_fwd: tensor sizes overflow the kernel's indexing");
+        return fail(COREY_ESHAPE, "%s: tensor sizes overflow the kernel's indexing", who);
     if (chunk < COREY_MIN_CHUNK || chunk > COREY_MAX_CHUNK || !corey::is_pow2(chunk))
-        return fail(COREY_EINVAL, "selective_scan_fwd: chunk = %d must be a power of two in [%d, %d]", chunk, COREY_MIN_CHUNK, COREY_MAX_CHUNK);
-    if (flags & ~(COREY_SCAN_GENERAL_A | COREY_SCAN_ONE_CHUNK)) return fail(COREY_EINVAL, "selective_scan_fwd: unknown flags 0x%x", flags);
+        return fail(COREY_EINVAL, "%s: chunk = %d must be a power of two in [%d, %d]", who, chunk, COREY_MIN_CHUNK, COREY_MAX_CHUNK);
+    if (flags & ~(COREY_SCAN_GENERAL_A | COREY_SCAN_ONE_CHUNK)) return fail(COREY_EINVAL, "%s: unknown flags 0x%x", who, flags);
 
     const size_t need = selective_scan_fwd_workspace(B, N, L);
     if (!workspace || workspace_bytes < need)
-        return fail(COREY_EWORKSPACE, "selective_scan_fwd: workspace of %zu bytes required", need);
-    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "selective_scan_fwd: workspace must be 16-byte aligned");
+        return fail(COREY_EWORKSPACE, "%s: workspace of %zu bytes required", who, need);
+    if (reinterpret_cast<uintptr_t>(workspace) % 16 != 0) return fail(COREY_EWORKSPACE, "%s: workspace must be 16-byte aligned", who);
 
     const size_t esz = dt == COREY_F32 ? 4 : 2;
     bool vector_ok = (L * (int64_t)esz) % 16 == 0;
@@ -79,6 +83,14 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.vector_ok = vector_ok ? 1 : 0;
     a.allow_structured = (flags & COREY_SCAN_GENERAL_A) ? 0 : 1;
     a.one_chunk = (flags & COREY_SCAN_ONE_CHUNK) ? 1 : 0;
+    a.route = corey_finalise::Args{};
+    if (route) {
+        if (!route->parts || !route->chunks_out || route->K < 2 || route->K > COREY_MAX_BINS || (route->nh != 1 && route->nh != B))
+            return fail(COREY_EINVAL, "%s: route was not filled by corey_route_device_deferred for this batch", who);
+        a.route = *route;
+        a.chunks_dev = route->chunks_out;                       // written by this call's first kernel, read by its second
+        a.one_chunk = route->nh == 1 ? 1 : 0;
+    }
     // LDS budget for the per-row arrays (carried state and A): at most 32 rows and 8 KiB each, so that the staging
     // buffers and the rows of a workgroup stay below what a compute unit gives four workgroups (chunks below 64,
     // which would put more than 32 rows into a workgroup, run with idle lanes).
@@ -89,7 +101,7 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     a.d16 = corey_scan::plan_d16(B, D, chunk, a.rows_cap);
     a.klo = corey_scan::plan_klo(B, D, chunk, a.d16);
     p.chunk = chunk;
-    p.routed = chunks_dev != nullptr;
+    p.routed = a.chunks_dev != nullptr;
     p.B = B; p.D = D; p.N = N;
     p.stream = static_cast<hipStream_t>(hip_stream);
     if (dt == COREY_F32) corey_scan::launch_scan_f32(a, p);
@@ -98,4 +110,30 @@ extern "C" int selective_scan_fwd(const void* u, const void* delta, const float*
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return corey::hip_fail(e, "selective_scan_fwd launch");
     return COREY_OK;
+}
+
+}  // namespace
+
+extern "C" int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
+                                  const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
+                                  const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
+                                  void* y, float* last_state, corey_dtype dt, int64_t B, int64_t D, int64_t N, int64_t L,
+                                  uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return scan_impl("selective_scan_fwd", u, delta, A, Bm, Cm, Dv, z, delta_bias, delta_softplus, h0, seqlens, chunk, chunks_dev, nullptr,
+                     y, last_state, dt, B, D, N, L, flags, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int selective_scan_fwd_routed(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
+                                         const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
+                                         const float* h0, const int32_t* seqlens, int32_t chunk, const corey_deferred_route* route,
+                                         void* y, float* last_state, corey_dtype dt, int64_t B, int64_t D, int64_t N, int64_t L,
+                                         uint32_t flags, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!route) return corey::fail(COREY_ENULL, "selective_scan_fwd_routed: route is required");
+    if (flags & COREY_SCAN_ONE_CHUNK) return corey::fail(COREY_EINVAL, "selective_scan_fwd_routed: COREY_SCAN_ONE_CHUNK follows from the route");
+    corey_finalise::Args fa;
+    memcpy(&fa, route, sizeof(fa));
+    return scan_impl("selective_scan_fwd_routed", u, delta, A, Bm, Cm, Dv, z, delta_bias, delta_softplus, h0, seqlens, chunk, nullptr, &fa,
+                     y, last_state, dt, B, D, N, L, flags, workspace, workspace_bytes, hip_stream);
 }

@@ -32,6 +32,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include "corey_finalise.h"
 #include "corey_internal.h"
 
 namespace corey_scan {
@@ -412,6 +413,7 @@ struct ScanArgs {
     int32_t allow_structured;   // take the power-chain path when A[d, n] = (n + 1) A[d, 0] (16-bit storage only)
     int32_t vector_ok;      // rows of the [.., L] tensors are 16-byte aligned
     int32_t one_chunk;      // chunks_dev holds a single entry that applies to every sequence
+    corey_finalise::Args route;   // route.parts != NULL: the statistic's reduction and the chunk rule run at the start of this call
 };
 
 __device__ __forceinline__ int resolve_chunk(const ScanArgs& a, int b)
@@ -435,13 +437,24 @@ __global__ __launch_bounds__(256) void k_relayout_bc(const T* __restrict__ Bm, c
                                                      float* __restrict__ ws_C, float* __restrict__ ws_B8, float* __restrict__ ws_C8,
                                                      const int32_t* __restrict__ seqlens, const int32_t* __restrict__ chunks_dev,
                                                      int one_chunk, int chunk_host, int64_t d16_host, int klo_host, int64_t Bn, int64_t D, int rows_cap,
-                                                     int Nreal, int N, int64_t L, int64_t Lpad)
+                                                     int Nreal, int N, int64_t L, int64_t Lpad, corey_finalise::Args route)
 {
     const int b = blockIdx.y;
     int chunk = chunk_host;
     int64_t d16 = d16_host;
     int klo = klo_host;
-    if (chunks_dev) {
+    if (route.parts) {
+        // the end of the entropy statistic, left to this kernel: every workgroup reduces the partial histograms of its
+        // sequence's statistic and applies the chunk rule (all arrive at the same chunk); the first one publishes counts, H,
+        // r and the chunk, which is where the scan kernel that follows reads it.  The partial histograms are read by all
+        // workgroups here, so clearing them for the next call is left to that scan kernel.
+        route.rezero = 0;
+        const bool first = blockIdx.x == 0 && (route.nh > 1 || b == 0);
+        const int c = corey_finalise::finalise(route, route.nh > 1 ? b : 0, first);
+        if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
+        d16 = plan_d16(Bn, D, chunk, rows_cap);
+        klo = plan_klo(Bn, D, chunk, d16);
+    } else if (chunks_dev) {
         const int c = chunks_dev[one_chunk ? 0 : b];
         if (c >= COREY_MIN_CHUNK && c <= COREY_MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
         d16 = plan_d16(Bn, D, chunk, rows_cap);
@@ -913,6 +926,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WA
 {
     extern __shared__ float s_mem[];
     const int chunk = resolve_chunk(a, blockIdx.y);
+    if (a.route.parts && a.route.rezero && blockIdx.x == 0 && blockIdx.y == 0) {
+        // the statistic's partial histograms live in the buffer its producer handed over and have been reduced by the kernel
+        // before this one: leave them cleared for the next count sweep, which adds into them without a clearing launch
+        const int n = a.route.nh * corey_range::kParts * a.route.K;
+        for (int i = threadIdx.x; i < n; i += kBlock) a.route.parts[i] = 0u;
+    }
     const int64_t d16 = plan_d16(gridDim.y, a.D, chunk, a.rows_cap);
     const int klo = plan_klo(gridDim.y, a.D, chunk, d16);
 #define COREY_CASE(C)                                                                       \
@@ -978,7 +997,7 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
     rb = rb < 1 ? 1 : (rb > 2048 ? 2048 : rb);
     k_relayout_bc<T><<<dim3((unsigned)rb, (unsigned)p.B), dim3(256), 0, p.stream>>>(
         static_cast<const T*>(a.Bm), static_cast<const T*>(a.Cm), a.ws_B, a.ws_C, a.ws_B8, a.ws_C8, a.seqlens, a.chunks_dev,
-        a.one_chunk, p.chunk, a.d16, a.klo, p.B, p.D, a.rows_cap, (int)p.N, a.Np, a.L, a.Lpad);
+        a.one_chunk, p.chunk, a.d16, a.klo, p.B, p.D, a.rows_cap, (int)p.N, a.Np, a.L, a.Lpad, a.route);
     int64_t gx = 0, g;
     size_t lds = 0, l;
     if (p.routed) {

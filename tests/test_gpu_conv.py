@@ -62,8 +62,10 @@ def _run(cfg, W, with_state=False, want_state=True, bias=True):
 
 def _parts_range(parts):
     """Reduce the partial ranges the producer left (host side, from their documented layout: lo_key, hi_key, saw_nan,
-    pad as uint32; keys order floats as unsigned integers)."""
-    p = parts.cpu().numpy().view(np.uint32).reshape(-1, 4)
+    pad as uint32; keys order floats as unsigned integers), and check that the partial histograms behind them are clear."""
+    raw = parts.cpu().numpy().view(np.uint32)
+    p = raw[:1024 * 4].reshape(-1, 4)                              # COREY_RANGE_PARTS records of 16 bytes ...
+    assert raw.size == 1024 * 4 + 16 * 4096 and not raw[1024 * 4:].any()     # ... then the cleared partial histograms
     def unkey(k):
         k = np.uint32(k)
         bits = (k ^ np.uint32(0x80000000)) if (k & np.uint32(0x80000000)) else ~k

@@ -56,3 +56,81 @@ def test_layer_prefill_then_one_token(dtype):
     assert_close(y.float().cpu().numpy(), y_ref[:, :, :P], rt, "y of the prompt", stored_bf16=sb)
     assert_close(y1.float().cpu().numpy(), y_ref[:, :, P], rt, "y of the generated token", stored_bf16=sb)
     assert_close(state.cpu().numpy(), s_ref, fp32_rtol(cfg.L), "state after the generated token")
+
+
+def _scan_args(d):
+    return dict(Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"], seqlens=d["seqlens"])
+
+
+@pytest.mark.parametrize("case", ["whole_tensor_batch", "per_sequence", "producer_exact", "producer_sampled"])
+def test_deferred_route_equals_the_separate_reduction(case):
+    """corey_route_device_deferred + selective_scan_fwd_routed (the statistic's reduction and the chunk rule inside the
+    scan's first kernel) against corey_route_device + selective_scan_fwd: every output bit for bit, several calls in a
+    row on the same buffers (the hand-over buffer's partial histograms must come back cleared each time)."""
+    print(f"[case] deferred route: {case}", flush=True)
+    pol = corey.policy_default()
+    calls_a = torch.zeros(12, dtype=torch.int32, device="cuda")
+    calls_b = torch.zeros(12, dtype=torch.int32, device="cuda")
+    if case in ("whole_tensor_batch", "per_sequence"):
+        lens = (1536, 40, 900) if case == "per_sequence" else None
+        import dataclasses
+        cfg = dataclasses.replace(wl.scaled(wl.CONFIGS["c3_mamba1p4b"], D=48, L=1536, B=3), seqlens=lens)
+        pol.mode = 1 if lens else 0
+        w = wl.make(cfg, a_kind="random")
+        d = upload(w)
+        u, parts, kw = d["u"], None, {}
+        stat_seqlens = d["seqlens"]
+    else:
+        cfg = wl.scaled(wl.CONFIGS["c4_mamba2p8b"], D=320, L=2048, seqlens=None)
+        w = wl.make(cfg, a_kind="random")
+        d = upload(w)
+        conv = wl.make_conv(cfg, 4)
+        x = to_dev(conv["dev"]["x"], cfg.dtype)
+        cw, cb = torch.from_numpy(conv["dev"]["weight"]).cuda(), torch.from_numpy(conv["dev"]["bias"]).cuda()
+        u, _, parts = corey.causal_conv1d_silu_fwd(x, cw, cb)
+        kw = dict(stride=8, block=512) if case == "producer_sampled" else {}
+        stat_seqlens = None
+    for rep in range(3):
+        if parts is not None and rep == 2:                         # a fresh hand-over from the producer in between
+            corey.causal_conv1d_silu_fwd(x, cw, cb, u=u, range_parts=parts)
+        a = corey.corey_route_device(u, cfg.K, pol, seqlens=stat_seqlens, range_parts=parts, chunk_calls=calls_a, **kw)
+        ya, sa = corey.selective_scan_fwd(u, d["delta"], d["A"], d["B"], d["C"], chunk=256, chunks_dev=a["chunks"], **_scan_args(d))
+        b = corey.corey_route_device_deferred(u, cfg.K, pol, seqlens=stat_seqlens, range_parts=parts, chunk_calls=calls_b, **kw)
+        yb, sb = corey.selective_scan_fwd(u, d["delta"], d["A"], d["B"], d["C"], chunk=256, route=b["route"], **_scan_args(d))
+        torch.cuda.synchronize()
+        for k in ("counts", "chunks", "range"):
+            assert torch.equal(a[k], b[k]), (case, rep, k)
+        for k in ("H", "r"):
+            assert torch.equal(a[k].view(torch.int64), b[k].view(torch.int64)), (case, rep, k)
+        assert torch.equal(ya.view(torch.int16), yb.view(torch.int16)) and torch.equal(sa, sb), (case, rep)
+        assert int(a["counts"].sum()) > 0 and torch.equal(calls_a, calls_b)
+    # and against the oracle once
+    ref = oracle.entropy_hist(u.float().cpu().numpy(), cfg.K, seqlens=w.seqlens if case == "per_sequence" else None,
+                              range_all=(case == "producer_sampled"), **kw)
+    assert np.array_equal(counts_u32(b["counts"]).reshape(ref["counts"].shape), ref["counts"])
+    nh = b["chunks"].numel()
+    for h in range(nh):
+        Lh = int(w.seqlens[h]) if case == "per_sequence" else cfg.L
+        st, c, margin = oracle.select_chunk(float(ref["r"][h]), Lh, oracle.policy(mode=pol.mode))
+        assert st == oracle.OK and (margin < 1e-9 and margin >= 0 or int(b["chunks"][h].item()) == c)
+
+
+def test_deferred_route_argument_errors():
+    x = torch.randn(2, 4, 64, device="cuda").bfloat16()
+    out = corey.corey_route_device_deferred(x, 16)
+    lib, ptr = corey.binding.lib(), corey.binding._ptr
+    ws = torch.empty(corey.selective_scan_fwd_workspace(3, 16, 64), dtype=torch.uint8, device="cuda")
+    t = torch.empty(8, device="cuda")
+    # a route taken for a whole-tensor statistic or a batch of 2 does not fit a batch of 3 with per-sequence chunks: nh is 1: fine;
+    # an empty ticket is refused
+    empty = corey.binding.DeferredRoute()
+    st = lib.selective_scan_fwd_routed(ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), None, None, None, 1, None, None, 256, empty, ptr(t), ptr(t),
+                                       1, 3, 4, 16, 64, 0, ptr(ws), ws.numel(), None)
+    assert st == 1
+    st = lib.selective_scan_fwd_routed(ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), None, None, None, 1, None, None, 256, None, ptr(t), ptr(t),
+                                       1, 3, 4, 16, 64, 0, ptr(ws), ws.numel(), None)
+    assert st == 2
+    st = lib.selective_scan_fwd_routed(ptr(t), ptr(t), ptr(t), ptr(t), ptr(t), None, None, None, 1, None, None, 256, out["route"], ptr(t),
+                                       ptr(t), 1, 3, 4, 16, 64, 2, ptr(ws), ws.numel(), None)
+    assert st == 1                                                # COREY_SCAN_ONE_CHUNK is not the caller's to set here
+    torch.cuda.synchronize()

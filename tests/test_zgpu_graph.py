@@ -32,7 +32,7 @@ def test_producer_routing_and_scan_replayed_from_a_graph():
     u = torch.empty_like(x)
     y = torch.empty_like(x)
     last = torch.empty((cfg.B, cfg.D, cfg.N), dtype=torch.float32, device="cuda")
-    parts = torch.empty(corey.binding.RANGE_PARTS_BYTES, dtype=torch.uint8, device="cuda")
+    parts = torch.empty(corey.binding.HANDOFF_BYTES, dtype=torch.uint8, device="cuda")
     ent = corey.corey_route_device(u, cfg.K, pol)      # allocates the outputs and the workspace once, outside the graph
     ws = torch.empty(corey.selective_scan_fwd_workspace(cfg.B, cfg.N, cfg.L), dtype=torch.uint8, device="cuda")
 
