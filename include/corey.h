@@ -254,7 +254,8 @@ int corey_route_device_deferred(const void* x, corey_dtype dt, int64_t B, int64_
  * corey_entropy_hist_from_table -- the same statistic from a table that causal_conv1d_silu_fwd filled while it wrote
  * the tensor (its `pattern_table` argument): no pass over the tensor at all, which is how the paper proposes to make
  * routing cheap ("fuse the entropy statistic more deeply").  Arguments as above; L is only the sequence length the
- * rule is applied for.  The table is consumed: one call per producer call.
+ * rule is applied for.  The table is left as it is: further calls (another K, another policy) give the statistic of
+ * the same tensor again.
  * ----------------------------------------------------------------------------------------------------- */
 size_t corey_pattern_table_workspace(void);
 int corey_entropy_hist_onesweep(const void* x, corey_dtype dt, int64_t B, int64_t D, int64_t L, int32_t K, double eps,

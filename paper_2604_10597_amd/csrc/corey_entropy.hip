@@ -732,6 +732,7 @@ int launch_entropy_finalise(const uint32_t* parts, uint32_t* counts, int32_t K, 
     fa.r_out = r_out; fa.range_out = range_out; fa.chunks_out = pol ? chunks_out : nullptr; fa.L_all = L; fa.eps = eps;
     if (pol) fa.pol = *pol;
     fa.K = K; fa.nh = 1;
+    fa.rezero = 1;                                              // the next statistic from the same table adds into them again
     k_entropy_finalise<<<dim3(1), dim3(kThreads), 0, stream>>>(fa);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "entropy reduction launch");

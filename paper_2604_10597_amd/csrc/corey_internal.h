@@ -34,7 +34,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 
 // Launch the O(K) reduction of corey_entropy_hist for ONE histogram whose kParts partial histograms of K bins sit in
 // `parts` and whose range sits in `slot` (a corey_range::RangeSlot): sums the partials into counts, H, r, optionally the
-// range and, with a policy, the chunk for sequence length L.  Defined in corey_entropy.hip.
+// range and, with a policy, the chunk for sequence length L; leaves the partial histograms cleared.  Defined in
+// corey_entropy.hip.
 int launch_entropy_finalise(const uint32_t* parts, uint32_t* counts, int32_t K, double eps, const void* slot, double* H_out,
                             double* r_out, float* range_out, const corey_policy* pol, int32_t* chunks_out, int64_t L,
                             hipStream_t stream);

@@ -156,12 +156,16 @@ def make(cfg: Config, a_kind: str = "mamba", with_z: bool = True, with_h0: bool 
 
 
 def make_conv(cfg: Config, W: int = 4, with_state: bool = False, seed_offset: int = 7919) -> dict:
-    """Inputs of the convolution that produces u: x [B, D, L] ~ N(0,1) rounded to cfg.dtype, weight [D, W] and bias [D]
+    """Inputs of the convolution that produces u: x [B, D, L] ~ N(0,1) (1 % of the channels scaled x20 when the
+    configuration's u has such outlier channels) rounded to cfg.dtype, weight [D, W] and bias [D]
     ~ U(-1/sqrt(W), 1/sqrt(W)) (the default initialisation of a depthwise Conv1d with W taps), optional
     state_in [B, D, W-1] ~ N(0,1) in the storage type.  Returns {"dev": storage arrays, "val": float32 values}."""
     rng = np.random.default_rng(cfg.seed + seed_offset)
     f = np.float32
     x = rng.standard_normal((cfg.B, cfg.D, cfg.L), dtype=f)
+    if cfg.u_kind == "outlier_channels":          # the layer's outlier channels are outliers of its input as well
+        ch = rng.choice(cfg.D, size=max(1, int(round(0.01 * cfg.D))), replace=False)
+        x[:, ch, :] *= f(20.0)
     k = f(1.0 / np.sqrt(W))
     weight = rng.uniform(-k, k, size=(cfg.D, W)).astype(f)
     bias = rng.uniform(-k, k, size=cfg.D).astype(f)
