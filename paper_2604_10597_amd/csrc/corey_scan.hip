@@ -96,6 +96,11 @@ int scan_impl(const char* who, const void* u, const void* delta, const float* A,
     // which would put more than 32 rows into a workgroup, run with idle lanes).
     int rows_cap = (int)(2048 / a.Np);
     a.rows_cap = rows_cap < 1 ? 1 : (rows_cap > 32 ? 32 : rows_cap);
+    // a lane addresses its row inside a group by a 32-bit byte offset from the group's first row
+    const int64_t row_bytes = L * (int64_t)esz;
+    if (row_bytes >= ((int64_t)1 << 31)) return fail(COREY_ESHAPE, "%s: a row of %lld bytes exceeds the kernels' 2 GiB", who, (long long)row_bytes);
+    const int64_t fit = (((int64_t)1 << 32) - 1) / row_bytes;
+    if (a.rows_cap > fit) a.rows_cap = (int)fit;
 
     corey_scan::LaunchPlan p;
     a.d16 = corey_scan::plan_d16(B, D, chunk, a.rows_cap);

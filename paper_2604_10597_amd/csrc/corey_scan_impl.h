@@ -382,6 +382,24 @@ __device__ __forceinline__ float from_left_lane(float v, float first)
     return r;
 }
 
+// The value of the lane to the left inside a segment of SEG = 16 or 32 lanes (segments start at multiples of SEG); the
+// first lane of every segment keeps `first`.  DPP rows are 16 lanes: a shift by one inside every row leaves the rows'
+// first lanes alone, and for 32-lane segments the odd rows' first lanes (16, 48) take the last lane of the row before
+// them first (row_bcast:15 on rows 1 and 3, limited by the bank mask to lanes 0..3 of the row, of which 1..3 are
+// overwritten by the shift that follows).
+template <int SEG>
+__device__ __forceinline__ float from_left_in_segment(float v, float first)
+{
+    static_assert(SEG == 16 || SEG == 32, "segments of one or two DPP rows");
+    float r = first;
+    if constexpr (SEG == 32)
+        asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 row_bcast:15 row_mask:0xa bank_mask:0x1\n\t"
+                     "v_mov_b32_dpp %0, %1 row_shr:1 row_mask:0xf bank_mask:0xf\n\ts_nop 0" : "+v"(r) : "v"(v));
+    else
+        asm volatile("s_nop 1\n\tv_mov_b32_dpp %0, %1 row_shr:1 row_mask:0xf bank_mask:0xf\n\ts_nop 0" : "+v"(r) : "v"(v));
+    return r;
+}
+
 // ------------------------------------------------------------------------------------------- kernel arguments
 struct ScanArgs {
     const void* u;
@@ -590,11 +608,20 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     for (int i = tid; i < N; i += kBlock) s_zero[i] = 0.f;
     __syncthreads();                                        // the first tile reads A before any other barrier (STRUCT)
 
-    const int64_t row = (int64_t)b * a.D + (active ? d : d0);
-    const T* u_row = static_cast<const T*>(a.u) + row * L;
-    const T* dl_row = static_cast<const T*>(a.delta) + row * L;
-    const T* z_row = a.z ? static_cast<const T*>(a.z) + row * L : nullptr;
-    T* y_row = static_cast<T*>(a.y) + row * L;
+    // u, delta, z and y are addressed as a base that is uniform over the workgroup (the group's first row; it lives in
+    // scalar registers and advances by a tile per iteration) plus ONE 32-bit byte offset per lane that never changes
+    // (the lane's row inside the group and its sub-block inside a tile): four 64-bit pointers per lane would not fit the
+    // register budget of the 16-step geometries.  The host limits the rows of a group so that the offset fits 32 bits.
+    const int64_t row0 = ((int64_t)b * a.D + d0) * L;
+    const T* u_grp = static_cast<const T*>(a.u) + row0;
+    const T* dl_grp = static_cast<const T*>(a.delta) + row0;
+    const T* z_grp = a.z ? static_cast<const T*>(a.z) + row0 : nullptr;
+    T* y_grp = static_cast<T*>(a.y) + row0;
+    const uint32_t lane_off = (uint32_t)(((int64_t)(active ? row_local : 0) * L + (int64_t)j * K) * (int64_t)sizeof(T));
+    auto at = [lane_off](const T* uniform_base) __attribute__((always_inline)) {
+        return reinterpret_cast<const T*>(reinterpret_cast<const char*>(uniform_base) + lane_off);
+    };
+    const bool z_on = z_grp != nullptr;
     const float* wsB = (K < 16 ? a.ws_B8 : a.ws_B) + (int64_t)b * N * a.Lpad;    // each kind of row has its own order of B / C
     const float* wsC = (K < 16 ? a.ws_C8 : a.ws_C) + (int64_t)b * N * a.Lpad;
     const float bias = (a.dbias && active) ? a.dbias[d] : 0.f;
@@ -642,20 +669,19 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
             widen<T, K>(d_nx, dl);
             widen<T, K>(u_nx, du);
         } else {
-            const Raw<T, K> u_raw = load_raw<T, K>(u_row + t0, nvalid, vec);
-            const Raw<T, K> d_raw = load_raw<T, K>(dl_row + t0, nvalid, vec);
-            if (z_row) z_raw = load_raw<T, K>(z_row + t0, nvalid, vec);
+            const Raw<T, K> u_raw = load_raw<T, K>(at(u_grp + tile), nvalid, vec);
+            const Raw<T, K> d_raw = load_raw<T, K>(at(dl_grp + tile), nvalid, vec);
+            if (z_on) z_raw = load_raw<T, K>(at(z_grp + tile), nvalid, vec);
             widen<T, K>(d_raw, dl);
             widen<T, K>(u_raw, du);
         }
         have_nx = false;
         float S = 0.f;
+#pragma unroll
+        for (int i = 0; i < K; ++i) dl[i] = dl[i] + bias;
         if (sp) {
 #pragma unroll
-            for (int i = 0; i < K; ++i) dl[i] = softplus(dl[i] + bias);
-        } else {
-#pragma unroll
-            for (int i = 0; i < K; ++i) dl[i] = dl[i] + bias;
+            for (int i = 0; i < K; ++i) dl[i] = softplus(dl[i]);
         }
         if (!full) {
 #pragma unroll
@@ -695,10 +721,9 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 }
                 if constexpr (kTileAhead) {                 // last group of this tile: fetch the next tile if it is a full one
                     if (nn0 == 0 && vec && tile + 2 * CHUNK <= len) {
-                        const int64_t t1 = t0 + CHUNK;
-                        u_nx = load_raw<T, K>(u_row + t1, K, true);
-                        d_nx = load_raw<T, K>(dl_row + t1, K, true);
-                        if (z_row) z_nx = load_raw<T, K>(z_row + t1, K, true);
+                        u_nx = load_raw<T, K>(at(u_grp + tile + CHUNK), K, true);
+                        d_nx = load_raw<T, K>(at(dl_grp + tile + CHUNK), K, true);
+                        if (z_on) z_nx = load_raw<T, K>(at(z_grp + tile + CHUNK), K, true);
                         have_nx = true;
                     }
                 }
@@ -726,7 +751,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                             const int i = E * q + e;
                             av[i] *= dl[i];                 // decay of state n from that of state n - 1
                             bv[i] = du[i] * b4[e];
-                            h = fmaf(av[i], h, bv[i]);
+                            h = i == 0 ? bv[i] : fmaf(av[i], h, bv[i]);
                         }
                     }
                     P_chain *= P_base;
@@ -740,7 +765,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                             const int i = E * q + e;
                             av[i] = fast_exp2(dl[i] * A2);
                             bv[i] = du[i] * b4[e];
-                            h = fmaf(av[i], h, bv[i]);
+                            h = i == 0 ? bv[i] : fmaf(av[i], h, bv[i]);      // the fold starts from a zero state
                         }
                     }
                     P = fast_exp2(S * A2);
@@ -766,6 +791,8 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 float hh;                                   // true state entering this lane's sub-block
                 if constexpr (LPR == 1) {
                     hh = cin;
+                } else if constexpr (SEG == 16 || SEG == 32) {
+                    hh = from_left_in_segment<SEG>(h, cin);  // a row inside one wave: its first lane enters with the carried state
                 } else {
                     hh = from_left_lane(h, first);
                     if constexpr (SEG < 64) hh = (jseg == 0) ? cin : hh;
@@ -785,16 +812,17 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
             for (int nl = 0; nl < G; ++nl) one_state(nl, n0 + nl);       // straight-line code for the whole group
         }
 
+        T* y_lane = const_cast<T*>(at(y_grp + tile));
         if (full) {
-            if (z_row) {
+            if (z_on) {
                 float zz[K];
                 widen<T, K>(z_raw, zz);
 #pragma unroll
                 for (int i = 0; i < K; ++i) yv[i] *= silu(zz[i]);
             }
-            if (active) store_items<T, K>(y_row + t0, K, true, yv);
+            if (active) store_items<T, K>(y_lane, K, true, yv);
         } else if (nstore > 0) {
-            if (nvalid > 0 && z_row) {
+            if (nvalid > 0 && z_on) {
                 float zz[K];
                 widen<T, K>(z_raw, zz);
 #pragma unroll
@@ -803,7 +831,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
 #pragma unroll
             for (int i = 0; i < K; ++i)
                 if (i >= nvalid) yv[i] = 0.f;                // padded positions are written as zero
-            store_items<T, K>(y_row + t0, nstore, vec, yv);
+            store_items<T, K>(y_lane, nstore, vec, yv);
         }
     }
 
@@ -815,7 +843,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
         for (int64_t tile = ntiles * CHUNK; tile < L; tile += CHUNK) {
             const int64_t t0 = tile + (int64_t)j * K;
             const int nstore = (t0 >= L) ? 0 : (L - t0 < K ? (int)(L - t0) : K);
-            if (nstore > 0) store_items<T, K>(y_row + t0, nstore, vec, zero);
+            if (nstore > 0) store_items<T, K>(const_cast<T*>(at(y_grp + tile)), nstore, vec, zero);
         }
     }
     __syncthreads();                                         // last writes of the carried state are visible
