@@ -475,6 +475,16 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
 {
     __shared__ uint32_t s_bins[kMaxLdsBins];
     __shared__ RangeSlot s_slot;
+    // the first words are requested before anything else, so that their trip from HBM overlaps the range fold and the
+    // clearing of the counters below (a sampled sweep is only two or three such turns long: their latency is its time)
+    const int64_t step = (int64_t)gridDim.x * kThreads * kUnroll;
+    int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll;
+    word4 q[kUnroll], qn[kUnroll];
+    bool have = base + kThreads * kUnroll <= nwords;
+    if (have) {
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) q[k] = x[map(base + k * kThreads + threadIdx.x)];
+    }
     {   // the range: every workgroup reduces the partial ranges of the sweep before, or of the tensor's producer (a few KB
         // from L2)
         uint32_t klo = 0xffffffffu, khi = 0u, knan = 0u;
@@ -521,16 +531,21 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
             }
         }
     };
-    const int64_t step = (int64_t)gridDim.x * kThreads * kUnroll;
-    int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll;
-    for (; base + kThreads * kUnroll <= nwords; base += step) {
-        word4 q[kUnroll];
+    while (have) {                                            // the next turn's words are requested before this turn's are counted
+        const int64_t next = base + step;
+        const bool have_next = next + kThreads * kUnroll <= nwords;
+        if (have_next) {
 #pragma unroll
-        for (int k = 0; k < kUnroll; ++k) q[k] = x[map(base + k * kThreads + threadIdx.x)];
+            for (int k = 0; k < kUnroll; ++k) qn[k] = x[map(next + k * kThreads + threadIdx.x)];
+        }
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) fold(q[k]);
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) q[k] = qn[k];
+        base = next;
+        have = have_next;
     }
-    for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) fold(x[map(i)]);
+    for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) fold(x[map(i)]);     // ragged end: at most one workgroup
     __syncthreads();
     for (int k = threadIdx.x; k < K; k += kThreads) {
         uint32_t c = 0;
