@@ -331,6 +331,8 @@ int causal_conv1d_silu_fwd(const void* x, const float* weight, const float* bias
  *                    other A takes the general path whatever the flag.
  *                    COREY_SCAN_ONE_CHUNK: chunks_dev holds ONE entry that applies to every sequence (the chunk
  *                    routed from a whole-tensor statistic of a batch: corey_route_device without seqlens writes one).
+ *                    COREY_SCAN_WHOLE_ROWS: never share the states of a channel between two rows of lanes (see
+ *                    selective_scan_fwd_plan_split; for tests and measurements of the other launch shape).
  *                    Unknown bits: COREY_EINVAL.
  * y and last_state may not alias any input.  Accuracy against a double-precision evaluation of the same
  * bits: about 1e-6 relative to the row's scale for fp32 storage; for bf16 storage y carries one bf16
@@ -338,6 +340,7 @@ int causal_conv1d_silu_fwd(const void* x, const float* weight, const float* bias
  * ----------------------------------------------------------------------------------------------------- */
 #define COREY_SCAN_GENERAL_A 1u
 #define COREY_SCAN_ONE_CHUNK 2u
+#define COREY_SCAN_WHOLE_ROWS 4u
 int selective_scan_fwd(const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
                        const float* Dv, const void* z, const float* delta_bias, int delta_softplus,
                        const float* h0, const int32_t* seqlens, int32_t chunk, const int32_t* chunks_dev,
@@ -363,9 +366,14 @@ size_t selective_scan_fwd_workspace(int64_t B, int64_t N, int64_t L);
  * per lane; the remaining D - d16 channels take selective_scan_fwd_plan_steps time steps per lane: 8, or 4 when the
  * launch would otherwise leave most of the GPU without a wave (short tiles, few channels).  d16 = 0 or D means one lane
  * geometry for all channels.  The shape never changes results beyond floating-point reassociation (each channel is an
- * independent recurrence; the steps of a tile are combined by an associative scan).  -1 if the arguments are invalid. */
+ * independent recurrence; the steps of a tile are combined by an associative scan).  -1 if the arguments are invalid.
+ * selective_scan_fwd_plan_split: 1 when the launch gives every channel two rows of lanes, each with half of the N states
+ * (launches of one lane geometry that would leave most SIMDs with at most one wave: small layers, short tiles; tiles of
+ * at most 1024 steps, N >= 4): the two partial sums over states of the read-out y_t = C_t h_t (Method, Preliminaries) are added
+ * once per tile.  0 otherwise, and always 0 under COREY_SCAN_WHOLE_ROWS. */
 int64_t selective_scan_fwd_plan(int64_t B, int64_t D, int64_t N, int32_t chunk);
 int32_t selective_scan_fwd_plan_steps(int64_t B, int64_t D, int64_t N, int32_t chunk);
+int32_t selective_scan_fwd_plan_split(int64_t B, int64_t D, int64_t N, int32_t chunk);
 
 /* Message for the most recent failing call on this thread ("" if none).  Static storage; do not free. */
 const char* corey_last_error(void);

@@ -20,7 +20,7 @@ STATUS = {0: "COREY_OK", 1: "COREY_EINVAL", 2: "COREY_ENULL", 3: "COREY_ESHAPE",
 EXPORTS = ("corey_entropy_hist", "corey_entropy_hist_static", "corey_entropy_hist_workspace", "corey_pattern_table_workspace",
            "corey_entropy_hist_onesweep", "corey_entropy_hist_from_table", "corey_policy_default", "corey_select_chunk",
            "corey_select_chunk_device", "corey_route_device", "corey_route_device_deferred", "selective_scan_fwd_routed", "corey_ema_update", "causal_conv1d_silu_fwd", "selective_state_update",
-           "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "corey_last_error", "corey_version")
+           "selective_scan_fwd", "selective_scan_fwd_workspace", "selective_scan_fwd_plan", "selective_scan_fwd_plan_steps", "selective_scan_fwd_plan_split", "corey_last_error", "corey_version")
 
 
 class CoreyError(RuntimeError):
@@ -96,6 +96,8 @@ def lib() -> ctypes.CDLL:
         L.selective_scan_fwd_plan.argtypes = [i64, i64, i64, i32]
         L.selective_scan_fwd_plan_steps.restype = i32
         L.selective_scan_fwd_plan_steps.argtypes = [i64, i64, i64, i32]
+        L.selective_scan_fwd_plan_split.restype = i32
+        L.selective_scan_fwd_plan_split.argtypes = [i64, i64, i64, i32]
         L.selective_scan_fwd_workspace.restype = ctypes.c_size_t
         L.selective_scan_fwd_workspace.argtypes = [i64, i64, i64]
         L.corey_last_error.restype = ctypes.c_char_p
@@ -405,21 +407,27 @@ def selective_scan_fwd_plan_steps(B: int, D: int, N: int, chunk: int) -> int:
     return int(lib().selective_scan_fwd_plan_steps(B, D, N, chunk))
 
 
+def selective_scan_fwd_plan_split(B: int, D: int, N: int, chunk: int) -> int:
+    return int(lib().selective_scan_fwd_plan_split(B, D, N, chunk))
+
+
 def selective_scan_fwd_workspace(B: int, N: int, L: int) -> int:
     return int(lib().selective_scan_fwd_workspace(B, N, L))
 
 
 COREY_SCAN_GENERAL_A = 1
 COREY_SCAN_ONE_CHUNK = 2
+COREY_SCAN_WHOLE_ROWS = 4
 
 
 def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True, h0=None,
                        seqlens=None, chunk: int = 512, chunks_dev=None, y=None, last_state=None, workspace=None,
-                       general_a: bool = False, route: DeferredRoute | None = None):
+                       general_a: bool = False, route: DeferredRoute | None = None, whole_rows: bool = False):
     """Tensors as in include/corey.h.  Returns (y, last_state); enqueues on torch's current stream.
     `workspace`: uint8 GPU tensor of selective_scan_fwd_workspace(B, N, L) bytes (allocated here if omitted).
     `general_a`: COREY_SCAN_GENERAL_A, i.e. never take the fast path for A[d, n] = (n + 1) A[d, 0].
     `chunks_dev` of one entry for a batch of several sequences is passed with COREY_SCAN_ONE_CHUNK.
+    `whole_rows`: COREY_SCAN_WHOLE_ROWS, i.e. never share a channel's states between two rows of lanes.
     `route`: the ticket of corey_route_device_deferred; the call is then selective_scan_fwd_routed (no chunks_dev)."""
     for name, t in (("u", u), ("delta", delta), ("A", A), ("Bm", Bm), ("Cm", Cm), ("Dv", Dv), ("z", z),
                     ("delta_bias", delta_bias), ("h0", h0), ("seqlens", seqlens), ("chunks_dev", chunks_dev),
@@ -450,16 +458,17 @@ def selective_scan_fwd(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, de
         last_state = torch.empty((B, D, N), dtype=torch.float32, device=u.device)
     if workspace is None:
         workspace = torch.empty(selective_scan_fwd_workspace(B, N, L), dtype=torch.uint8, device=u.device)
+    flags = (COREY_SCAN_GENERAL_A if general_a else 0) | (COREY_SCAN_WHOLE_ROWS if whole_rows else 0)
     if route is not None:
         if chunks_dev is not None:
             raise ValueError("a route brings its own chunks")
         _check(lib().selective_scan_fwd_routed(_ptr(u), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dv), _ptr(z),
                                                _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(h0), _ptr(seqlens), int(chunk),
                                                ctypes.byref(route), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L,
-                                               COREY_SCAN_GENERAL_A if general_a else 0, _ptr(workspace), workspace.numel(), _stream()))
+                                               flags, _ptr(workspace), workspace.numel(), _stream()))
         return y, last_state
     _check(lib().selective_scan_fwd(_ptr(u), _ptr(delta), _ptr(A), _ptr(Bm), _ptr(Cm), _ptr(Dv), _ptr(z),
                                     _ptr(delta_bias), 1 if delta_softplus else 0, _ptr(h0), _ptr(seqlens), int(chunk),
                                     _ptr(chunks_dev), _ptr(y), _ptr(last_state), _dtype_code(u), B, D, N, L,
-                                    (COREY_SCAN_GENERAL_A if general_a else 0) | (COREY_SCAN_ONE_CHUNK if one_chunk else 0), _ptr(workspace), workspace.numel(), _stream()))
+                                    flags | (COREY_SCAN_ONE_CHUNK if one_chunk else 0), _ptr(workspace), workspace.numel(), _stream()))
     return y, last_state

@@ -38,6 +38,13 @@ extern "C" int32_t selective_scan_fwd_plan_steps(int64_t B, int64_t D, int64_t N
     return corey_scan::plan_klo(B, D, chunk, d16);
 }
 
+extern "C" int32_t selective_scan_fwd_plan_split(int64_t B, int64_t D, int64_t N, int32_t chunk)
+{
+    const int64_t d16 = selective_scan_fwd_plan(B, D, N, chunk);
+    if (d16 < 0) return -1;
+    return corey_scan::plan_split(B, D, (int)N, chunk, d16, corey_scan::plan_klo(B, D, chunk, d16), 1);
+}
+
 namespace {
 
 int scan_impl(const char* who, const void* u, const void* delta, const float* A, const void* Bm, const void* Cm,
@@ -58,7 +65,7 @@ int scan_impl(const char* who, const void* u, const void* delta, const float* A,
         return fail(COREY_ESHAPE, "%s: tensor sizes overflow the kernel's indexing", who);
     if (chunk < COREY_MIN_CHUNK || chunk > COREY_MAX_CHUNK || !corey::is_pow2(chunk))
         return fail(COREY_EINVAL, "%s: chunk = %d must be a power of two in [%d, %d]", who, chunk, COREY_MIN_CHUNK, COREY_MAX_CHUNK);
-    if (flags & ~(COREY_SCAN_GENERAL_A | COREY_SCAN_ONE_CHUNK)) return fail(COREY_EINVAL, "%s: unknown flags 0x%x", who, flags);
+    if (flags & ~(COREY_SCAN_GENERAL_A | COREY_SCAN_ONE_CHUNK | COREY_SCAN_WHOLE_ROWS)) return fail(COREY_EINVAL, "%s: unknown flags 0x%x", who, flags);
 
     const size_t need = selective_scan_fwd_workspace(B, N, L);
     if (!workspace || workspace_bytes < need)
@@ -83,6 +90,7 @@ int scan_impl(const char* who, const void* u, const void* delta, const float* A,
     a.vector_ok = vector_ok ? 1 : 0;
     a.allow_structured = (flags & COREY_SCAN_GENERAL_A) ? 0 : 1;
     a.one_chunk = (flags & COREY_SCAN_ONE_CHUNK) ? 1 : 0;
+    a.allow_split = (flags & COREY_SCAN_WHOLE_ROWS) ? 0 : 1;
     a.route = corey_finalise::Args{};
     if (route) {
         if (!route->parts || !route->chunks_out || route->K < 2 || route->K > COREY_MAX_BINS || (route->nh != 1 && route->nh != B))
@@ -105,6 +113,7 @@ int scan_impl(const char* who, const void* u, const void* delta, const float* A,
     corey_scan::LaunchPlan p;
     a.d16 = corey_scan::plan_d16(B, D, chunk, a.rows_cap);
     a.klo = corey_scan::plan_klo(B, D, chunk, a.d16);
+    a.split = corey_scan::plan_split(B, D, (int)N, chunk, a.d16, a.klo, a.allow_split);
     p.chunk = chunk;
     p.routed = a.chunks_dev != nullptr;
     p.B = B; p.D = D; p.N = N;

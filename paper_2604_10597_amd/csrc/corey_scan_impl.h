@@ -61,6 +61,9 @@ constexpr int kWaves = kBlock / 64;
 #ifndef COREY_CPREFETCH_MAXK
 #define COREY_CPREFETCH_MAXK 8        // geometries with at most this many steps per lane fetch C before the lane scan
 #endif
+#ifndef COREY_SPLIT_WAVES
+#define COREY_SPLIT_WAVES 1536        // a launch with at most this many waves splits the states of a row between two rows
+#endif
 constexpr int kMaxGroup = 4;          // most states staged (and unrolled) per group
 constexpr int kPad = COREY_MAX_CHUNK; // the relaid-out time axis is padded to whole tiles
 constexpr float kLog2e = 1.4426950408889634f;
@@ -118,6 +121,24 @@ __host__ __device__ inline int plan_klo(int64_t B, int64_t D, int chunk, int64_t
 {
     if (d16 != 0 || chunk > 256) return 8;
     return B * D * (chunk / 8) / 64 <= kFewWaves ? 4 : 8;
+}
+
+// A launch of one kind of row that still leaves the SIMDs short of waves (small layers, short tiles) gives every channel
+// TWO rows in the same workgroup, each with half of the states: twice the waves, each with half the per-state work and
+// all of the per-token work, and one exchange of partial y per tile through LDS.  The staging group must hold at least
+// one state of each half (tiles up to 1024 steps), and only the geometries such a launch can have are built.
+constexpr int64_t kSplitWaves = COREY_SPLIT_WAVES;
+template <int K, int CHUNK> constexpr bool split_exists()
+{
+    return (K == 16 && CHUNK == 1024) || (K == 8 && CHUNK == 512) || (K == 4 && CHUNK >= 4 && CHUNK <= 256);
+}
+__host__ __device__ inline int plan_split(int64_t B, int64_t D, int N, int chunk, int64_t d16, int klo, int allow)
+{
+    if (!allow || N < 4 || (d16 > 0 && d16 < D)) return 0;    // (fewer than four states: the second row would hold padding only)
+    const int K = d16 >= D ? 16 : klo;
+    if (!((K == 16 && chunk == 1024) || (K == 8 && chunk == 512) || (K == 4 && chunk <= 256))) return 0;
+    const int lpr = chunk / K < 1 ? 1 : chunk / K;
+    return B * D * lpr / 64 <= kSplitWaves ? 1 : 0;
 }
 
 // ------------------------------------------------------------------------------------------- storage types
@@ -421,6 +442,8 @@ struct ScanArgs {
     float* ws_C8;
     int64_t d16;            // channels below d16 take 16 steps per lane, the others klo (host chunk; see plan_d16)
     int32_t klo;            // 8 or 4 (host chunk; see plan_klo)
+    int32_t split;          // the states of a channel are shared by two rows (host chunk; see plan_split)
+    int32_t allow_split;    // 0: every channel keeps one row whatever the size of the launch
     int64_t L, Lpad;
     int64_t rows_total;     // B * D (input of the items-per-lane rule)
     int32_t D, N;
@@ -555,9 +578,10 @@ __device__ __forceinline__ void stage_async(const float* __restrict__ srcB, cons
 
 // Floats of dynamic LDS one workgroup of the (K, CHUNK) geometry needs for `rows` rows of N states.
 template <int K, int CHUNK>
-__host__ __device__ constexpr int lds_floats(int rows, int N)
+__host__ __device__ constexpr int lds_floats(int rows, int N, bool split = false)
 {
-    return 4 * Geo<K, CHUNK>::STAGE + 2 * rows * N + N + 4 * kWaves + kBlock + N;    // N: padded state count
+    // N: padded state count; a split launch adds the partial y of the rows that hold the second half of the states
+    return 4 * Geo<K, CHUNK>::STAGE + 2 * rows * N + N + 4 * kWaves + kBlock + N + (split ? kBlock / 2 * K : 0);
 }
 
 // ------------------------------------------------------------------------------------------- the scan
@@ -567,11 +591,18 @@ __host__ __device__ constexpr int lds_floats(int rows, int N)
 // the benchmark's A = -(n + 1)).  Then exp(dl A[d, n]) = exp(dl A[d, 0])^(n + 1): one exponential per time step
 // instead of one per (time step, state), the decay of state n following from that of state n - 1 by one multiply
 // (likewise the sub-block product P).  The chain adds at most n roundings (about (n + 1) 2^-24 relative) to a decay.
-template <typename T, int K, int CHUNK, bool STRUCT>
+//
+// SPLIT: a channel has two rows of the workgroup (neighbours), the first with states [0, N/2), the second with
+// [N/2, N); `rows` counts channels.  Both do the per-token work; the second hands its partial y to the first through
+// LDS at the end of every tile, and the first adds the skip term, gates and stores.
+template <typename T, int K, int CHUNK, bool STRUCT, bool SPLIT>
 __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, const int rows, const int d0)
 {
     using Gm = Geo<K, CHUNK>;
     constexpr int LPR = Gm::LPR, SEG = Gm::SEG, WPR = Gm::WPR, G = Gm::G, STAGE = Gm::STAGE;
+    constexpr int NS = SPLIT ? 2 : 1;                       // rows per channel
+    constexpr int GH = G / NS;                              // states of one row per staging group
+    static_assert(!SPLIT || (G >= 2 && WPR == 1 && Gm::ROWS >= 2), "a split row needs a state of its own in every staging group");
     constexpr int E = K < 4 ? K : 4;                        // staged B / C values a lane reads per LDS instruction
     constexpr int KQ = K / E;
     typedef float BCv __attribute__((ext_vector_type(E)));
@@ -580,10 +611,14 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     const int tid = threadIdx.x;
     const int row_local = tid / LPR;
     const int j = tid % LPR;                                // sub-block of this lane inside the tile
-    const int d = d0 + row_local;
-    const bool active = row_local < rows && d < a.D;
-    const int rl = active ? row_local : 0;                  // safe LDS row for idle lanes
+    const int ch_local = SPLIT ? row_local >> 1 : row_local; // channel of this lane inside the group
+    const int half = SPLIT ? row_local & 1 : 0;             // which half of the states its row holds
+    const int d = d0 + ch_local;
+    const bool active = ch_local < rows && d < a.D;
+    const int rl = active ? ch_local : 0;                   // safe LDS row for idle lanes
     const int N = a.Np;                                     // padded state count: whole staging groups, no tail group
+    const int NH = N / NS;                                  // states per row (N is a multiple of 4: whole half-groups)
+    const int n_first = half * NH;                          // first state of this lane's row
     const int Nreal = a.N;
     const int64_t L = a.L;
     int64_t len = L;
@@ -598,6 +633,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     float* s_zero = s_A2 + rows * N;                        // [N] zeros: the "carried state" of lanes that are not first in their row
     float* s_xchg = s_zero + N;                             // [2][kWaves][2] wave totals when a row spans several waves
     float* s_sink = s_xchg + 4 * kWaves;                    // [kBlock + N] where lanes that are not last in their row "store" the state
+    float* s_ypart = s_sink + kBlock + N;                   // SPLIT: [K][kBlock / 2] partial y of the second rows
     for (int i = tid; i < rows * N; i += kBlock) {
         const int r = i / N, n = i - r * N;
         const int dd = d0 + r;
@@ -617,7 +653,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     const T* dl_grp = static_cast<const T*>(a.delta) + row0;
     const T* z_grp = a.z ? static_cast<const T*>(a.z) + row0 : nullptr;
     T* y_grp = static_cast<T*>(a.y) + row0;
-    const uint32_t lane_off = (uint32_t)(((int64_t)(active ? row_local : 0) * L + (int64_t)j * K) * (int64_t)sizeof(T));
+    const uint32_t lane_off = (uint32_t)(((int64_t)rl * L + (int64_t)j * K) * (int64_t)sizeof(T));
     auto at = [lane_off](const T* uniform_base) __attribute__((always_inline)) {
         return reinterpret_cast<const T*>(reinterpret_cast<const char*>(uniform_base) + lane_off);
     };
@@ -625,22 +661,31 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     const float* wsB = (K < 16 ? a.ws_B8 : a.ws_B) + (int64_t)b * N * a.Lpad;    // each kind of row has its own order of B / C
     const float* wsC = (K < 16 ? a.ws_C8 : a.ws_C) + (int64_t)b * N * a.Lpad;
     const float bias = (a.dbias && active) ? a.dbias[d] : 0.f;
-    const float Dd = (a.Dv && active) ? a.Dv[d] : 0.f;
+    const float Dd = (a.Dv && active && half == 0) ? a.Dv[d] : 0.f;      // the skip term enters once per channel
     const bool vec = a.vector_ok != 0;
     const bool sp = a.softplus != 0;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // uniform: addresses built from it stay in scalar registers
     const int jseg = lane & (SEG - 1);
     const int wpos = wave & (WPR - 1);                      // this wave's position inside its row
-    const float* A2_row = s_A2 + rl * N;
-    const float* carry_rd = (active && j == 0) ? s_carry + rl * N : s_zero;
+    // per-state arrays are indexed with the state's number inside the row: the row's first state is folded into the bases
+    const float* A2_row = s_A2 + rl * N + n_first;
+    const float* carry_rd = ((active && j == 0) ? s_carry + rl * N : s_zero) + n_first;
     // every lane stores its end-of-sub-block state each step (no branch in the inner loop): the row's last lane into
     // the carried state, all others into a scratch slot of their own
-    float* carry_wr = (active && j == LPR - 1) ? s_carry + rl * N : s_sink + tid;
+    float* carry_wr = (active && j == LPR - 1) ? s_carry + rl * N + n_first : s_sink + tid;
+    // staging: one block of GH states per row kind and operand, [half][GH][CHUNK]
+    auto stage_group = [&](const int64_t tau_s, const int n_s, float* dst) __attribute__((always_inline)) {
+        constexpr bool kScalarBase = CHUNK >= 1024;
+#pragma unroll
+        for (int hs = 0; hs < NS; ++hs) {
+            const int64_t off = (tau_s * N + hs * NH + n_s) * CHUNK;
+            stage_async<GH * CHUNK, kScalarBase>(wsB + off, wsC + off, dst + hs * GH * CHUNK, dst + STAGE + hs * GH * CHUNK, wave, lane);
+        }
+    };
 
     int buf = 0;                                            // staging buffer holding the group about to be used
-    constexpr bool kScalarBase = CHUNK >= 1024;
-    if (len > 0) stage_async<STAGE, kScalarBase>(wsB, wsC, s_stage, s_stage + STAGE, wave, lane);
+    if (len > 0) stage_group(0, 0, s_stage);
 
     // Geometries with at most 8 steps per lane have the registers to fetch the next tile's u / delta / z while the last
     // group of states of the current tile is computed, which takes the HBM latency out of every tile's start.
@@ -695,30 +740,28 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
         }
         float av_chain[K], P_chain = 1.f, P_base = 1.f;      // STRUCT: decay of the current state, built up state by state
         if constexpr (STRUCT) {
-            const float A20 = A2_row[0];
+            const float A20 = s_A2[rl * N];
 #pragma unroll
             for (int i = 0; i < K; ++i) {
+                // a row that starts at state n_first starts its chain at the decay of state 0 to the power n_first
+                av_chain[i] = SPLIT ? fast_exp2(dl[i] * A20 * (float)n_first) : 1.f;
                 dl[i] = fast_exp2(dl[i] * A20);             // from here on dl holds the decay of state 0
-                av_chain[i] = 1.f;
             }
             P_base = fast_exp2(S * A20);
+            if constexpr (SPLIT) P_chain = fast_exp2(S * A20 * (float)n_first);
         }
 
-        for (int n0 = 0; n0 < N; n0 += G) {
+        for (int n0 = 0; n0 < NH; n0 += GH) {                 // n0: number inside the row of the group's first state
             const float* s_B = s_stage + buf * 2 * STAGE;
             const float* s_C = s_B + STAGE;
             // this group's copy (started one group earlier) has landed; every wave is past the previous group
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             {   // start the copy of the next group: same tile, or the first group of the next tile
-                int nn0 = n0 + G;
+                int nn0 = n0 + GH;
                 int64_t ntau = tau;
-                if (nn0 >= N) { nn0 = 0; ntau = tau + 1; }
-                if (ntau < ntiles) {
-                    const int64_t off = (ntau * N + nn0) * CHUNK;
-                    float* d_B = s_stage + (buf ^ 1) * 2 * STAGE;
-                    stage_async<STAGE, kScalarBase>(wsB + off, wsC + off, d_B, d_B + STAGE, wave, lane);
-                }
+                if (nn0 >= NH) { nn0 = 0; ntau = tau + 1; }
+                if (ntau < ntiles) stage_group(ntau, nn0, s_stage + (buf ^ 1) * 2 * STAGE);
                 if constexpr (kTileAhead) {                 // last group of this tile: fetch the next tile if it is a full one
                     if (nn0 == 0 && vec && tile + 2 * CHUNK <= len) {
                         u_nx = load_raw<T, K>(at(u_grp + tile + CHUNK), K, true);
@@ -729,8 +772,8 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 }
             }
             buf ^= 1;
-            const BCv* bq0 = reinterpret_cast<const BCv*>(s_B) + j;
-            const BCv* cq0 = reinterpret_cast<const BCv*>(s_C) + j;
+            const BCv* bq0 = reinterpret_cast<const BCv*>(s_B + half * GH * CHUNK) + j;
+            const BCv* cq0 = reinterpret_cast<const BCv*>(s_C + half * GH * CHUNK) + j;
             constexpr bool kEarlyC = K <= COREY_CPREFETCH_MAXK;   // C is requested before the lane scan, which covers the LDS latency
             auto one_state = [&](const int nl, const int n) __attribute__((always_inline)) {
                 const float cin = carry_rd[n];              // carried state for the first lane of the row, 0 elsewhere
@@ -809,19 +852,35 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
                 }
             };
 #pragma unroll
-            for (int nl = 0; nl < G; ++nl) one_state(nl, n0 + nl);       // straight-line code for the whole group
+            for (int nl = 0; nl < GH; ++nl) one_state(nl, n0 + nl);      // straight-line code for the whole group
         }
+
+        if constexpr (SPLIT) {                              // the second row of a channel hands over its part of the sum over states
+            float* yp = s_ypart + ch_local * LPR + j;
+            if (half == 1 && active) {
+#pragma unroll
+                for (int i = 0; i < K; ++i) yp[i * (kBlock / 2)] = yv[i];
+            }
+            __syncthreads();                                // (the next tile's barriers separate these reads from its writes)
+            if (half == 0 && active) {
+#pragma unroll
+                for (int i = 0; i < K; ++i) yv[i] += yp[i * (kBlock / 2)];
+            }
+        }
+        const bool writer = active && half == 0;            // the row that gates and stores y
 
         T* y_lane = const_cast<T*>(at(y_grp + tile));
         if (full) {
-            if (z_on) {
-                float zz[K];
-                widen<T, K>(z_raw, zz);
+            if (!SPLIT || writer) {
+                if (z_on) {
+                    float zz[K];
+                    widen<T, K>(z_raw, zz);
 #pragma unroll
-                for (int i = 0; i < K; ++i) yv[i] *= silu(zz[i]);
+                    for (int i = 0; i < K; ++i) yv[i] *= silu(zz[i]);
+                }
+                if (active) store_items<T, K>(y_lane, K, true, yv);
             }
-            if (active) store_items<T, K>(y_lane, K, true, yv);
-        } else if (nstore > 0) {
+        } else if (nstore > 0 && (!SPLIT || writer)) {
             if (nvalid > 0 && z_on) {
                 float zz[K];
                 widen<T, K>(z_raw, zz);
@@ -836,7 +895,7 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
     }
 
     // tiles wholly beyond the sequence: y is written as zero
-    if (active) {
+    if (active && half == 0) {
         float zero[K];
 #pragma unroll
         for (int i = 0; i < K; ++i) zero[i] = 0.f;
@@ -859,11 +918,12 @@ __device__ __forceinline__ void scan_group(const ScanArgs& a, float* s_mem, cons
 // run-time chunk gives every workgroup exactly one group; a launch that reads the chunk from device memory sizes
 // its grid from the host's hint and is correct for any chunk (more groups than workgroups: some take several in
 // turn; fewer: the surplus leaves at once).
-template <typename T, int K, int CHUNK>
+template <typename T, int K, int CHUNK, bool SPLIT = false>
 __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem, const int64_t d_first, const int64_t d_end,
                                           const int64_t wg, const int64_t nwg)
 {
-    const int rows_full = Geo<K, CHUNK>::ROWS < a.rows_cap ? Geo<K, CHUNK>::ROWS : a.rows_cap;
+    constexpr int kChannels = Geo<K, CHUNK>::ROWS / (SPLIT ? 2 : 1);                  // channels of a full group
+    const int rows_full = kChannels < a.rows_cap ? kChannels : a.rows_cap;
     for (int64_t d0 = d_first + wg * rows_full; d0 < d_end; d0 += nwg * rows_full) {   // uniform over the workgroup
         const int rows = d_end - d0 < rows_full ? (int)(d_end - d0) : rows_full;     // the range's last group may be short
         bool structured = false;
@@ -878,8 +938,8 @@ __device__ __forceinline__ void scan_rows(const ScanArgs& a, float* s_mem, const
                 structured = __syncthreads_and(ok) != 0;
             }
         }
-        if (structured) scan_group<T, K, CHUNK, true>(a, s_mem, rows, (int)d0);
-        else scan_group<T, K, CHUNK, false>(a, s_mem, rows, (int)d0);
+        if (structured) scan_group<T, K, CHUNK, true, SPLIT>(a, s_mem, rows, (int)d0);
+        else scan_group<T, K, CHUNK, false, SPLIT>(a, s_mem, rows, (int)d0);
         __syncthreads();                                     // the LDS arrays are set up afresh for the next group
     }
 }
@@ -893,6 +953,12 @@ template <typename T, int K, int CHUNK>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_target<K>()))) void k_scan(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
+    if constexpr (split_exists<K, CHUNK>()) {
+        if (a.split) {
+            scan_rows<T, K, CHUNK, true>(a, s_mem, 0, a.D, blockIdx.x, gridDim.x);
+            return;
+        }
+    }
     scan_rows<T, K, CHUNK>(a, s_mem, 0, a.D, blockIdx.x, gridDim.x);
 }
 
@@ -904,16 +970,26 @@ template <int K, int CHUNK> constexpr bool geometry_exists()
     return CHUNK >= K && (K == 16 || (K == 8 && CHUNK <= 512) || (K == 4 && CHUNK <= 256));
 }
 
-template <int CHUNK> __host__ __device__ inline int rows_of(int K, int rows_cap)
+template <int CHUNK> __host__ __device__ inline int rows_of(int K, int rows_cap, int split = 0)
 {
     const int lpr = CHUNK / K < 1 ? 1 : CHUNK / K;
-    const int rows = kBlock / lpr;
+    const int rows = kBlock / lpr / (split ? 2 : 1);        // channels of a workgroup
     return rows < rows_cap ? rows : rows_cap;
 }
 
 template <typename T, int CHUNK>
-__device__ __forceinline__ void scan_split(const ScanArgs& a, float* s_mem, const int64_t d16, const int klo)
+__device__ __forceinline__ void scan_split(const ScanArgs& a, float* s_mem, const int64_t d16, const int klo, const int split)
 {
+    if (split) {                                                 // one kind of row, two rows per channel
+        if (d16 >= a.D) {
+            if constexpr (split_exists<16, CHUNK>()) scan_rows<T, 16, CHUNK, true>(a, s_mem, 0, a.D, blockIdx.x, gridDim.x);
+        } else if (klo == 8) {
+            if constexpr (split_exists<8, CHUNK>()) scan_rows<T, 8, CHUNK, true>(a, s_mem, 0, a.D, blockIdx.x, gridDim.x);
+        } else {
+            if constexpr (split_exists<4, CHUNK>()) scan_rows<T, 4, CHUNK, true>(a, s_mem, 0, a.D, blockIdx.x, gridDim.x);
+        }
+        return;
+    }
     const int rows16 = rows_of<CHUNK>(16, a.rows_cap);
     const int64_t n16 = (d16 + rows16 - 1) / rows16;
     const int64_t nwg = gridDim.x;
@@ -944,7 +1020,7 @@ template <typename T, int CHUNK>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WAVES_K16))) void k_scan_mix(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
-    scan_split<T, CHUNK>(a, s_mem, a.d16, a.klo);
+    scan_split<T, CHUNK>(a, s_mem, a.d16, a.klo, 0);
 }
 
 // Per-sequence chunk read from device memory: every geometry in one kernel, selected per workgroup (register budget
@@ -962,9 +1038,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WA
     }
     const int64_t d16 = plan_d16(gridDim.y, a.D, chunk, a.rows_cap);
     const int klo = plan_klo(gridDim.y, a.D, chunk, d16);
+    const int split = plan_split(gridDim.y, a.D, a.N, chunk, d16, klo, a.allow_split);
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        scan_split<T, C>(a, s_mem, d16, klo);                                               \
+        scan_split<T, C>(a, s_mem, d16, klo, split);                                        \
         break;
     switch (chunk) {
         COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
@@ -985,33 +1062,34 @@ struct LaunchPlan {
 inline int a_np(int64_t N) { return (int)((N + kMaxGroup - 1) / kMaxGroup * kMaxGroup); }
 
 template <int K, int CHUNK>
-inline void geometry(int64_t nrows, int64_t N, int rows_cap, int64_t& gx, size_t& lds)
+inline void geometry(int64_t nrows, int64_t N, int rows_cap, int split, int64_t& gx, size_t& lds)
 {
     gx = 0;
     lds = 0;
     if constexpr (geometry_exists<K, CHUNK>()) {
-        int rows = Geo<K, CHUNK>::ROWS < rows_cap ? Geo<K, CHUNK>::ROWS : rows_cap;
+        const int full = Geo<K, CHUNK>::ROWS / (split ? 2 : 1);
+        int rows = full < rows_cap ? full : rows_cap;
         gx = (nrows + rows - 1) / rows;
-        lds = (size_t)lds_floats<K, CHUNK>(rows, a_np(N)) * sizeof(float);
+        lds = (size_t)lds_floats<K, CHUNK>(rows, a_np(N), split != 0) * sizeof(float);
     }
 }
 
 // Grid and LDS of a launch whose channels below d16 take 16 steps per lane and the others klo.
 template <int CHUNK>
-inline void split_geometry(const LaunchPlan& p, int rows_cap, int64_t d16, int klo, int64_t& gx, size_t& lds)
+inline void split_geometry(const LaunchPlan& p, int rows_cap, int64_t d16, int klo, int split, int64_t& gx, size_t& lds)
 {
     gx = 0;
     lds = 0;
     int64_t g = 0;
     size_t l = 0;
     if (d16 > 0) {
-        geometry<16, CHUNK>(d16, p.N, rows_cap, g, l);
+        geometry<16, CHUNK>(d16, p.N, rows_cap, split, g, l);
         gx += g;
         lds = l > lds ? l : lds;
     }
     if (d16 < p.D) {
-        if (klo == 8) geometry<8, CHUNK>(p.D - d16, p.N, rows_cap, g, l);
-        else geometry<4, CHUNK>(p.D - d16, p.N, rows_cap, g, l);
+        if (klo == 8) geometry<8, CHUNK>(p.D - d16, p.N, rows_cap, split, g, l);
+        else geometry<4, CHUNK>(p.D - d16, p.N, rows_cap, split, g, l);
         gx += g;
         lds = l > lds ? l : lds;
     }
@@ -1034,7 +1112,8 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
 #define COREY_GEO(C)                                                                        \
         {                                                                                   \
             const int64_t d16_c = plan_d16(p.B, p.D, C, a.rows_cap);                        \
-            split_geometry<C>(p, a.rows_cap, d16_c, plan_klo(p.B, p.D, C, d16_c), g, l);    \
+            const int klo_c = plan_klo(p.B, p.D, C, d16_c);                                 \
+            split_geometry<C>(p, a.rows_cap, d16_c, klo_c, plan_split(p.B, p.D, (int)p.N, C, d16_c, klo_c, a.allow_split), g, l);    \
         }                                                                                   \
         lds = l > lds ? l : lds;                                                            \
         if (C == p.chunk) gx = g;
@@ -1049,7 +1128,7 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
         k_scan<T, K, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a)
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        split_geometry<C>(p, a.rows_cap, a.d16, a.klo, gx, lds);                            \
+        split_geometry<C>(p, a.rows_cap, a.d16, a.klo, a.split, gx, lds);                   \
         if (a.d16 >= p.D) { COREY_LAUNCH(16, C); }                                          \
         else if constexpr (C <= 512) {                                                      \
             if (a.d16 > 0) k_scan_mix<T, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                 \

@@ -119,7 +119,7 @@ def test_gpu_entry_points_reject_bad_arguments_before_any_launch():
         kw.get("y", fake), kw.get("last", fake), kw.get("dt", 1), kw.get("B", 1), kw.get("D", 4), kw.get("N", 16),
         kw.get("L", 64), kw.get("flags", 0), kw.get("ws", fake), kw.get("wsb", 1 << 30), none)
     assert ss(u=none) == 2 and ss(y=none) == 2 and ss(last=none) == 2
-    assert ss(dt=3) == 1 and ss(flags=4) == 1 and ss(flags=0x80000001) == 1
+    assert ss(dt=3) == 1 and ss(flags=8) == 1 and ss(flags=0x80000001) == 1
     for bad in (0, 8, 100, 4096, -64):
         assert ss(chunk=bad) == 1
     assert ss(N=0) == 3 and ss(N=257) == 3 and ss(B=0) == 3 and ss(L=0) == 3 and ss(B=70000) == 3
@@ -166,6 +166,13 @@ def test_launch_plan_of_the_scan():
                     assert 0 <= d16 <= D and (d16 == D or d16 % 32 == 0), (B, D, N, chunk, d16)
                     steps = binding.selective_scan_fwd_plan_steps(B, D, N, chunk)
                     assert steps in (4, 8) and (steps == 8 or (d16 == 0 and chunk <= 256)), (B, D, N, chunk, d16, steps)
+    # launches of one geometry with at most 1536 waves give a channel two rows (tiles up to 1024 steps, N >= 4)
+    split = binding.selective_scan_fwd_plan_split
+    assert split(0, 64, 16, 256) == -1 and split(1, 64, 16, 100) == -1
+    assert split(1, 64, 16, 256) == 1 and split(1, 64, 16, 1024) == 1 and split(1, 64, 16, 2048) == 0 and split(1, 64, 3, 256) == 0
+    assert split(1, 1024, 16, 1024) == 1 and split(1, 1536, 16, 1024) == 1 and split(1, 1537, 16, 1024) == 0     # 64 lanes per row
+    assert split(1, 1536, 16, 512) == 1 and split(1, 5120, 16, 512) == 0 and split(1, 5120, 16, 128) == 0
+    assert split(1, 5120, 16, 64) == 1 and split(1, 5120, 16, 16) == 1 and split(4, 2048, 16, 32) == 1 and split(4, 2048, 16, 64) == 0
     # short of waves (few channels or short tiles, a 4-step row still inside one wave): 4 steps per lane
     steps = binding.selective_scan_fwd_plan_steps
     assert steps(0, 64, 16, 256) == -1 and steps(1, 64, 16, 100) == -1

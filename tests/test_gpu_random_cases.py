@@ -41,8 +41,9 @@ def test_random_combinations(seed):
         a_kind = "mamba" if rng.random() < 0.4 else "random"
         with_h0, use_z, softplus = bool(rng.random() < 0.5), bool(rng.random() < 0.7), bool(rng.random() < 0.8)
         routed, struct = bool(rng.random() < 0.4), bool(rng.random() < 0.5)
+        whole_rows = bool(rng.random() < 0.35)             # small launches split a channel's states over two rows unless told not to
         print(f"[case] seed {seed} #{case}: {cfg.dtype} B{B} D{D} N{N} L{L} chunk {chunk} seqlens {seqlens} A={a_kind} h0={with_h0} "
-              f"z={use_z} softplus={softplus} routed={routed} structured={struct}", flush=True)
+              f"z={use_z} softplus={softplus} routed={routed} structured={struct} whole_rows={whole_rows}", flush=True)
         w = wl.make(cfg, a_kind=a_kind, with_h0=with_h0)
         d, v = upload(w), w.val
         st, y_ref, s_ref = oracle.selective_scan(
@@ -57,7 +58,7 @@ def test_random_combinations(seed):
         y, last = corey.selective_scan_fwd(
             d["u"], d["delta"] if softplus else d["delta"].abs(), d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"] if use_z else None,
             delta_bias=d["delta_bias"] if softplus else None, delta_softplus=softplus, h0=d.get("h0") if with_h0 else None,
-            seqlens=d["seqlens"], chunk=host_chunk, chunks_dev=chunks_dev, general_a=not struct)
+            seqlens=d["seqlens"], chunk=host_chunk, chunks_dev=chunks_dev, general_a=not struct, whole_rows=whole_rows)
         torch.cuda.synchronize()
         _close(y_to_f64(y), y_ref, y_rtol(cfg), "y", store_bits(cfg))
         _close(last.cpu().numpy().astype(np.float64), s_ref, fp32_rtol(cfg.L), "state", False)

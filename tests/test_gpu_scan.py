@@ -22,11 +22,11 @@ def _say(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def _run(d, chunk, use_z=True, use_h0=True, chunks_dev=None, softplus=True, general_a=False):
+def _run(d, chunk, use_z=True, use_h0=True, chunks_dev=None, softplus=True, general_a=False, whole_rows=False):
     y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"] if use_z else None,
                                        delta_bias=d["delta_bias"], delta_softplus=softplus,
                                        h0=d.get("h0") if use_h0 else None, seqlens=d["seqlens"], chunk=chunk,
-                                       chunks_dev=chunks_dev, general_a=general_a)
+                                       chunks_dev=chunks_dev, general_a=general_a, whole_rows=whole_rows)
     torch.cuda.synchronize()
     return y_to_f64(y), last.cpu().numpy().astype(np.float64)
 
@@ -40,11 +40,15 @@ def _parity(cfg, chunks, a_kind="mamba", with_h0=False, use_z=True):
     # are measured on the general path)
     for general_a in ((False, True) if a_kind == "mamba" and cfg.dtype != wl.F32 else (False,)):
         for chunk in chunks:
-            _say(f"scan {cfg.name} B{cfg.B} D{cfg.D} N{cfg.N} L{cfg.L} {cfg.dtype} A={a_kind} chunk={chunk} z={use_z} h0={with_h0} "
-                 f"general_a={general_a}")
-            y, s = _run(d, chunk, use_z=use_z, general_a=general_a)
-            worst = max(worst, check_y(y, y_ref, cfg, f"y chunk {chunk} general_a={general_a}")[0])
-            assert_close(s, s_ref, fp32_rtol(cfg.L), f"last_state chunk {chunk} general_a={general_a}")
+            # a launch this small gives every channel two rows of lanes with half of the states each: the launch shape of
+            # large layers (one row per channel) is run on it as well
+            split = corey.selective_scan_fwd_plan_split(cfg.B, cfg.D, cfg.N, chunk) == 1
+            for whole_rows in ((False, True) if split else (False,)):
+                what = f"chunk {chunk} general_a={general_a} whole_rows={whole_rows}"
+                _say(f"scan {cfg.name} B{cfg.B} D{cfg.D} N{cfg.N} L{cfg.L} {cfg.dtype} A={a_kind} z={use_z} h0={with_h0} {what}")
+                y, s = _run(d, chunk, use_z=use_z, general_a=general_a, whole_rows=whole_rows)
+                worst = max(worst, check_y(y, y_ref, cfg, f"y {what}")[0])
+                assert_close(s, s_ref, fp32_rtol(cfg.L), f"last_state {what}")
     return worst
 
 
@@ -99,9 +103,9 @@ def test_padded_batches_and_empty_sequence():
         w = wl.make(cfg, with_h0=True)
         d = upload(w)
         y_ref, s_ref = oracle_scan(w)
-        for chunk in (64, 256, 2048):
-            _say(f"scan padded lens={lens} chunk={chunk}")
-            y, s = _run(d, chunk)
+        for chunk, whole_rows in ((64, False), (64, True), (256, False), (256, True), (2048, False)):
+            _say(f"scan padded lens={lens} chunk={chunk} whole_rows={whole_rows}")
+            y, s = _run(d, chunk, whole_rows=whole_rows)
             assert_close(y, y_ref, y_rtol(cfg), f"y lens {lens}", True)
             assert_close(s, s_ref, fp32_rtol(cfg.L), f"state lens {lens}")
             for b, n in enumerate(lens):
@@ -277,7 +281,7 @@ def test_structured_A_fast_path():
     ws = torch.empty(corey.selective_scan_fwd_workspace(cfg.B, cfg.N, cfg.L), dtype=torch.uint8, device="cuda")
     y, last = torch.empty_like(d["u"]), torch.empty((cfg.B, cfg.D, cfg.N), dtype=torch.float32, device="cuda")
     st = lib.selective_scan_fwd(ptr(d["u"]), ptr(d["delta"]), ptr(d["A"]), ptr(d["B"]), ptr(d["C"]), None, None, None, 1, None, None, 256,
-                                None, ptr(y), ptr(last), 0, cfg.B, cfg.D, cfg.N, cfg.L, 4, ptr(ws), ws.numel(), None)
+                                None, ptr(y), ptr(last), 0, cfg.B, cfg.D, cfg.N, cfg.L, 8, ptr(ws), ws.numel(), None)
     assert st == 1
 
 
@@ -444,7 +448,7 @@ def test_full_size_sampled_rows(name):
         worst[:] = max(worst[0], a), max(worst[1], b), max(worst[2], c)
 
     for general_a in (True, False):
-        for c in sorted({chunk, 64, 2048}):
+        for c in sorted({chunk, 64, 512, 1024, 2048}):      # (small layers: two rows per channel up to 1024, one beyond)
             _say(f"scan full size {name} chunk={c} (routed={chunk}) general_a={general_a}")
             y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"],
                                                delta_bias=d["delta_bias"], seqlens=d["seqlens"], chunk=c, general_a=general_a)
