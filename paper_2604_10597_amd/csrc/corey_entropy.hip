@@ -508,13 +508,13 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
     for (int i = threadIdx.x; i < cs * copies; i += kThreads) s_bins[i] = 0u;
     __syncthreads();
     uint32_t* mine = s_bins + (threadIdx.x % copies) * cs;
-    const bool flat = hi == lo;                               // degenerate range: everything in bin 0
-    const float scale = flat ? 0.f : (float)((double)K / ((double)hi - (double)lo));
-    const int top = K - 1;
+    const float scale = hi == lo ? 0.f : (float)((double)K / ((double)hi - (double)lo));     // degenerate range: everything in bin 0
+    const uint32_t top = (uint32_t)K - 1u;
     auto bin = [&](float v) {
         const float q = __fmul_rn(__fsub_rn(v, lo), scale);    // two separate binary32 roundings
-        int k = (int)q;                                        // truncation; q >= 0
-        k = flat ? 0 : (k > top ? top : k);
+        // truncation; q >= 0 (a degenerate range has scale 0: bin 0).  The conversion to unsigned saturates, so a value
+        // outside a stale range still lands inside the counters.
+        const uint32_t k = min(__float2uint_rz(q), top);
         atomicAdd(&mine[k], 1u);
     };
     auto fold = [&](const word4& q) {
@@ -531,19 +531,24 @@ __global__ __launch_bounds__(kThreads) void k_entropy_count_flat(const word4* __
             }
         }
     };
-    while (have) {                                            // the next turn's words are requested before this turn's are counted
-        const int64_t next = base + step;
-        const bool have_next = next + kThreads * kUnroll <= nwords;
-        if (have_next) {
+    while (have) {                                            // the next turn's words are requested before this turn's are counted;
+        base += step;                                         // two turns per iteration, so the two sets of registers swap roles
+        have = base + kThreads * kUnroll <= nwords;           // without being copied
+        if (have) {
 #pragma unroll
-            for (int k = 0; k < kUnroll; ++k) qn[k] = x[map(next + k * kThreads + threadIdx.x)];
+            for (int k = 0; k < kUnroll; ++k) qn[k] = x[map(base + k * kThreads + threadIdx.x)];
         }
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) fold(q[k]);
+        if (!have) break;
+        base += step;
+        have = base + kThreads * kUnroll <= nwords;
+        if (have) {
 #pragma unroll
-        for (int k = 0; k < kUnroll; ++k) q[k] = qn[k];
-        base = next;
-        have = have_next;
+            for (int k = 0; k < kUnroll; ++k) q[k] = x[map(base + k * kThreads + threadIdx.x)];
+        }
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) fold(qn[k]);
     }
     for (int64_t i = base + threadIdx.x; i < nwords; i += kThreads) fold(x[map(i)]);     // ragged end: at most one workgroup
     __syncthreads();
