@@ -963,7 +963,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(waves_ta
 }
 
 // Workgroup `wg` of `nwg` takes its share of one sequence's channels: those below d16 with 16 steps per lane (the first
-// g16 workgroups), the others with 8.  With a grid sized for exactly this split every workgroup has one row group;
+// g16 workgroups), the others with 8.  With a grid sized for exactly these two kinds every workgroup has one row group;
 // any other grid is still correct (row groups are taken grid-stride within each kind).
 template <int K, int CHUNK> constexpr bool geometry_exists()
 {
@@ -978,7 +978,7 @@ template <int CHUNK> __host__ __device__ inline int rows_of(int K, int rows_cap,
 }
 
 template <typename T, int CHUNK>
-__device__ __forceinline__ void scan_split(const ScanArgs& a, float* s_mem, const int64_t d16, const int klo, const int split)
+__device__ __forceinline__ void scan_by_kind(const ScanArgs& a, float* s_mem, const int64_t d16, const int klo, const int split)
 {
     if (split) {                                                 // one kind of row, two rows per channel
         if (d16 >= a.D) {
@@ -1020,7 +1020,7 @@ template <typename T, int CHUNK>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WAVES_K16))) void k_scan_mix(const ScanArgs a)
 {
     extern __shared__ float s_mem[];
-    scan_split<T, CHUNK>(a, s_mem, a.d16, a.klo, 0);
+    scan_by_kind<T, CHUNK>(a, s_mem, a.d16, a.klo, 0);
 }
 
 // Per-sequence chunk read from device memory: every geometry in one kernel, selected per workgroup (register budget
@@ -1041,7 +1041,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(COREY_WA
     const int split = plan_split(gridDim.y, a.D, a.N, chunk, d16, klo, a.allow_split);
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        scan_split<T, C>(a, s_mem, d16, klo, split);                                        \
+        scan_by_kind<T, C>(a, s_mem, d16, klo, split);                                      \
         break;
     switch (chunk) {
         COREY_CASE(16) COREY_CASE(32) COREY_CASE(64) COREY_CASE(128) COREY_CASE(256) COREY_CASE(512) COREY_CASE(1024)
@@ -1076,7 +1076,7 @@ inline void geometry(int64_t nrows, int64_t N, int rows_cap, int split, int64_t&
 
 // Grid and LDS of a launch whose channels below d16 take 16 steps per lane and the others klo.
 template <int CHUNK>
-inline void split_geometry(const LaunchPlan& p, int rows_cap, int64_t d16, int klo, int split, int64_t& gx, size_t& lds)
+inline void launch_geometry(const LaunchPlan& p, int rows_cap, int64_t d16, int klo, int split, int64_t& gx, size_t& lds)
 {
     gx = 0;
     lds = 0;
@@ -1113,13 +1113,13 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
         {                                                                                   \
             const int64_t d16_c = plan_d16(p.B, p.D, C, a.rows_cap);                        \
             const int klo_c = plan_klo(p.B, p.D, C, d16_c);                                 \
-            split_geometry<C>(p, a.rows_cap, d16_c, klo_c, plan_split(p.B, p.D, (int)p.N, C, d16_c, klo_c, a.allow_split), g, l);    \
+            launch_geometry<C>(p, a.rows_cap, d16_c, klo_c, plan_split(p.B, p.D, (int)p.N, C, d16_c, klo_c, a.allow_split), g, l);    \
         }                                                                                   \
         lds = l > lds ? l : lds;                                                            \
         if (C == p.chunk) gx = g;
         COREY_GEO(16) COREY_GEO(32) COREY_GEO(64) COREY_GEO(128) COREY_GEO(256) COREY_GEO(512) COREY_GEO(1024) COREY_GEO(2048)
 #undef COREY_GEO
-        if (gx < 2) gx = 2;     // a split decided on the device needs a workgroup for each kind (a surplus one leaves at once)
+        if (gx < 2) gx = 2;     // two kinds of rows decided on the device need a workgroup for each kind (a surplus one leaves at once)
         k_scan_any<T><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);
         return;
     }
@@ -1128,7 +1128,7 @@ inline void launch_scan(const ScanArgs& a, const LaunchPlan& p)
         k_scan<T, K, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a)
 #define COREY_CASE(C)                                                                       \
     case C:                                                                                 \
-        split_geometry<C>(p, a.rows_cap, a.d16, a.klo, a.split, gx, lds);                   \
+        launch_geometry<C>(p, a.rows_cap, a.d16, a.klo, a.split, gx, lds);                   \
         if (a.d16 >= p.D) { COREY_LAUNCH(16, C); }                                          \
         else if constexpr (C <= 512) {                                                      \
             if (a.d16 > 0) k_scan_mix<T, C><<<dim3((unsigned)gx, (unsigned)p.B), dim3(kBlock), lds, p.stream>>>(a);                 \
