@@ -5,6 +5,8 @@ fp32 storage at the stated configuration (growing with sqrt(L/256) for longer se
 and 3e-3 for bf16 storage with fp32 state, plus the bf16 store's own half ulp; the fp32 state is held to the fp32
 bound for both storage types.
 """
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -382,6 +384,50 @@ def test_short_tiles_and_few_channels(D, chunk, L):
         assert torch.isfinite(y.float()).all()
         outs.append((y, last))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+@pytest.mark.parametrize("B,D,N,L,chunk,steps", [(1, 1024, 16, 4096, 1024, 16), (1, 1536, 16, 2048, 512, 8), (2, 300, 64, 1500, 256, 4),
+                                                  (1, 5120, 16, 700, 64, 4), (3, 257, 24, 333, 16, 4), (1, 1537, 16, 2048, 1024, 16)])
+def test_two_rows_per_channel_against_whole_rows(B, D, N, L, chunk, steps):
+    """Launches short of waves give a channel two rows of lanes with half of the states each.  Per (channel, state) both
+    launch shapes do the same arithmetic in the same order, so on the general path the final state is the same bit for bit;
+    y adds the two halves' sums in another order and is held to the oracle (sampled channels) and to the other shape."""
+    expect = 0 if D == 1537 else 1                        # 1537 channels of 64 lanes: one wave more than the rule's 1536
+    assert corey.selective_scan_fwd_plan_split(B, D, N, chunk) == expect
+    d16 = corey.selective_scan_fwd_plan(B, D, N, chunk)
+    assert (16 if d16 == D else corey.selective_scan_fwd_plan_steps(B, D, N, chunk)) == steps and d16 in (0, D)
+    lens = None if B == 1 else tuple(L - 37 * b for b in range(B))
+    cfg = dataclasses.replace(wl.scaled(wl.CONFIGS["c2_mamba370m"], B=B, D=D, N=N, L=L), seqlens=lens)
+    _say(f"two rows per channel B{B} D{D} N{N} L{L} chunk {chunk} ({steps} steps per lane) split={expect}")
+    w = wl.make(cfg, a_kind="random", with_h0=True)
+    d = upload(w)
+    rows = np.unique(np.concatenate([[0, 1, D // 2, D - 2, D - 1], np.random.default_rng(D).integers(0, D, 8)]))
+    y_ref, s_ref = oracle_scan(w, rows=rows)
+    idx = torch.from_numpy(rows).cuda()
+    outs = {}
+    for whole_rows in (False, True):
+        for routed in (False, True):
+            cd = torch.full((B,), chunk, dtype=torch.int32, device="cuda") if routed else None
+            y, last = corey.selective_scan_fwd(d["u"], d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
+                                               h0=d["h0"], seqlens=d["seqlens"], chunk=2048 if routed else chunk, chunks_dev=cd,
+                                               general_a=True, whole_rows=whole_rows)
+            torch.cuda.synchronize()
+            check_y(y_to_f64(y[:, idx, :]), y_ref, cfg, f"y whole_rows={whole_rows} routed={routed}")
+            assert_close(last.cpu().numpy()[:, rows, :], s_ref, fp32_rtol(cfg.L), f"state whole_rows={whole_rows} routed={routed}")
+            outs[(whole_rows, routed)] = (y, last)
+        # the chunk read from device memory picks the same launch shape as the host's
+        assert torch.equal(outs[(whole_rows, False)][0], outs[(whole_rows, True)][0])
+        assert torch.equal(outs[(whole_rows, False)][1], outs[(whole_rows, True)][1])
+    assert torch.equal(outs[(False, False)][1], outs[(True, False)][1])            # the state, bit for bit
+    ya, yb = y_to_f64(outs[(False, False)][0]), y_to_f64(outs[(True, False)][0])
+    if expect:
+        if ya.size >= 2_000_000:                          # (enough values for a sum in another order to cross a 16-bit rounding)
+            assert not np.array_equal(ya, yb)             # the two shapes really are different code
+    else:
+        assert np.array_equal(ya, yb)                     # no split planned: the flag changes nothing
+    scale = np.sqrt((yb ** 2).mean(-1, keepdims=True)) + np.abs(yb)
+    store = {wl.BF16: 2.0 ** -8, wl.F16: 2.0 ** -11, wl.F32: 0.0}[cfg.dtype]
+    assert np.all(np.abs(ya - yb) <= 4e-6 * scale + 2 * store * np.abs(yb))
 
 
 @pytest.mark.parametrize("chunk", [128, 512, 2048])
