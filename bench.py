@@ -15,6 +15,8 @@ memory (no host round trip inside a step).  Prints ONE JSON line.
   producer   the causal convolution + SiLU that writes u and its range, and the statistic with and without that range
              (two sweeps, one sweep, one sweep over every 8th block), each also as a percentage of the scan
   decode     one generated token (selective_state_update), eager calls and replayed from a HIP graph
+  paper_shape  the scan on the paper's kernel-benchmark shape (a small layer) per chunk, with two rows of lanes per channel where
+             the launch plan gives them and with one row per channel (COREY_SCAN_WHOLE_ROWS)
   graph_replay  the same step replayed from a HIP graph (no faster than the eager launches here: the step is GPU-bound)
   overhead   entropy + routing cost relative to the scan alone at the routed chunk, for the exact statistic (the
              timed step) and for the sampled one (every 8th block of 512 values, the paper's stride-8 variant at
@@ -508,25 +510,30 @@ def main() -> int:
         p_ent = corey.corey_entropy_hist(pd["u"], pc.K)
         p_chunk = corey.corey_select_chunk(p_ent["r"].item(), pc.L, pol)
 
-        def p_scan(c):
+        def p_scan(c, whole_rows=False):
             corey.selective_scan_fwd(pd["u"], pd["delta"], pd["A"], pd["B"], pd["C"], Dv=pd["D"], z=pd["z"],
-                                     delta_bias=pd["delta_bias"], chunk=c, y=p_y, last_state=p_last, workspace=p_ws, general_a=True)
+                                     delta_bias=pd["delta_bias"], chunk=c, y=p_y, last_state=p_last, workspace=p_ws, general_a=True,
+                                     whole_rows=whole_rows)
 
-        def p_time(c):
+        def p_time(c, whole_rows=False):
             for _ in range(5):
-                p_scan(c)
+                p_scan(c, whole_rows)
             a0, b0 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             a0.record()
             for _ in range(30):
-                p_scan(c)
+                p_scan(c, whole_rows)
             b0.record()
             torch.cuda.synchronize()
             return a0.elapsed_time(b0) / 30
 
         paper_shape = {"workload": "B1 D1024 N16 L4096 fp16 (the paper's kernel-level benchmark shape), 5 warm-up + 30 timed",
                        "r": round(p_ent["r"].item(), 4), "routed_chunk": p_chunk,
-                       "scan_ms": {str(c): round(p_time(c), 4) for c in (64, 256, 512, 2048)},
+                       "scan_ms": {str(c): round(p_time(c), 4) for c in (64, 256, 512, 1024, 2048)},
+                       "scan_ms_one_row_per_channel": {str(c): round(p_time(c, True), 4) for c in (64, 256, 512, 1024)},
+                       "two_rows_per_channel": {str(c): bool(corey.selective_scan_fwd_plan_split(pc.B, pc.D, pc.N, c)) for c in (64, 256, 512, 1024, 2048)},
+                       "note": "a launch this small gives every channel two rows of lanes with half of the states each (up to chunk "
+                               "1024); scan_ms_one_row_per_channel is the same launch under COREY_SCAN_WHOLE_ROWS",
                        "scan_bytes": wl.scan_bytes(pc)}
         del pd, pw, p_ws, p_y
 
