@@ -150,8 +150,9 @@ def select_chunk(r, L, pol: Policy | None = None):
 
 
 def selective_scan(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_softplus=True,
-                   h0=None, seqlens=None, chunk=256, threads=1):
-    """All inputs float arrays (widened).  Returns (status, y float64 [B,D,L], last float64 [B,D,N])."""
+                   h0=None, seqlens=None, chunk=256, threads=1, want_terms=False):
+    """All inputs float arrays (widened).  Returns (status, y float64 [B,D,L], last float64 [B,D,N]); with `want_terms`
+    also the sum of the absolute values of the terms each y is made of (for a checker's rounding bound)."""
     u = np.asarray(u)
     B, D, L = u.shape
     A = np.asarray(A)
@@ -168,12 +169,15 @@ def selective_scan(u, delta, A, Bm, Cm, Dv=None, z=None, delta_bias=None, delta_
     sk, sp = _i32(seqlens)
     y = np.zeros((B, D, L), dtype=np.float64)
     last = np.zeros((B, D, N), dtype=np.float64)
+    terms = np.zeros((B, D, L), dtype=np.float64) if want_terms else None
     st = lib().oracle_selective_scan(
         ptrs[0], ptrs[1], ptrs[2], ptrs[3], ptrs[4], ptrs[5], ptrs[6], ptrs[7],
         ctypes.c_int(1 if delta_softplus else 0), hp, sp, ctypes.c_int64(chunk),
         ctypes.c_int64(B), ctypes.c_int64(D), ctypes.c_int64(N), ctypes.c_int64(L),
         y.ctypes.data_as(ctypes.c_void_p), last.ctypes.data_as(ctypes.c_void_p),
-        ctypes.c_int(threads))
+        ctypes.c_int(threads), terms.ctypes.data_as(ctypes.c_void_p) if want_terms else None)
+    if want_terms:
+        return st, y, last, terms
     return st, y, last
 
 

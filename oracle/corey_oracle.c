@@ -269,12 +269,15 @@ int oracle_select_chunk(double r, int64_t L, const oracle_policy* p, int32_t* ch
  *               depend on it.
  * y             double[B][D][L] out;  last_state double[B][D][N] out.
  * threads       OpenMP threads over the independent (b, d) rows (<= 1: sequential).
+ * y_terms       double[B][D][L] out or NULL: the sum of the ABSOLUTE values of the terms y is made of,
+ *               (sum_n |C h| + |D u|) |gate|.  Not part of the method: a checker that compares a single-precision y
+ *               with this one needs the size of the terms to bound the rounding of a sum that cancels.
  * ---------------------------------------------------------------------------------------------- */
 int oracle_selective_scan(const float* u, const float* delta, const float* A, const float* Bm,
                           const float* Cm, const float* Dv, const float* z, const float* dbias,
                           int delta_softplus, const float* h0, const int32_t* seqlens, int64_t chunk,
                           int64_t B, int64_t D, int64_t N, int64_t L,
-                          double* y, double* last_state, int threads)
+                          double* y, double* last_state, int threads, double* y_terms)
 {
     if (!u || !delta || !A || !Bm || !Cm || !y || !last_state) return ORACLE_EINVAL;
     if (B < 1 || D < 1 || N < 1 || N > 1024 || L < 1 || chunk < 1) return ORACLE_EINVAL;
@@ -299,12 +302,13 @@ int oracle_selective_scan(const float* u, const float* delta, const float* A, co
                 if (delta_softplus)
                     dl = (dl > 0.0 ? dl : 0.0) + log1p(exp(-fabs(dl)));   /* log(1 + e^dl) */
                 const double uu = (double)u[row * L + t];
-                double acc = 0.0;
+                double acc = 0.0, mag = 0.0;
                 for (int64_t n = 0; n < N; ++n) {
                     const double abar = exp(dl * (double)A[d * N + n]);
                     const double bbar_u = dl * (double)Bm[(b * N + n) * L + t] * uu;
                     h[n] = abar * h[n] + bbar_u;
                     acc += (double)Cm[(b * N + n) * L + t] * h[n];
+                    mag += fabs((double)Cm[(b * N + n) * L + t] * h[n]);
                 }
                 double yv = acc + (Dv ? (double)Dv[d] * uu : 0.0);
                 if (z) {
@@ -312,9 +316,16 @@ int oracle_selective_scan(const float* u, const float* delta, const float* A, co
                     yv *= zz / (1.0 + exp(-zz));
                 }
                 y[row * L + t] = yv;
+                if (y_terms) {
+                    mag += Dv ? fabs((double)Dv[d] * uu) : 0.0;
+                    if (z) mag *= fabs((double)z[row * L + t] / (1.0 + exp(-(double)z[row * L + t])));
+                    y_terms[row * L + t] = mag;
+                }
             }
         }
         for (int64_t t = len; t < L; ++t) y[row * L + t] = 0.0;
+        if (y_terms)
+            for (int64_t t = len; t < L; ++t) y_terms[row * L + t] = 0.0;
         for (int64_t n = 0; n < N; ++n) last_state[row * N + n] = h[n];
     }
     return ORACLE_OK;

@@ -186,6 +186,34 @@ def test_gate_and_padding():
     assert np.array_equal(stt[0], sl[1])
 
 
+def test_size_of_the_terms_for_a_checkers_rounding_bound():
+    """The optional extra output: the sum of the absolute values of the terms every y is made of.  With every term
+    positive it is y itself; in general it bounds |y|, equals the unrolled sum of |C h| + |D u| times |gate|, is zero on
+    padding, and asking for it changes neither y nor the state."""
+    rng = np.random.default_rng(21)
+    p = _problem(rng, 2, 3, 4, 29)
+    kw = dict(Dv=p["Dv"], delta_bias=p["delta_bias"], delta_softplus=True)
+    lens = np.array([29, 11], dtype=np.int32)
+    st, y, s, terms = oracle.selective_scan(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], z=p["z"], seqlens=lens, want_terms=True, **kw)
+    _, y_b, s_b = oracle.selective_scan(p["u"], p["delta"], p["A"], p["Bm"], p["Cm"], z=p["z"], seqlens=lens, **kw)
+    assert st == oracle.OK and np.array_equal(y, y_b) and np.array_equal(s, s_b)
+    assert (terms >= np.abs(y) * (1 - 1e-14)).all() and not terms[1, :, 11:].any() and (terms[0] > 0).all()
+    # every operand positive, no gate: no cancellation anywhere
+    pos = {k: np.abs(v) for k, v in p.items()}
+    _, y_p, _, t_p = oracle.selective_scan(pos["u"], p["delta"], p["A"], pos["Bm"], pos["Cm"], Dv=pos["Dv"], delta_bias=p["delta_bias"],
+                                           want_terms=True)
+    np.testing.assert_allclose(t_p, y_p, rtol=1e-14)
+    # written out for one element: states by the recurrence in numpy, then the absolute read-out
+    b, d, t_end = 0, 1, 7
+    dl = np.logaddexp(0.0, p["delta"][b, d, :t_end + 1].astype(np.float64) + float(p["delta_bias"][d]))
+    h = np.zeros(4)
+    for t in range(t_end + 1):
+        h = np.exp(dl[t] * p["A"][d].astype(np.float64)) * h + dl[t] * p["Bm"][b, :, t].astype(np.float64) * float(p["u"][b, d, t])
+    zz = float(p["z"][b, d, t_end])
+    want = (np.abs(p["Cm"][b, :, t_end].astype(np.float64) * h).sum() + abs(float(p["Dv"][d]) * float(p["u"][b, d, t_end]))) * abs(zz * expit(zz))
+    assert terms[b, d, t_end] == pytest.approx(want, rel=1e-12)
+
+
 def test_argument_errors():
     rng = np.random.default_rng(10)
     p = _problem(rng, 1, 2, 2, 8)
