@@ -1,7 +1,8 @@
 """GPU parity on seeded random combinations of everything the scan and the statistic accept: shapes from one value to a
 few thousand per axis, every chunk, padded batches (including empty sequences), initial state, gate, softplus on and
 off, both decay paths, host and device chunk, whole-tensor / per-sequence / sampled statistics.  Each case is checked
-against the oracle element by element."""
+against the oracle element by element.  Also: the producer of u with every form of the statistic behind it, and the
+routed scan with the reduction deferred, separate, and launched from the host's chunk."""
 import dataclasses
 
 import numpy as np
@@ -71,3 +72,116 @@ def test_random_combinations(seed):
         ref = oracle.entropy_hist(v["u"], K, seqlens=w.seqlens, stride=stride, block=block)
         torch.cuda.synchronize()
         assert np.array_equal(got["counts"].cpu().numpy().view(np.uint32).reshape(ref["counts"].shape), ref["counts"]), (K, stride, block)
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_random_producer_and_every_statistic(seed):
+    """Random shapes, tap counts and storage types through the producer of u, then every form of the statistic on that u
+    (two sweeps, the producer's range, sampled on that range, the built-in scratch, one sweep over the bit-pattern table, the
+    table filled by the producer) against the oracle's histogram of the same bits: counts bit for bit, H, the routed chunk."""
+    import math
+
+    import test_gpu_conv as tc
+    import test_gpu_table as tt
+    from gpu_util import counts_u32, to_dev
+    tws = tt._ws()
+    rng = np.random.default_rng(seed)
+    for case in range(12):
+        dtype = [wl.BF16, wl.F16, wl.F32][int(rng.integers(3))]
+        B, D = int(rng.choice([1, 1, 2, 3])), int(rng.choice([1, 3, 17, 64, 200, 700]))
+        L = int(rng.choice([1, 5, 64, 333, 1024, 2049, 4104, 8192, 20000]))
+        if B * D * L > 6e6:
+            D = max(1, int(6e6 / (B * L)))
+        W, K = int(rng.integers(1, 5)), int(rng.choice([2, 16, 256, 1000, 4096]))
+        with_state, bias = bool(rng.random() < 0.5), bool(rng.random() < 0.8)
+        stride, block = int(rng.choice([2, 8, 5])), int(rng.choice([8, 64, 512, 4096, 24, 1]))
+        print(f"[case] seed {seed} #{case}: {dtype} B{B} D{D} L{L} W{W} K{K} state={with_state} bias={bias} stride={stride} "
+              f"block={block}", flush=True)
+        cfg = wl.Config(name="rnd", B=B, D=D, N=16, L=L, dtype=dtype, K=K, chunks=(64,), seed=int(rng.integers(1 << 30)))
+        u, parts, xd, wd, bd = tc._run(cfg, W, with_state=with_state, bias=bias)      # the producer against the oracle
+        uv = u.float().cpu().numpy()
+        ref = oracle.entropy_hist(uv, K)
+        ref_s = oracle.entropy_hist(uv, K, stride=stride, block=block, range_all=True)
+        pol = corey.policy_default()
+        given = corey.corey_route_device(u, K, pol, range_parts=parts)
+        two = corey.corey_route_device(u, K, pol)
+        sampled = corey.corey_route_device(u, K, pol, range_parts=parts, stride=stride, block=block)
+        static = corey.corey_entropy_hist(u, K)
+        static["counts"].zero_()
+        corey.corey_entropy_hist_static(u, K, static)
+        again = corey.corey_route_device(u, K, pol, range_parts=parts)     # the hand-over buffer came back cleared
+        torch.cuda.synchronize()
+        for what, out, r in (("given range", given, ref), ("two sweeps", two, ref), ("sampled", sampled, ref_s),
+                             ("static", static, ref), ("given range again", again, ref)):
+            assert np.array_equal(counts_u32(out["counts"]).reshape(-1), r["counts"].reshape(-1)), what
+            if not math.isnan(r["H"][0]):
+                assert out["H"].item() == pytest.approx(r["H"][0], rel=1e-12, abs=1e-14), what
+                st, c_ref, margin = oracle.select_chunk(float(r["r"][0]), L, oracle.policy())
+                assert "chunks" not in out or margin < 1e-9 or out["chunks"].item() == c_ref, what
+        if dtype == wl.F32:
+            continue
+        one = corey.corey_entropy_hist_onesweep(u, K, policy=pol, table_ws=tws)
+        torch.cuda.synchronize()
+        tt._compare(one, ref, K)
+        conv = wl.make_conv(cfg, W, with_state=with_state)
+        u2 = torch.empty_like(u)
+        corey.causal_conv1d_silu_fwd(xd, wd, bd, to_dev(conv["dev"]["state_in"], dtype), u=u2, range_parts=parts, pattern_table=tws)
+        from_table = corey.corey_entropy_hist_from_table(tws, u.dtype, L, K, policy=pol)
+        torch.cuda.synchronize()
+        if L > 16:                                                     # (shorter rows take the single-step kernel without a table)
+            assert torch.equal(u2.view(torch.int16), u.view(torch.int16))
+        tt._compare(from_table, oracle.entropy_hist(u2.float().cpu().numpy(), K), K)
+
+
+@pytest.mark.parametrize("seed", [31, 32, 33])
+def test_random_routing_deferred_separate_and_host_chunk(seed):
+    """Random layers, policies, statistics and launch options: the statistic's reduction and the rule inside the scan's
+    first kernel against the separate reduction, and against the scan launched with the routed chunk from the host, every
+    output bit for bit, twice in a row on the same buffers."""
+    from gpu_util import to_dev
+    rng = np.random.default_rng(seed)
+    for case in range(10):
+        dtype = [wl.BF16, wl.F16, wl.F32][int(rng.integers(3))]
+        B, D = int(rng.choice([1, 1, 2, 3])), int(rng.choice([1, 8, 33, 100, 300, 1200]))
+        L, N = int(rng.choice([1, 16, 100, 512, 1024, 1500, 2048, 4100])), int(rng.choice([1, 4, 16, 16, 24, 64]))
+        if B * D * L * N > 4e7:
+            D = max(1, int(4e7 / (B * L * N)))
+        K, mode = int(rng.choice([2, 16, 256, 1000])), int(rng.choice([0, 0, 2, 4]))
+        per_seq = bool(rng.random() < 0.3) and B > 1
+        use_conv = (not per_seq) and bool(rng.random() < 0.5)
+        kw = dict(stride=8, block=int(rng.choice([8, 64, 512]))) if rng.random() < 0.5 else {}
+        general_a, whole_rows = bool(rng.random() < 0.5), bool(rng.random() < 0.3)
+        lens = tuple(int(rng.integers(0, L + 1)) for _ in range(B)) if per_seq else None
+        print(f"[case] seed {seed} #{case}: {dtype} B{B} D{D} N{N} L{L} K{K} mode {mode} lens {lens} conv={use_conv} {kw} "
+              f"general_a={general_a} whole_rows={whole_rows}", flush=True)
+        cfg = dataclasses.replace(wl.scaled(wl.CONFIGS["c2_mamba370m"], B=B, D=D, N=N, L=L, dtype=dtype), seqlens=lens,
+                                  seed=int(rng.integers(1 << 30)))
+        w = wl.make(cfg, a_kind="mamba" if rng.random() < 0.5 else "random")
+        d = upload(w)
+        pol = corey.policy_default()
+        pol.mode = 1 if per_seq and mode == 0 else mode
+        u, parts = d["u"], None
+        if use_conv:
+            conv = wl.make_conv(cfg, 4)
+            u, _, parts = corey.causal_conv1d_silu_fwd(to_dev(conv["dev"]["x"], dtype), torch.from_numpy(conv["dev"]["weight"]).cuda(),
+                                                       torch.from_numpy(conv["dev"]["bias"]).cuda())
+        stat_lens = d["seqlens"] if per_seq else None
+        hint = int(rng.choice([64, 512, 2048]))
+        scan = lambda **more: corey.selective_scan_fwd(u, d["delta"], d["A"], d["B"], d["C"], Dv=d["D"], z=d["z"], delta_bias=d["delta_bias"],
+                                                       seqlens=d["seqlens"], general_a=general_a, whole_rows=whole_rows, **more)
+        for rep in range(2):
+            a = corey.corey_route_device(u, K, pol, seqlens=stat_lens, range_parts=parts, **kw)
+            ya, sa = scan(chunk=hint, chunks_dev=a["chunks"])
+            b = corey.corey_route_device_deferred(u, K, pol, seqlens=stat_lens, range_parts=parts, **kw)
+            yb, sb = scan(chunk=hint, route=b["route"])
+            torch.cuda.synchronize()
+            for k in ("counts", "chunks", "range"):
+                assert torch.equal(a[k], b[k]), (k, rep)
+            for k in ("H", "r"):
+                assert torch.equal(a[k].view(torch.int64), b[k].view(torch.int64)), (k, rep)
+            assert torch.equal(ya.view(torch.uint8), yb.view(torch.uint8)) and torch.equal(sa, sb), rep
+            chunks = a["chunks"].cpu().tolist()
+            if len(set(chunks)) == 1:
+                yc, sc = scan(chunk=chunks[0])
+                torch.cuda.synchronize()
+                assert torch.equal(ya.view(torch.uint8), yc.view(torch.uint8)) and torch.equal(sa, sc), "host chunk"
