@@ -324,7 +324,9 @@ __device__ __forceinline__ float softplus(float x)
     const float e = fast_exp2(-fabsf(x) * kLog2e);
     const float w = 1.f + e;
     const float fix = e - (w - 1.f);
-    return fmaxf(x, 0.f) + fmaf(__builtin_amdgcn_logf(w), kLn2, fix);
+    float pos;                                             // max(x, 0) in one instruction: fmaxf would first quiet a signalling
+    asm("v_max_f32_e32 %0, 0, %1" : "=v"(pos) : "v"(x));   // NaN with a second one, which x (a sum) cannot be
+    return pos + fmaf(__builtin_amdgcn_logf(w), kLn2, fix);
 }
 
 // z * sigmoid(z)
