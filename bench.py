@@ -53,11 +53,11 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CUs x 2.4 GHz x 256 flop/clk)
 # HBM bytes per scan launch measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`, scaled by what the same counters
 # read for a 256 MiB device copy (profiles/hot_path_c4_mamba2p8b_counters.txt); not re-measured by this script
-MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 749_700_000}
+MEASURED_TRAFFIC_BYTES = {"c4_mamba2p8b": 749_400_000}
 TRAFFIC_FROM = "profiles/hot_path_c4_mamba2p8b_counters.txt"
 # vector instructions per wave-level state update of the scan at the routed chunk, from SQ_INSTS_VALU and
 # SQ_INSTS_VALU_TRANS_F32 of the same counter summary
-COUNTED_INSTRUCTIONS = {"c4_mamba2p8b": {"plain": 7.48, "trans": 1.325, "from": "profiles/hot_path_c4_mamba2p8b_counters.txt"}}
+COUNTED_INSTRUCTIONS = {"c4_mamba2p8b": {"plain": 7.42, "trans": 1.325, "from": "profiles/hot_path_c4_mamba2p8b_counters.txt"}}
 
 
 def cpu_model() -> str:
