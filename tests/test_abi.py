@@ -24,6 +24,19 @@ def test_library_exports_every_declared_symbol():
     assert binding.corey_version() == "0.1"
 
 
+def test_binding_constants_are_the_headers():
+    """The numbers the Python binding carries (it cannot include the header) against include/corey.h."""
+    hdr = open(os.path.join(ROOT, "include", "corey.h")).read()
+    defs = dict(re.findall(r"^#define\s+(COREY_\w+)\s+(.+?)\s*(?:/\*.*)?$", hdr, flags=re.M))
+    val = lambda name: eval(re.sub(r"(\d)u\b", r"\1", re.sub(r"COREY_\w+", lambda m: "(" + defs[m.group(0)] + ")", defs[name])))
+    assert binding.HANDOFF_BYTES == val("COREY_HANDOFF_BYTES") and binding.CHUNK_SLOTS == val("COREY_CHUNK_SLOTS")
+    assert binding.COREY_SCAN_GENERAL_A == val("COREY_SCAN_GENERAL_A") and binding.COREY_SCAN_ONE_CHUNK == val("COREY_SCAN_ONE_CHUNK")
+    assert binding.COREY_SCAN_WHOLE_ROWS == val("COREY_SCAN_WHOLE_ROWS")
+    enum = re.search(r"typedef enum \{([^}]*)\} corey_dtype;", hdr).group(1)
+    codes = {k: int(v) for k, v in re.findall(r"(COREY_(?:F32|BF16|F16))\s*=\s*(\d+)", enum)}
+    assert (binding.COREY_F32, binding.COREY_BF16, binding.COREY_F16) == (codes["COREY_F32"], codes["COREY_BF16"], codes["COREY_F16"])
+
+
 def _href(tok):
     return math.log(int(tok.split(":")[1])) if tok.startswith("logK:") else float(tok)
 
